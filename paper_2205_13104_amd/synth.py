@@ -1,0 +1,120 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+This module holds NO arithmetic of the method: it only draws checkpoints and gradients.
+It serves the tests (oracle side and HIP side alike) and the benchmark.  Tensors are
+produced with torch's seeded generators on the requested device (CPU or the GPU); the
+side that did not generate them receives a copy, so both sides always see identical bits.
+
+The paper averages checkpoints of one training trajectory (one per epoch, n = 60..100,
+Sec. 5.1) or of several fine-tuning runs from one pre-trained model (Sec. 5.3) and notes
+that such weights are almost collinear (pairwise cosine ~0.99, Sec. 5.4.4).  The recipes
+below reproduce the SHAPES (D = parameter count, n = number of checkpoints) and that
+correlation structure; none of the paper's data sets or trained weights is involved.
+
+Layout: a D x n matrix is a tensor of shape (n, ld), ld >= D, row j = checkpoint j,
+elements [D, ld) of every row are zero padding.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+
+def padded_ld(D: int, mult: int = 128) -> int:
+    return (D + mult - 1) // mult * mult
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    D: int
+    n: int
+    kind: str            # "trajectory" | "finetune"
+    decay: float = 0.97  # per-checkpoint decay of the step noise (trajectory)
+    drift: float = 0.3   # weight of the shared drift direction (trajectory)
+    sigma_g: float = 1e-2
+    lr: float = 0.1
+    steps: int = 1000
+    k: int = 1
+
+
+# The five benchmark configurations (shapes: ResNet-18 / ResNet-50 / ViT-B/16 parameter counts).
+WORKLOADS = {
+    "tiny": Workload("tiny", 1_000_000, 10, "trajectory", decay=0.9, drift=0.5, sigma_g=1e-2, steps=100),
+    "cifar_resnet18": Workload("cifar_resnet18", 11_173_962, 100, "trajectory", sigma_g=1e-2),
+    "imagenet_resnet50": Workload("imagenet_resnet50", 25_557_032, 100, "trajectory", sigma_g=5e-3),
+    "vit_b16_finetune": Workload("vit_b16_finetune", 86_567_656, 20, "finetune", sigma_g=1e-2, k=8),
+    "large": Workload("large", 350_000_000, 128, "trajectory", sigma_g=1e-2, steps=200),
+}
+
+
+def _gen(seed: int, device) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    return g
+
+
+def trajectory(D: int, n: int, decay: float, drift: float, seed: int = 0, device="cpu",
+               ld: Optional[int] = None, out: Optional[torch.Tensor] = None,
+               w0_std: float = 0.05, step_std: float = 1e-3) -> torch.Tensor:
+    """Checkpoints of a synthetic training trajectory, fp32, shape (n, ld).
+
+    w_0 ~ N(0, w0_std^2);  c ~ N(0, step_std^2) is one fixed drift direction;
+    w_i = w_{i-1} + drift * c + N(0, (step_std * decay^i)^2),  i = 1 .. n-1.
+    Row i of the result is w_i.  The rows are nearly collinear (ill-conditioned)."""
+    ld = padded_ld(D) if ld is None else ld
+    gen = _gen(seed, device)
+    W = torch.zeros((n, ld), dtype=torch.float32, device=device) if out is None else out
+    assert W.shape == (n, ld) and W.dtype == torch.float32
+    if out is not None:
+        W[:, D:].zero_()
+    W[0, :D] = torch.randn(D, generator=gen, device=device, dtype=torch.float32) * w0_std
+    c = torch.randn(D, generator=gen, device=device, dtype=torch.float32) * step_std
+    for i in range(1, n):
+        noise = torch.randn(D, generator=gen, device=device, dtype=torch.float32)
+        noise *= step_std * (decay ** i)
+        noise.add_(c, alpha=drift)
+        torch.add(W[i - 1, :D], noise, out=W[i, :D])
+    return W
+
+
+def finetune_offsets(D: int, n: int, seed: int = 0, device="cpu", ld: Optional[int] = None,
+                     base_std: float = 0.02, offset_std: float = 2e-3,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Checkpoints fine-tuned from one base model: w_i = w_base + N(0, offset_std^2)."""
+    ld = padded_ld(D) if ld is None else ld
+    gen = _gen(seed, device)
+    W = torch.zeros((n, ld), dtype=torch.float32, device=device) if out is None else out
+    assert W.shape == (n, ld) and W.dtype == torch.float32
+    if out is not None:
+        W[:, D:].zero_()
+    base = torch.randn(D, generator=gen, device=device, dtype=torch.float32) * base_std
+    for i in range(n):
+        off = torch.randn(D, generator=gen, device=device, dtype=torch.float32) * offset_std
+        torch.add(base, off, out=W[i, :D])
+    return W
+
+
+def checkpoints(wl: Workload, seed: int = 0, device="cpu", D: Optional[int] = None,
+                n: Optional[int] = None, ld: Optional[int] = None) -> torch.Tensor:
+    """Checkpoints of workload `wl`, optionally at a reduced D / n (same recipe)."""
+    D = wl.D if D is None else D
+    n = wl.n if n is None else n
+    if wl.kind == "trajectory":
+        return trajectory(D, n, wl.decay, wl.drift, seed=seed, device=device, ld=ld)
+    return finetune_offsets(D, n, seed=seed, device=device, ld=ld)
+
+
+def gradient(D: int, sigma: float, seed: int, step: int = 0, device="cpu", k: int = 1,
+             ldg: Optional[int] = None) -> torch.Tensor:
+    """k synthetic gradients ~ N(0, sigma^2), fp32, shape (D,) for k == 1 else (k, ldg)."""
+    gen = _gen(seed * 1_000_003 + 7919 * (step + 1), device)
+    if k == 1 and ldg is None:
+        return torch.randn(D, generator=gen, device=device, dtype=torch.float32) * sigma
+    ldg = D if ldg is None else ldg
+    G = torch.zeros((k, ldg), dtype=torch.float32, device=device)
+    for c in range(k):
+        G[c, :D] = torch.randn(D, generator=gen, device=device, dtype=torch.float32) * sigma
+    return G
