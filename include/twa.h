@@ -1,0 +1,174 @@
+/*
+ * twa.h -- C ABI of the MI355X (gfx950) library for the projected-gradient step of
+ * Trainable Weight Averaging (arXiv 2205.13104).
+ *
+ * The paper trains the n coefficients of a weighted average of n checkpoints
+ * w_1..w_n in R^D by ordinary gradient descent restricted to U = span{w_i} (Sec. 3):
+ * with P = [e_1 .. e_n] a basis of U (Sec. 4.1) each iteration computes
+ *     s  = P^T g                      (Sec. 4.2, gradient w.r.t. the coefficients)
+ *     g~ = P s ,  w <- w - eta g~     (Sec. 4.2, weight-space form of the update, lambda = 0)
+ * and P may be kept as low-bit integer codes plus scaling factors (Sec. 4.6).
+ * This library provides exactly those operations, plus the one-time construction of an
+ * orthonormal P from the checkpoints (the orthogonalisation variant of Sec. 4.1).
+ *
+ * Conventions common to every entry point
+ *   - Plain C types only.  Every pointer is a DEVICE pointer unless its name ends in
+ *     _host.  The caller owns every buffer; the library never frees or keeps them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on it and return without synchronising, except where stated.
+ *   - Matrices are "basis major": vector j (0-based) of a D x n matrix is the contiguous
+ *     run x[j*ld .. j*ld + D), ld >= D.  Elements [D, ld) of each run are padding.
+ *   - Return value: TWA_OK (0) or a negative twa_status.  Argument errors are detected on
+ *     the host before anything is enqueued (no GPU needed to get them).
+ *   - Device base pointers must be 16-byte aligned and `ld` a multiple of 128 elements.
+ *   - Limits: 1 <= n <= TWA_MAX_N, 1 <= k <= TWA_MAX_K, 1 <= D, and D * (bytes per stored
+ *     element) < 2^32 for one vector (D <= 1.07e9 for fp32).
+ */
+#ifndef TWA_H_
+#define TWA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TWA_MAX_N 128
+#define TWA_MAX_K 8
+#define TWA_LD_MULTIPLE 128
+
+typedef enum twa_status {
+  TWA_OK = 0,
+  TWA_ERR_NULL = -1,      /* a required pointer is NULL                                        */
+  TWA_ERR_SHAPE = -2,     /* D, n, k, ld or block out of range                                 */
+  TWA_ERR_ALIGN = -3,     /* pointer not 16-byte aligned, or ld not a multiple of 128 / block  */
+  TWA_ERR_DTYPE = -4,     /* unknown storage type, or one the call does not accept             */
+  TWA_ERR_WORKSPACE = -5, /* workspace missing or smaller than the query reports               */
+  TWA_ERR_RANK = -6,      /* checkpoints numerically linearly dependent (build_basis)          */
+  TWA_ERR_HIP = -7,       /* a HIP runtime call failed; see twa_last_hip_error()               */
+  TWA_ERR_NO_DEVICE = -8  /* no usable gfx950 device                                           */
+} twa_status;
+
+/* Storage type of a projection matrix. */
+typedef enum twa_dtype {
+  TWA_F32 = 0,  /* IEEE binary32 values                                                        */
+  TWA_BF16 = 1, /* bfloat16 values (binary32 rounded to nearest even to 16 bits)               */
+  TWA_I8 = 2,   /* int8 codes q in [-127,127] + one binary32 scale per block: value = scale*q  */
+  TWA_I4 = 3    /* 4-bit codes q in [-7,7], two per byte (element i in the LOW nibble when i is
+                   even), stored offset-binary as q+8; one binary16 scale h per block:
+                   value = (float(h) * gscale) * q                                             */
+} twa_dtype;
+
+/*
+ * Descriptor of a stored projection matrix P (Sec. 4.2: P = [e_1 .. e_n]; Sec. 4.6 for the
+ * integer forms).  Filled by the caller; passed by pointer; never retained.
+ *   data   : n runs of `ld` elements (F32: 4 B, BF16: 2 B, I8: 1 B, I4: 1/2 B per element).
+ *   scales : I8: float[n][ld/block];  I4: binary16 bits, uint16_t[n][ld/block];  else NULL.
+ *            Block b of vector j covers elements [b*block, min((b+1)*block, D)) of THAT
+ *            vector.  The paper keeps one scale pair per layer (Sec. 4.6); the per-block
+ *            grouping here is the finer-grained form used by the benchmark configuration.
+ *   block  : power of two in {32, 64, 128, 256} (I8, I4); ignored for F32/BF16.
+ *   gscale : I4 only: a power of two multiplying every binary16 scale so that the scales of
+ *            a matrix with tiny entries (|p| ~ D^-1/2) stay normal binary16 numbers.
+ */
+typedef struct twa_pmat {
+  int32_t dtype;   /* twa_dtype */
+  int32_t n;
+  int64_t D;
+  int64_t ld;
+  void* data;
+  void* scales;
+  int32_t block;
+  float gscale;
+} twa_pmat;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int twa_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char* twa_strerror(int status);
+
+/* hipError_t value of the most recent failing HIP call made by this library in the calling
+ * thread (0 if none). */
+int twa_last_hip_error(void);
+
+/*
+ * Sizes of the buffers that hold an n-vector matrix of logical length D in storage `dtype`.
+ * Writes the smallest admissible ld, and the byte sizes of `data` and `scales` for that ld
+ * (scale_bytes = 0 for F32/BF16).  Matches the paper's memory table (Sec. 4.6): 4nD bytes at
+ * 32 bits, nBD/8 bytes of codes at B bits.  Pure host arithmetic.
+ */
+int twa_pmat_bytes(int32_t dtype, int64_t D, int32_t n, int32_t block, int64_t* ld,
+                   size_t* data_bytes, size_t* scale_bytes);
+
+/* Workspace (device bytes) needed by twa_project for n vectors and k gradients. */
+int twa_project_workspace_bytes(int32_t n, int32_t k, size_t* bytes);
+
+/* Workspace (device bytes) needed by twa_build_basis for n checkpoints. */
+int twa_build_basis_workspace_bytes(int32_t n, size_t* bytes);
+
+/*
+ * Orthonormal basis of span{w_1..w_n}  (Sec. 3, solution set U; Sec. 4.1, construction by
+ * orthogonalising the checkpoints in their given order).
+ *   W  [in]  n checkpoints, fp32, basis major with stride ldw.
+ *   P  [out] n orthonormal vectors, fp32, stride ldp; W = P R with R upper triangular and
+ *            diag(R) > 0, so p_1 = w_1/||w_1|| and span(P) = span(W).  P may alias W (then
+ *            ldp == ldw): the checkpoints are overwritten in place.  Padding is zeroed.
+ *   R_host [out, HOST, optional] n*n doubles, row major, R[a*n + b] (zero below diagonal).
+ *   ws, ws_bytes  device workspace of at least twa_build_basis_workspace_bytes(n).
+ * Method: CholeskyQR2 -- twice { Gram matrix accumulated in fp64 on the matrix cores,
+ * Cholesky factor in fp64 on the host, P <- P R^-1 in fp32 }.  SYNCHRONISES `stream` twice
+ * (the n x n Gram matrix travels to the host).  On TWA_ERR_RANK (a Cholesky pivot <=
+ * 1e-12 * largest diagonal entry) R_host[0], if given, holds the 0-based index of the
+ * offending checkpoint and P is unspecified.
+ */
+int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P, int64_t ldp,
+                    double* R_host, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Store an fp32 matrix in the form described by `out`  (Sec. 4.6: P as B-bit integers plus
+ * scaling factors).  `out->dtype, n, D, ld, data, scales, block` are preset by the caller;
+ * buffers sized per twa_pmat_bytes.  Exact recipe (each step ONE correctly rounded binary32
+ * operation, so the result is unique bit for bit), per block of one vector:
+ *     amax  = max |p_i| over the block's elements with i < D
+ *     scale = amax / qmax                         qmax = 127 (I8), 7 (I4)
+ *     I8: stored scale = effective scale e = scale
+ *     I4: stored h = binary16(scale / gscale) (round to nearest even), e = float(h) * gscale
+ *     e == 0 -> all codes of the block are 0;   inv = 1 / e
+ *     q_i   = clamp(round_half_to_even(p_i * inv), -qmax, qmax)
+ *   Padding elements [D, ld) get code 0, blocks wholly in the padding get scale 0.
+ *   BF16: round to nearest even; F32: copy.  Padding is zeroed.
+ * I4 and out->gscale == 0: the library first finds the largest block scale, sets
+ *   out->gscale = 2^(floor(log2(max scale)) - 14) (1 if P == 0) and SYNCHRONISES `stream`
+ *   once to do so; with out->gscale > 0 (a power of two) nothing synchronises.
+ */
+int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* out, void* stream);
+
+/*
+ * s = P^T g for k gradients  (Sec. 4.2: the gradient w.r.t. the coefficients is the model
+ * gradient projected on the basis).
+ *   g  [in]  k gradients, fp32, gradient c at g[c*ldg .. c*ldg + D)  (ldg ignored if k == 1;
+ *            otherwise a multiple of 4 and >= D).
+ *   s  [out] k*n floats, s[c*n + j] = sum_i value(P)_ij * g_c[i].
+ *   ws, ws_bytes  device workspace of at least twa_project_workspace_bytes(n, k).
+ * fp32 arithmetic; the reduction order is fixed, so repeated calls give identical bits.
+ */
+int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float* s, void* ws,
+                size_t ws_bytes, void* stream);
+
+/*
+ * g~ = P s ; w <- w - lr * g~   (Sec. 4.2, weight-space form of the update rule, lambda = 0;
+ * Alg. 1 "update weights").  The caller may put any n coefficients in `s` (for instance
+ * P^T g after momentum or Adam, as the paper applies a base optimiser to the coefficients).
+ *   s  [in]     n floats (device).
+ *   w  [in/out] D floats, updated in place.
+ *   g_tilde [out, optional] D floats receiving g~ (NULL: not stored).
+ */
+int twa_expand_update(const twa_pmat* P, const float* s, float* w, float lr, float* g_tilde,
+                      void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TWA_H_ */

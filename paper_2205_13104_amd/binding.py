@@ -1,0 +1,221 @@
+"""Thin ctypes binding of ``libtwa.so`` (the C ABI declared in ``include/twa.h``).
+
+Argument marshalling only: torch tensors provide device memory and the current stream, every
+step of the path runs in the library's HIP kernels.  There is no fallback: if the library has
+not been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtwa.so")
+
+F32, BF16, I8, I4 = 0, 1, 2, 3
+MAX_N, MAX_K, LD_MULTIPLE = 128, 8, 128
+DEFAULT_BLOCK = {I8: 128, I4: 64}
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_WORKSPACE, ERR_RANK, ERR_HIP, ERR_NO_DEVICE = range(-1, -9, -1)
+
+
+class TwaError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        self.code = code
+        msg = f"{where}: {strerror(code)} (status {code})"
+        if code == ERR_HIP:
+            msg += f", hipError {lib().twa_last_hip_error()}"
+        super().__init__(msg + (f" {detail}" if detail else ""))
+
+
+class _Pmat(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("n", C.c_int32), ("D", C.c_int64), ("ld", C.c_int64),
+                ("data", C.c_void_p), ("scales", C.c_void_p), ("block", C.c_int32), ("gscale", C.c_float)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2205_13104_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        L.twa_version.restype = C.c_int
+        L.twa_strerror.restype = C.c_char_p
+        L.twa_strerror.argtypes = [C.c_int]
+        L.twa_last_hip_error.restype = C.c_int
+        L.twa_pmat_bytes.argtypes = [i32, i64, i32, i32, C.POINTER(i64), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.twa_project_workspace_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
+        L.twa_build_basis_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
+        L.twa_build_basis.argtypes = [vp, i64, i32, i64, vp, i64, vp, vp, C.c_size_t, vp]
+        L.twa_quantize.argtypes = [vp, i64, i32, i64, C.POINTER(_Pmat), vp]
+        L.twa_project.argtypes = [C.POINTER(_Pmat), vp, i32, i64, vp, vp, C.c_size_t, vp]
+        L.twa_expand_update.argtypes = [C.POINTER(_Pmat), vp, vp, f32, vp, vp]
+        for f in (L.twa_pmat_bytes, L.twa_project_workspace_bytes, L.twa_build_basis_workspace_bytes,
+                  L.twa_build_basis, L.twa_quantize, L.twa_project, L.twa_expand_update):
+            f.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().twa_strerror(int(code)).decode()
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise TwaError(rc, where)
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def pmat_bytes(dtype: int, D: int, n: int, block: int = 0):
+    """(ld, data_bytes, scale_bytes) of the smallest admissible buffers."""
+    ld, db, sb = C.c_int64(), C.c_size_t(), C.c_size_t()
+    _check(lib().twa_pmat_bytes(dtype, D, n, block or DEFAULT_BLOCK.get(dtype, 0), C.byref(ld), C.byref(db),
+                                C.byref(sb)), "twa_pmat_bytes")
+    return int(ld.value), int(db.value), int(sb.value)
+
+
+def project_workspace_bytes(n: int, k: int = 1) -> int:
+    b = C.c_size_t()
+    _check(lib().twa_project_workspace_bytes(n, k, C.byref(b)), "twa_project_workspace_bytes")
+    return int(b.value)
+
+
+def build_basis_workspace_bytes(n: int) -> int:
+    b = C.c_size_t()
+    _check(lib().twa_build_basis_workspace_bytes(n, C.byref(b)), "twa_build_basis_workspace_bytes")
+    return int(b.value)
+
+
+_TORCH_OF = {F32: torch.float32, BF16: torch.bfloat16, I8: torch.int8, I4: torch.uint8}
+
+
+@dataclass
+class Pmat:
+    """A projection matrix stored on the device: the tensors plus the C descriptor."""
+    dtype: int
+    D: int
+    n: int
+    ld: int
+    data: torch.Tensor                      # (n, ld) values/codes; I4: (n, ld // 2) bytes
+    scales: Optional[torch.Tensor] = None   # (n, ld // block): float32 (I8) / float16 (I4)
+    block: int = 0
+    gscale: float = 1.0
+
+    def c_struct(self) -> _Pmat:
+        return _Pmat(self.dtype, self.n, self.D, self.ld, _ptr(self.data), _ptr(self.scales), self.block,
+                     float(self.gscale))
+
+    @property
+    def stream_bytes(self) -> int:
+        """Bytes of P one pass over the matrix has to move (codes/values of the D logical elements + scales)."""
+        bits = {F32: 32, BF16: 16, I8: 8, I4: 4}[self.dtype]
+        b = self.n * self.D * bits // 8
+        if self.scales is not None:
+            b += self.n * ((self.D + self.block - 1) // self.block) * self.scales.element_size()
+        return b
+
+
+def wrap_f32(P: torch.Tensor, D: Optional[int] = None) -> Pmat:
+    """Describe an existing (n, ld) float32 device tensor as an F32 projection matrix."""
+    assert P.dtype == torch.float32 and P.dim() == 2 and P.is_contiguous()
+    return Pmat(F32, P.shape[1] if D is None else D, P.shape[0], P.shape[1], P)
+
+
+def alloc_pmat(dtype: int, D: int, n: int, block: int = 0, device="cuda") -> Pmat:
+    block = block or DEFAULT_BLOCK.get(dtype, 0)
+    ld, _, _ = pmat_bytes(dtype, D, n, block)
+    cols = ld // 2 if dtype == I4 else ld
+    data = torch.empty((n, cols), dtype=_TORCH_OF[dtype], device=device)
+    scales = None
+    if dtype in (I8, I4):
+        scales = torch.empty((n, ld // block), dtype=torch.float32 if dtype == I8 else torch.float16, device=device)
+    return Pmat(dtype, D, n, ld, data, scales, block if dtype in (I8, I4) else 0, 0.0 if dtype == I4 else 1.0)
+
+
+def quantize(P: torch.Tensor, D: int, dtype: int, block: int = 0, gscale: float = 0.0,
+             out: Optional[Pmat] = None) -> Pmat:
+    """twa_quantize: store the fp32 matrix P ((n, ldp) device tensor) as `dtype`."""
+    assert P.dtype == torch.float32 and P.dim() == 2 and P.is_contiguous()
+    n, ldp = P.shape
+    if out is None:
+        out = alloc_pmat(dtype, D, n, block, device=P.device)
+    if dtype == I4:
+        out.gscale = float(gscale)
+    st = out.c_struct()
+    _check(lib().twa_quantize(_ptr(P), D, n, ldp, C.byref(st), _stream()), "twa_quantize")
+    out.gscale = float(st.gscale)
+    return out
+
+
+class Workspace:
+    """Device scratch of a fixed size, owned by the caller of the library."""
+
+    def __init__(self, nbytes: int, device="cuda"):
+        self.nbytes = int(nbytes)
+        self.buf = torch.empty(max(self.nbytes, 16), dtype=torch.uint8, device=device)
+
+    @property
+    def ptr(self) -> int:
+        return int(self.buf.data_ptr())
+
+
+def project(P: Pmat, g: torch.Tensor, s: Optional[torch.Tensor] = None, ws: Optional[Workspace] = None) -> torch.Tensor:
+    """twa_project: s = P^T g.  g: (D,) or (k, ldg) float32 on the device.  Returns s: (n,) or (k, n)."""
+    assert g.dtype == torch.float32 and g.is_contiguous()
+    if g.dim() == 1:
+        k, ldg = 1, 0
+    else:
+        k, ldg = int(g.shape[0]), int(g.shape[1])
+    if s is None:
+        s = torch.empty((P.n,) if g.dim() == 1 else (k, P.n), dtype=torch.float32, device=g.device)
+    if ws is None:
+        ws = Workspace(project_workspace_bytes(P.n, k), device=g.device)
+    st = P.c_struct()
+    _check(lib().twa_project(C.byref(st), _ptr(g), k, ldg, _ptr(s), ws.ptr, ws.nbytes, _stream()), "twa_project")
+    return s
+
+
+def expand_update(P: Pmat, s: torch.Tensor, w: torch.Tensor, lr: float, g_tilde: Optional[torch.Tensor] = None) -> None:
+    """twa_expand_update: g~ = P s; w -= lr * g~ (in place); g~ stored if a tensor is given."""
+    assert s.dtype == torch.float32 and w.dtype == torch.float32 and w.is_contiguous() and s.is_contiguous()
+    st = P.c_struct()
+    _check(lib().twa_expand_update(C.byref(st), _ptr(s), _ptr(w), float(lr), _ptr(g_tilde), _stream()),
+           "twa_expand_update")
+
+
+def build_basis(W: torch.Tensor, D: int, out: Optional[torch.Tensor] = None, want_R: bool = True,
+                ws: Optional[Workspace] = None):
+    """twa_build_basis: orthonormal P with W = P R.  W: (n, ldw) float32 device tensor.
+
+    out=None allocates P; out=W orthonormalises in place.  Returns (P tensor, R as an (n, n) float64 CPU tensor
+    or None)."""
+    assert W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous()
+    n, ldw = W.shape
+    P = torch.empty_like(W) if out is None else out
+    R = torch.zeros((n, n), dtype=torch.float64) if want_R else None
+    if ws is None:
+        ws = Workspace(build_basis_workspace_bytes(n), device=W.device)
+    rc = lib().twa_build_basis(_ptr(W), D, n, ldw, _ptr(P), int(P.shape[1]), _ptr(R), ws.ptr, ws.nbytes, _stream())
+    if rc == ERR_RANK and R is not None:
+        raise TwaError(rc, "twa_build_basis", f"(checkpoint {int(R[0, 0].item())})")
+    _check(rc, "twa_build_basis")
+    return P, R

@@ -1,0 +1,362 @@
+// C-ABI entry points (include/twa.h): argument validation on the host, dispatch to the gfx950
+// kernels, and the small fp64 host algebra of CholeskyQR2 (n <= 128).
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "twa_device.h"
+#include "twa_host.h"
+
+namespace twa {
+
+static thread_local int g_last_hip_error = 0;
+
+int hip_check(hipError_t e) {
+  if (e == hipSuccess) return TWA_OK;
+  g_last_hip_error = (int)e;
+  return (e == hipErrorNoDevice || e == hipErrorInvalidDevice) ? TWA_ERR_NO_DEVICE : TWA_ERR_HIP;
+}
+
+int device_cus() {
+  static std::mutex mu;
+  static int cus[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+  std::lock_guard<std::mutex> lk(mu);
+  if (cus[dev] == 0) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return -1;
+    cus[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : -1;
+  }
+  return cus[dev];
+}
+
+int env_int(const char* name, int fallback) {
+  const char* v = getenv(name);
+  if (!v || !*v) return fallback;
+  char* end = nullptr;
+  long x = strtol(v, &end, 10);
+  return (end && *end == 0 && x > 0 && x < (1 << 20)) ? (int)x : fallback;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+static int bits_of(int dtype) {
+  switch (dtype) {
+    case TWA_F32: return 32;
+    case TWA_BF16: return 16;
+    case TWA_I8: return 8;
+    case TWA_I4: return 4;
+    default: return 0;
+  }
+}
+static bool scaled(int dtype) { return dtype == TWA_I8 || dtype == TWA_I4; }
+
+static int check_dims(int64_t D, int32_t n, int64_t ld, int bits) {
+  if (D <= 0 || n <= 0 || n > TWA_MAX_N || ld < D) return TWA_ERR_SHAPE;
+  if ((D * (int64_t)bits + 7) / 8 >= ((int64_t)1 << 32)) return TWA_ERR_SHAPE;
+  if (D * 4 >= ((int64_t)1 << 32)) return TWA_ERR_SHAPE;          // g and w are fp32 vectors of length D
+  if (ld % TWA_LD_MULTIPLE != 0) return TWA_ERR_ALIGN;
+  return TWA_OK;
+}
+
+// Validate a descriptor and turn it into the kernel-side view.
+static int view_of(const twa_pmat* P, PView* v) {
+  if (!P) return TWA_ERR_NULL;
+  const int bits = bits_of(P->dtype);
+  if (bits == 0) return TWA_ERR_DTYPE;
+  if (!P->data) return TWA_ERR_NULL;
+  int rc = check_dims(P->D, P->n, P->ld, bits);
+  if (rc != TWA_OK) return rc;
+  if (!aligned16(P->data)) return TWA_ERR_ALIGN;
+  int shift = 0;
+  float gscale = 1.0f;
+  if (scaled(P->dtype)) {
+    if (!P->scales) return TWA_ERR_NULL;
+    if (!aligned16(P->scales)) return TWA_ERR_ALIGN;
+    if (!pow2(P->block) || P->block < 32 || P->block > 256) return TWA_ERR_SHAPE;
+    if (P->ld % P->block != 0) return TWA_ERR_ALIGN;
+    while ((1 << shift) < P->block) ++shift;
+    if (P->dtype == TWA_I4) {
+      int ex = 0;
+      if (!(P->gscale > 0.0f) || !isfinite(P->gscale) || frexpf(P->gscale, &ex) != 0.5f) return TWA_ERR_SHAPE;
+      gscale = P->gscale;
+    }
+  }
+  v->data = static_cast<const uint8_t*>(P->data);
+  v->scales = static_cast<const uint8_t*>(P->scales);
+  v->D = P->D;
+  v->ld = P->ld;
+  v->n = P->n;
+  v->block_shift = shift;
+  v->gscale = gscale;
+  return TWA_OK;
+}
+
+static int persistent_grid(const char* env_name, int default_wgs_per_cu, int64_t max_useful) {
+  const int cus = device_cus();
+  if (cus <= 0) return -1;
+  int64_t g = (int64_t)cus * env_int(env_name, default_wgs_per_cu);
+  if (g > kMaxGrid) g = kMaxGrid;
+  if (g > max_useful) g = max_useful;
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+// ---- fp64 host algebra for CholeskyQR2 (row-major n x n) --------------------------------------
+
+// G = R^T R with R upper triangular, diag > 0.  Returns -1 or the index of the first pivot that
+// is <= tol * (largest diagonal entry of G).
+static int cholesky_upper(const std::vector<double>& G, int n, double tol, std::vector<double>& R) {
+  R.assign((size_t)n * n, 0.0);
+  double dmax = 0.0;
+  for (int i = 0; i < n; ++i) dmax = fmax(dmax, G[(size_t)i * n + i]);
+  for (int j = 0; j < n; ++j) {
+    double d = G[(size_t)j * n + j];
+    for (int k = 0; k < j; ++k) d -= R[(size_t)k * n + j] * R[(size_t)k * n + j];
+    if (!(d > tol * dmax)) return j;
+    const double rjj = sqrt(d);
+    R[(size_t)j * n + j] = rjj;
+    for (int i = j + 1; i < n; ++i) {
+      double v = G[(size_t)j * n + i];
+      for (int k = 0; k < j; ++k) v -= R[(size_t)k * n + j] * R[(size_t)k * n + i];
+      R[(size_t)j * n + i] = v / rjj;
+    }
+  }
+  return -1;
+}
+
+// X = R^-1 (upper triangular) by back substitution, column by column.
+static void invert_upper(const std::vector<double>& R, int n, std::vector<double>& X) {
+  X.assign((size_t)n * n, 0.0);
+  for (int j = 0; j < n; ++j) {
+    X[(size_t)j * n + j] = 1.0 / R[(size_t)j * n + j];
+    for (int i = j - 1; i >= 0; --i) {
+      double v = 0.0;
+      for (int k = i + 1; k <= j; ++k) v += R[(size_t)i * n + k] * X[(size_t)k * n + j];
+      X[(size_t)i * n + j] = -v / R[(size_t)i * n + i];
+    }
+  }
+}
+
+}  // namespace twa
+
+using namespace twa;
+
+extern "C" {
+
+int twa_version(void) { return 100; }
+
+const char* twa_strerror(int status) {
+  switch (status) {
+    case TWA_OK: return "success";
+    case TWA_ERR_NULL: return "a required pointer is NULL";
+    case TWA_ERR_SHAPE: return "D, n, k, ld, block or gscale out of range";
+    case TWA_ERR_ALIGN: return "pointer not 16-byte aligned, or ld not a multiple of 128 / of the block";
+    case TWA_ERR_DTYPE: return "unknown or unsupported storage type";
+    case TWA_ERR_WORKSPACE: return "workspace missing or too small";
+    case TWA_ERR_RANK: return "checkpoints are numerically linearly dependent";
+    case TWA_ERR_HIP: return "a HIP runtime call failed";
+    case TWA_ERR_NO_DEVICE: return "no usable GPU device";
+    default: return "unknown status";
+  }
+}
+
+int twa_last_hip_error(void) { return g_last_hip_error; }
+
+int twa_pmat_bytes(int32_t dtype, int64_t D, int32_t n, int32_t block, int64_t* ld, size_t* data_bytes,
+                   size_t* scale_bytes) {
+  if (!ld || !data_bytes || !scale_bytes) return TWA_ERR_NULL;
+  const int bits = bits_of(dtype);
+  if (bits == 0) return TWA_ERR_DTYPE;
+  if (D <= 0 || n <= 0 || n > TWA_MAX_N) return TWA_ERR_SHAPE;
+  if (scaled(dtype) && (!pow2(block) || block < 32 || block > 256)) return TWA_ERR_SHAPE;
+  const int64_t l = (D + TWA_LD_MULTIPLE - 1) / TWA_LD_MULTIPLE * TWA_LD_MULTIPLE;
+  int rc = check_dims(D, n, l, bits);
+  if (rc != TWA_OK) return rc;
+  *ld = l;
+  *data_bytes = (size_t)n * (size_t)l * (size_t)bits / 8;
+  *scale_bytes = scaled(dtype) ? (size_t)n * (size_t)(l / block) * (dtype == TWA_I8 ? 4 : 2) : 0;
+  return TWA_OK;
+}
+
+int twa_project_workspace_bytes(int32_t n, int32_t k, size_t* bytes) {
+  if (!bytes) return TWA_ERR_NULL;
+  if (n <= 0 || n > TWA_MAX_N || k <= 0 || k > TWA_MAX_K) return TWA_ERR_SHAPE;
+  *bytes = (size_t)kMaxGrid * (size_t)n * (size_t)k * sizeof(float);
+  return TWA_OK;
+}
+
+static constexpr int kGramMaxGrid = 512;
+
+int twa_build_basis_workspace_bytes(int32_t n, size_t* bytes) {
+  if (!bytes) return TWA_ERR_NULL;
+  if (n <= 0 || n > TWA_MAX_N) return TWA_ERR_SHAPE;
+  const size_t NP = (size_t)(n + 15) / 16 * 16;
+  // per-workgroup partial Gram matrices + the reduced Gram matrix + R^-1 in fp32
+  *bytes = (size_t)kGramMaxGrid * NP * NP * sizeof(double) + NP * NP * sizeof(double) + NP * NP * sizeof(float);
+  return TWA_OK;
+}
+
+int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float* s, void* ws, size_t ws_bytes,
+                void* stream) {
+  PView v;
+  int rc = view_of(P, &v);
+  if (rc != TWA_OK) return rc;
+  if (!g || !s) return TWA_ERR_NULL;
+  if (k <= 0 || k > TWA_MAX_K) return TWA_ERR_SHAPE;
+  if (k > 1 && (ldg < v.D || (ldg & 3) != 0)) return TWA_ERR_SHAPE;
+  if (!aligned16(g) || (reinterpret_cast<uintptr_t>(s) & 3u)) return TWA_ERR_ALIGN;
+  size_t need = 0;
+  twa_project_workspace_bytes(v.n, k, &need);
+  if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
+  if (!aligned16(ws)) return TWA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t ntiles = (v.D + project_tile_elems(P->dtype) - 1) / project_tile_elems(P->dtype);
+  const int grid = persistent_grid("TWA_PROJECT_WGS_PER_CU", 3, ntiles);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  float* partial = static_cast<float*>(ws);
+  if (k == 1) return launch_project(v, P->dtype, g, s, partial, grid, st);
+  return launch_project_batched(v, P->dtype, g, ldg, k, s, partial, grid, st);
+}
+
+int twa_expand_update(const twa_pmat* P, const float* s, float* w, float lr, float* g_tilde, void* stream) {
+  PView v;
+  int rc = view_of(P, &v);
+  if (rc != TWA_OK) return rc;
+  if (!s || !w) return TWA_ERR_NULL;
+  if (!aligned16(w) || (g_tilde && !aligned16(g_tilde)) || (reinterpret_cast<uintptr_t>(s) & 3u))
+    return TWA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t min_tile = 64 * 4;   // never more waves than 256-element pieces of D
+  const int grid = persistent_grid("TWA_EXPAND_WGS_PER_CU", 3, (v.D + 4 * min_tile - 1) / (4 * min_tile));
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  const bool reverse = env_int("TWA_EXPAND_REVERSE", 1) != 2;   // 2 switches the descending order off
+  return launch_expand_update(v, P->dtype, s, w, lr, g_tilde, grid, reverse, st);
+}
+
+int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* out, void* stream) {
+  if (!P || !out || !out->data) return TWA_ERR_NULL;
+  const int bits = bits_of(out->dtype);
+  if (bits == 0) return TWA_ERR_DTYPE;
+  if (out->D != D || out->n != n) return TWA_ERR_SHAPE;
+  int rc = check_dims(D, n, ldp, 32);
+  if (rc != TWA_OK) return rc;
+  rc = check_dims(D, n, out->ld, bits);
+  if (rc != TWA_OK) return rc;
+  if (!aligned16(P) || !aligned16(out->data)) return TWA_ERR_ALIGN;
+  if (scaled(out->dtype)) {
+    if (!out->scales) return TWA_ERR_NULL;
+    if (!aligned16(out->scales)) return TWA_ERR_ALIGN;
+    if (!pow2(out->block) || out->block < 32 || out->block > 256) return TWA_ERR_SHAPE;
+    if (out->ld % out->block != 0) return TWA_ERR_ALIGN;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (out->dtype == TWA_I4) {
+    if (out->gscale == 0.0f) {
+      // largest block scale = (largest |p|) / 7: find it, then pick the power of two that puts
+      // the largest binary16 scale in [2^14, 2^15).  The first word of the code buffer is scratch.
+      float* tmp = static_cast<float*>(out->data);
+      rc = launch_absmax(P, D, n, ldp, tmp, st);
+      if (rc != TWA_OK) return rc;
+      float amax = 0.0f;
+      rc = hip_check(hipMemcpyAsync(&amax, tmp, sizeof(float), hipMemcpyDeviceToHost, st));
+      if (rc != TWA_OK) return rc;
+      rc = hip_check(hipStreamSynchronize(st));
+      if (rc != TWA_OK) return rc;
+      const float smax = amax / 7.0f;
+      if (smax > 0.0f && isfinite(smax)) {
+        int ex = 0;
+        (void)frexpf(smax, &ex);                    // smax = m * 2^ex, m in [0.5, 1)
+        out->gscale = ldexpf(1.0f, ex - 1 - 14);
+      } else {
+        out->gscale = 1.0f;
+      }
+    } else {
+      int ex = 0;
+      if (!(out->gscale > 0.0f) || !isfinite(out->gscale) || frexpf(out->gscale, &ex) != 0.5f) return TWA_ERR_SHAPE;
+    }
+  }
+  return launch_quantize(P, D, n, ldp, *out, st);
+}
+
+int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P, int64_t ldp, double* R_host,
+                    void* ws, size_t ws_bytes, void* stream) {
+  if (!W || !P) return TWA_ERR_NULL;
+  int rc = check_dims(D, n, ldw, 32);
+  if (rc != TWA_OK) return rc;
+  rc = check_dims(D, n, ldp, 32);
+  if (rc != TWA_OK) return rc;
+  if (n > D) return TWA_ERR_SHAPE;
+  if (!aligned16(W) || !aligned16(P)) return TWA_ERR_ALIGN;
+  if (static_cast<const void*>(W) == static_cast<const void*>(P) && ldw != ldp) return TWA_ERR_SHAPE;
+  size_t need = 0;
+  twa_build_basis_workspace_bytes(n, &need);
+  if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
+  if (!aligned16(ws)) return TWA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  const int NP = (n + 15) / 16 * 16;
+  const int cus = device_cus();
+  if (cus <= 0) return TWA_ERR_NO_DEVICE;
+  const int64_t nchunks = (D + 63) / 64;
+  int grid = cus * env_int("TWA_BASIS_WGS_PER_CU", 2);
+  if (grid > kGramMaxGrid) grid = kGramMaxGrid;
+  if (grid > nchunks) grid = (int)nchunks;
+  double* partial = static_cast<double*>(ws);
+  double* gram_dev = partial + (size_t)kGramMaxGrid * NP * NP;
+  float* rinv_dev = reinterpret_cast<float*>(gram_dev + (size_t)NP * NP);
+
+  std::vector<double> gram_pad((size_t)NP * NP), G((size_t)n * n), R, X, Rtot;
+  std::vector<float> rinv_pad((size_t)NP * NP);
+  const float* src = W;
+  int64_t lds = ldw;
+  for (int pass = 0; pass < 2; ++pass) {
+    rc = launch_gram(src, D, n, lds, partial, grid, gram_dev, st);
+    if (rc != TWA_OK) return rc;
+    rc = hip_check(hipMemcpyAsync(gram_pad.data(), gram_dev, sizeof(double) * NP * NP, hipMemcpyDeviceToHost, st));
+    if (rc != TWA_OK) return rc;
+    rc = hip_check(hipStreamSynchronize(st));
+    if (rc != TWA_OK) return rc;
+    for (int i = 0; i < n; ++i)
+      for (int j = 0; j < n; ++j)
+        G[(size_t)i * n + j] = (j >= i) ? gram_pad[(size_t)i * NP + j] : gram_pad[(size_t)j * NP + i];
+    const int bad = cholesky_upper(G, n, 1e-12, R);
+    if (bad >= 0) {
+      if (R_host) R_host[0] = (double)bad;
+      return TWA_ERR_RANK;
+    }
+    invert_upper(R, n, X);
+    std::fill(rinv_pad.begin(), rinv_pad.end(), 0.0f);
+    for (int i = 0; i < n; ++i)
+      for (int j = i; j < n; ++j) rinv_pad[(size_t)i * NP + j] = (float)X[(size_t)i * n + j];
+    rc = hip_check(hipMemcpyAsync(rinv_dev, rinv_pad.data(), sizeof(float) * NP * NP, hipMemcpyHostToDevice, st));
+    if (rc != TWA_OK) return rc;
+    rc = hip_check(hipStreamSynchronize(st));     // rinv_pad is reused by the next pass
+    if (rc != TWA_OK) return rc;
+    rc = launch_apply_rinv(src, lds, P, ldp, D, n, rinv_dev, grid, st);
+    if (rc != TWA_OK) return rc;
+    if (pass == 0) {
+      Rtot = R;
+    } else {
+      // W = Q1 R1, Q1 = P R2  ->  W = P (R2 R1)
+      std::vector<double> T((size_t)n * n, 0.0);
+      for (int i = 0; i < n; ++i)
+        for (int j = i; j < n; ++j) {
+          double v = 0.0;
+          for (int k = i; k <= j; ++k) v += R[(size_t)i * n + k] * Rtot[(size_t)k * n + j];
+          T[(size_t)i * n + j] = v;
+        }
+      Rtot.swap(T);
+    }
+    src = P;
+    lds = ldp;
+  }
+  if (R_host) memcpy(R_host, Rtot.data(), sizeof(double) * (size_t)n * n);
+  return TWA_OK;
+}
+
+}  // extern "C"

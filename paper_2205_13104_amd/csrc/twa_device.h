@@ -1,0 +1,161 @@
+// Device-side helpers shared by the gfx950 kernels: buffer-descriptor loads/stores and the
+// in-register decoding of the four storage types of the projection matrix.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/twa.h"
+
+namespace twa {
+
+using u32x4 = unsigned int __attribute__((ext_vector_type(4)));
+using u32x2 = unsigned int __attribute__((ext_vector_type(2)));
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+
+constexpr int kWave = 64;
+
+// Raw (stride 0) buffer descriptor over [base, base+bytes).  A load whose byte offset lies
+// outside the range returns 0 and moves no data; a store outside it is dropped.  Every
+// streaming access in the hot kernels goes through such a descriptor, so ragged tails and
+// unused column slots need no branches: they are given an empty range.
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 ld128(rsrc_t r, uint32_t voff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
+}
+// Same, with the non-temporal hint: for data that is streamed once per kernel (the stored P).
+// Measured on MI355X: a pure read stream reaches ~7.1 TB/s with the hint and ~6.3 TB/s without.
+__device__ __forceinline__ u32x4 ld128_stream(rsrc_t r, uint32_t voff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, /*nt*/ 2);
+}
+__device__ __forceinline__ uint32_t ld32(rsrc_t r, uint32_t voff) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, 0, 0);
+}
+__device__ __forceinline__ uint32_t ld16(rsrc_t r, uint32_t voff) {
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, 0, 0);
+}
+__device__ __forceinline__ void st128(rsrc_t r, uint32_t voff, u32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, 0, 0);
+}
+__device__ __forceinline__ void st32(rsrc_t r, uint32_t voff, uint32_t v) {
+  __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, 0, 0);
+}
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// Storage traits.  One "vector" is what a lane fetches with one 128-bit load.
+template <int DT> struct Store;
+template <> struct Store<TWA_F32> {
+  static constexpr int kEPV = 4;          // elements per 128-bit vector
+  static constexpr int kBitsPerElem = 32;
+  static constexpr bool kScaled = false;
+  static constexpr int kScaleBytes = 0;
+};
+template <> struct Store<TWA_BF16> {
+  static constexpr int kEPV = 8;
+  static constexpr int kBitsPerElem = 16;
+  static constexpr bool kScaled = false;
+  static constexpr int kScaleBytes = 0;
+};
+template <> struct Store<TWA_I8> {
+  static constexpr int kEPV = 16;
+  static constexpr int kBitsPerElem = 8;
+  static constexpr bool kScaled = true;
+  static constexpr int kScaleBytes = 4;
+};
+template <> struct Store<TWA_I4> {
+  static constexpr int kEPV = 32;
+  static constexpr int kBitsPerElem = 4;
+  static constexpr bool kScaled = true;
+  static constexpr int kScaleBytes = 2;
+};
+
+// Decode one 128-bit vector into kEPV "raw" floats: the stored value up to the per-block
+// scale, and for I4 up to the bias and nibble position:
+//   F32, BF16 : raw = value
+//   I8        : raw = q
+//   I4        : raw[e] = (q+8) for even e, 16*(q+8) for odd e   (elements e = 2*byte, 2*byte+1)
+// Callers fold the 1/16 and the -8 into per-tile / per-block terms instead of per element.
+template <int DT> __device__ __forceinline__ void decode(const u32x4& v, float* raw);
+
+template <> __device__ __forceinline__ void decode<TWA_F32>(const u32x4& v, float* raw) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) raw[q] = as_f32(v[q]);
+}
+template <> __device__ __forceinline__ void decode<TWA_BF16>(const u32x4& v, float* raw) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    raw[2 * q] = as_f32(v[q] << 16);
+    raw[2 * q + 1] = as_f32(v[q] & 0xffff0000u);
+  }
+}
+template <> __device__ __forceinline__ void decode<TWA_I8>(const u32x4& v, float* raw) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t w = v[q];
+    raw[4 * q + 0] = (float)(int8_t)(w & 0xff);          // one sign-extending byte convert each
+    raw[4 * q + 1] = (float)(int8_t)((w >> 8) & 0xff);
+    raw[4 * q + 2] = (float)(int8_t)((w >> 16) & 0xff);
+    raw[4 * q + 3] = (float)(int8_t)(w >> 24);
+  }
+}
+template <> __device__ __forceinline__ void decode<TWA_I4>(const u32x4& v, float* raw) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t lo = v[q] & 0x0f0f0f0fu;               // even elements: q+8
+    const uint32_t hi = v[q] & 0xf0f0f0f0u;               // odd elements: 16*(q+8)
+    raw[8 * q + 0] = (float)(lo & 0xff);
+    raw[8 * q + 1] = (float)(hi & 0xff);
+    raw[8 * q + 2] = (float)((lo >> 8) & 0xff);
+    raw[8 * q + 3] = (float)((hi >> 8) & 0xff);
+    raw[8 * q + 4] = (float)((lo >> 16) & 0xff);
+    raw[8 * q + 5] = (float)((hi >> 16) & 0xff);
+    raw[8 * q + 6] = (float)(lo >> 24);
+    raw[8 * q + 7] = (float)(hi >> 24);
+  }
+}
+
+// Scale of one block as a float (binary16 scales are widened and multiplied by gscale).
+template <int DT> __device__ __forceinline__ float load_scale(rsrc_t r, uint32_t voff, float gscale) {
+  if constexpr (DT == TWA_I8) {
+    return as_f32(ld32(r, voff));
+  } else if constexpr (DT == TWA_I4) {
+    const uint16_t h = (uint16_t)ld16(r, voff);
+    return (float)__builtin_bit_cast(_Float16, h) * gscale;
+  } else {
+    return 1.0f;
+  }
+}
+
+// Sum over the 64 lanes of a wave, same order on every call; result valid in every lane.
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, kWave);
+  return x;
+}
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, kWave);
+  return x;
+}
+
+// View of a stored matrix passed to kernels by value.
+struct PView {
+  const uint8_t* data;
+  const uint8_t* scales;
+  int64_t D;
+  int64_t ld;
+  int32_t n;
+  int32_t block_shift;   // log2(block)
+  float gscale;
+};
+
+// Balanced split of `total` units over `parts` workers: worker w owns [lo, hi).
+__device__ __forceinline__ void split_range(int64_t total, int parts, int w, int64_t& lo, int64_t& hi) {
+  lo = total * (int64_t)w / parts;
+  hi = total * (int64_t)(w + 1) / parts;
+}
+
+}  // namespace twa

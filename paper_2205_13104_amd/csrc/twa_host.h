@@ -1,0 +1,37 @@
+// Host-side plumbing shared by the translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/twa.h"
+
+namespace twa {
+
+struct PView;
+
+// Records a failing hipError_t for twa_last_hip_error() and maps it to a twa_status.
+int hip_check(hipError_t e);
+
+// Number of compute units of the current device (cached per device); <= 0 on failure.
+int device_cus();
+
+// Upper bound of any persistent grid the library launches (sizes the workspaces).
+constexpr int kMaxGrid = 2048;
+
+// Integer tuning knob from the environment (read once per name), e.g. TWA_PROJECT_WGS_PER_CU.
+int env_int(const char* name, int fallback);
+
+// Kernel launchers (defined next to their kernels).
+int project_tile_elems(int dtype);
+int launch_project(const PView& P, int dtype, const float* g, float* s, float* partial, int grid, hipStream_t st);
+int launch_project_batched(const PView& P, int dtype, const float* g, int64_t ldg, int k, float* s, float* partial,
+                           int grid, hipStream_t st);
+int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int grid,
+                         bool reverse, hipStream_t st);
+int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pmat& out, hipStream_t st);
+int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st);
+int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram, hipStream_t st);
+int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
+                      int grid, hipStream_t st);
+
+}  // namespace twa

@@ -1,0 +1,115 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol that
+include/twa.h declares, sizes buffers as the paper's memory table says, and rejects bad arguments
+with the documented status codes before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2205_13104_amd import binding as twa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    src = open(os.path.join(ROOT, "include", "twa.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(twa_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = twa.lib()
+    names = declared_symbols()
+    assert {"twa_build_basis", "twa_quantize", "twa_project", "twa_expand_update"} <= set(names)
+    for nm in names:
+        assert hasattr(L, nm), nm
+    assert L.twa_version() >= 100
+    assert twa.strerror(0) == "success" and "NULL" in twa.strerror(twa.ERR_NULL)
+
+
+def test_pmat_bytes_follow_the_memory_table():
+    # Sec. 4.6: 4nD bytes at 32 bits, nBD/8 bytes of codes at B bits (here D is padded to a multiple of 128)
+    D, n = 25_557_032, 100
+    ld, db, sb = twa.pmat_bytes(twa.F32, D, n)
+    assert ld == (D + 127) // 128 * 128 and db == 4 * n * ld and sb == 0
+    ld, db, sb = twa.pmat_bytes(twa.I8, D, n, 128)
+    assert db == n * 8 * ld // 8 and sb == n * (ld // 128) * 4
+    ld, db, sb = twa.pmat_bytes(twa.I4, D, n, 64)
+    assert db == n * 4 * ld // 8 and sb == n * (ld // 64) * 2
+    ld, db, sb = twa.pmat_bytes(twa.BF16, D, n)
+    assert db == 2 * n * ld
+    with pytest.raises(twa.TwaError) as e:
+        twa.pmat_bytes(twa.I8, D, n, 100)          # block must be a power of two
+    assert e.value.code == twa.ERR_SHAPE
+    with pytest.raises(twa.TwaError) as e:
+        twa.pmat_bytes(7, D, n)
+    assert e.value.code == twa.ERR_DTYPE
+    with pytest.raises(twa.TwaError) as e:
+        twa.pmat_bytes(twa.F32, D, 129)
+    assert e.value.code == twa.ERR_SHAPE
+    with pytest.raises(twa.TwaError) as e:
+        twa.pmat_bytes(twa.F32, 2 ** 31, 1)        # one fp32 vector must stay below 4 GiB
+    assert e.value.code == twa.ERR_SHAPE
+
+
+def _pm(dtype=twa.F32, n=4, D=1000, ld=1024, data=0x1000, scales=0, block=0, gscale=1.0):
+    return twa._Pmat(dtype, n, D, ld, data, scales, block, gscale)
+
+
+def _project(pm, g=0x2000, k=1, ldg=0, s=0x3000, ws=0x4000, wsb=None):
+    if wsb is None:
+        wsb = twa.project_workspace_bytes(max(1, min(pm.n, 128)), max(1, min(k, 8)))
+    return twa.lib().twa_project(C.byref(pm), g, k, ldg, s, ws, wsb, None)
+
+
+def test_project_argument_errors():
+    assert twa.lib().twa_project(None, 0x2000, 1, 0, 0x3000, 0x4000, 1 << 30, None) == twa.ERR_NULL
+    assert _project(_pm(data=0)) == twa.ERR_NULL
+    assert _project(_pm(), g=0) == twa.ERR_NULL
+    assert _project(_pm(), s=0) == twa.ERR_NULL
+    assert _project(_pm(dtype=9)) == twa.ERR_DTYPE
+    assert _project(_pm(n=0)) == twa.ERR_SHAPE
+    assert _project(_pm(n=129)) == twa.ERR_SHAPE
+    assert _project(_pm(D=0)) == twa.ERR_SHAPE
+    assert _project(_pm(D=2000)) == twa.ERR_SHAPE            # ld < D
+    assert _project(_pm(ld=1000)) == twa.ERR_ALIGN           # ld not a multiple of 128
+    assert _project(_pm(data=0x1004)) == twa.ERR_ALIGN
+    assert _project(_pm(), g=0x2004) == twa.ERR_ALIGN
+    assert _project(_pm(), k=0) == twa.ERR_SHAPE
+    assert _project(_pm(), k=9) == twa.ERR_SHAPE
+    assert _project(_pm(), k=2, ldg=999) == twa.ERR_SHAPE    # ldg < D
+    assert _project(_pm(), ws=0) == twa.ERR_WORKSPACE
+    assert _project(_pm(), wsb=16) == twa.ERR_WORKSPACE
+    assert _project(_pm(dtype=twa.I8, block=128)) == twa.ERR_NULL          # scales missing
+    assert _project(_pm(dtype=twa.I8, block=100, scales=0x5000)) == twa.ERR_SHAPE
+    assert _project(_pm(dtype=twa.I8, block=256, scales=0x5000, ld=1152, D=1100)) == twa.ERR_ALIGN  # ld % block
+    assert _project(_pm(dtype=twa.I4, block=64, scales=0x5000, gscale=3.0)) == twa.ERR_SHAPE       # not a power of 2
+    assert _project(_pm(dtype=twa.I4, block=64, scales=0x5000, gscale=0.0)) == twa.ERR_SHAPE
+
+
+def test_other_entry_points_argument_errors():
+    L = twa.lib()
+    pm = _pm()
+    assert L.twa_expand_update(C.byref(pm), 0, 0x3000, 0.1, None, None) == twa.ERR_NULL
+    assert L.twa_expand_update(C.byref(pm), 0x2000, 0, 0.1, None, None) == twa.ERR_NULL
+    assert L.twa_expand_update(C.byref(pm), 0x2000, 0x3004, 0.1, None, None) == twa.ERR_ALIGN
+    out = _pm(dtype=twa.I8, block=128, scales=0x5000)
+    assert L.twa_quantize(None, 1000, 4, 1024, C.byref(out), None) == twa.ERR_NULL
+    assert L.twa_quantize(0x6000, 1000, 5, 1024, C.byref(out), None) == twa.ERR_SHAPE     # n mismatch
+    assert L.twa_quantize(0x6000, 1000, 4, 1000, C.byref(out), None) == twa.ERR_ALIGN     # ldp
+    bad = _pm(dtype=twa.I4, block=64, scales=0x5000, gscale=0.3)
+    assert L.twa_quantize(0x6000, 1000, 4, 1024, C.byref(bad), None) == twa.ERR_SHAPE
+    wsb = twa.build_basis_workspace_bytes(4)
+    assert L.twa_build_basis(None, 1000, 4, 1024, 0x7000, 1024, None, 0x8000, wsb, None) == twa.ERR_NULL
+    assert L.twa_build_basis(0x6000, 3, 4, 128, 0x7000, 128, None, 0x8000, wsb, None) == twa.ERR_SHAPE   # n > D
+    assert L.twa_build_basis(0x6000, 1000, 4, 1024, 0x7000, 1024, None, 0x8000, 8, None) == twa.ERR_WORKSPACE
+    assert L.twa_build_basis(0x6000, 1000, 4, 1024, 0x6000, 2048, None, 0x8000, wsb, None) == twa.ERR_SHAPE  # alias
+
+
+def test_valid_call_without_a_gpu_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    # every argument is acceptable, so the only thing missing is the device: no silent fallback
+    assert _project(_pm()) == twa.ERR_NO_DEVICE

@@ -1,0 +1,304 @@
+"""Parity of the HIP library (through its C ABI) against the fp64 CPU oracle, element by element, on
+seeded synthetic inputs.  Bars: integer codes, scales and 16-bit conversions bit-exact; s, g~, w
+within a relative L2 error of 1e-5 of the oracle evaluated on the SAME stored P; max|P^T P - I| <= 1e-5
+after basis construction.  Sizes span several tiles of every kernel plus a ragged tail."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import twa_oracle as orc
+from paper_2205_13104_amd import binding as twa
+from paper_2205_13104_amd import synth
+from tests.gpu_common import ORTHO_TOL, REL_L2_TOL, random_basis_like, rel_l2, store_as, to_oracle
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [twa.F32, twa.BF16, twa.I8, twa.I4]
+NAMES = {twa.F32: "f32", twa.BF16: "bf16", twa.I8: "i8", twa.I4: "i4"}
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------------------------------------ quantize
+@pytest.mark.parametrize("D,n,block", [(128 * 9 + 40, 3, 128), (70001, 5, 128), (4096, 2, 32), (5000, 4, 64),
+                                       (100000, 7, 256), (17, 1, 128)])
+def test_quantize_i8_bit_exact(D, n, block):
+    say("quantize_i8", D, n, block)
+    P = random_basis_like(D, n, seed=D + n)
+    P[0, 128:256] = 0.0 if D > 256 else P[0, 128:256]          # an all-zero block
+    ref = orc.quantize_i8(P.cpu().numpy(), D=D, block=block, ld=P.shape[1])
+    pm = twa.quantize(P, D, twa.I8, block=block)
+    torch.cuda.synchronize()
+    assert pm.ld == ref.ld
+    assert np.array_equal(pm.scales.cpu().numpy().view(np.uint32), ref.scales.view(np.uint32))
+    assert np.array_equal(pm.data.cpu().numpy(), ref.data)
+
+
+@pytest.mark.parametrize("mag", [1.0, 3e-5, 250.0])
+def test_quantize_i8_bit_exact_near_ties(mag):
+    # values placed on and next to rounding ties of the recipe
+    D, n = 128 * 64, 2
+    g = torch.Generator().manual_seed(5)
+    base = torch.rand((n, D), generator=g) * 2 - 1
+    amax = base.abs().amax()
+    k = torch.randint(-126, 127, (n, D), generator=g).float() + 0.5
+    P = (k * (amax / 127.0)).float()
+    P[:, ::3] = base[:, ::3]
+    P[:, 0] = amax
+    P = (P * mag).contiguous().cuda()
+    ref = orc.quantize_i8(P.cpu().numpy())
+    pm = twa.quantize(P, D, twa.I8)
+    assert np.array_equal(pm.scales.cpu().numpy().view(np.uint32), ref.scales.view(np.uint32))
+    assert np.array_equal(pm.data.cpu().numpy(), ref.data)
+
+
+@pytest.mark.parametrize("D,n,block", [(64 * 9 + 21, 3, 64), (70001, 5, 64), (4096, 2, 32), (100000, 3, 256),
+                                       (33, 1, 64)])
+def test_quantize_i4_bit_exact(D, n, block):
+    say("quantize_i4", D, n, block)
+    P = random_basis_like(D, n, seed=D + 3 * n)
+    if D > 256:
+        P[0, 128:256] = 0.0
+    Pn = P.cpu().numpy()
+    gs = orc.gscale_i4(Pn, D)
+    ref = orc.quantize_i4(Pn, D=D, block=block, ld=P.shape[1], gscale=gs)
+    pm = twa.quantize(P, D, twa.I4, block=block)              # gscale chosen by the library
+    assert pm.gscale == gs
+    assert np.array_equal(pm.scales.view(torch.int16).cpu().numpy().view(np.uint16), ref.scales)
+    assert np.array_equal(pm.data.cpu().numpy(), ref.data)
+    # caller-supplied power of two: no synchronisation inside, same rules
+    pm2 = twa.quantize(P, D, twa.I4, block=block, gscale=gs * 4)
+    ref2 = orc.quantize_i4(Pn, D=D, block=block, ld=P.shape[1], gscale=gs * 4)
+    assert np.array_equal(pm2.scales.view(torch.int16).cpu().numpy().view(np.uint16), ref2.scales)
+    assert np.array_equal(pm2.data.cpu().numpy(), ref2.data)
+
+
+def test_quantize_bf16_and_f32_bit_exact():
+    D, n = 70001, 3
+    P = random_basis_like(D, n, seed=9)
+    P[1, :6] = torch.tensor([1.0, 1.00390625, 1.01171875, -1.00390625, 0.0, 3.0e38])
+    ref = orc.to_bf16(P.cpu().numpy(), D=D, ld=P.shape[1])
+    pm = twa.quantize(P, D, twa.BF16)
+    assert np.array_equal(pm.data.view(torch.int16).cpu().numpy().view(np.uint16), ref.data)
+    pf = twa.quantize(P, D, twa.F32)
+    assert torch.equal(pf.data[:, :D], P[:, :D]) and not pf.data[:, D:].any()
+
+
+# ------------------------------------------------------------------------------------------------ project
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("D,n", [(300017, 100), (65536, 10), (1000, 1), (40000, 128), (123457, 37), (9, 3)])
+def test_project_matches_oracle(dtype, D, n):
+    say("project", NAMES[dtype], D, n)
+    P32 = random_basis_like(D, n, seed=11 + n)
+    pm = store_as(P32, D, dtype)
+    g = synth.gradient(D, 1e-2, seed=1, device="cuda")
+    s = twa.project(pm, g)
+    ref = orc.project(to_oracle(pm), g.cpu().numpy().astype(np.float64))
+    err = rel_l2(s.cpu().numpy(), ref)
+    say("  rel_l2", err)
+    assert err <= REL_L2_TOL
+    # deterministic reduction order: a second call returns identical bits
+    s2 = twa.project(pm, g)
+    assert torch.equal(s, s2)
+
+
+def test_project_ignores_padding_garbage():
+    D, n = 5000, 6
+    P32 = random_basis_like(D, n, seed=3)
+    P32[:, D:] = float("nan")
+    pm = twa.wrap_f32(P32, D)
+    g = synth.gradient(D, 1e-2, seed=2, device="cuda")
+    s = twa.project(pm, g)
+    ref = orc.project(to_oracle(pm), g.cpu().numpy().astype(np.float64))
+    assert rel_l2(s.cpu().numpy(), ref) <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("dtype,n,k", [(twa.BF16, 20, 8), (twa.F32, 10, 3), (twa.I8, 32, 8), (twa.I4, 12, 2),
+                                       (twa.BF16, 40, 4)])
+def test_project_batched_matches_oracle(dtype, n, k):
+    D = 150001
+    say("project_batched", NAMES[dtype], D, n, k)
+    P32 = random_basis_like(D, n, seed=21 + n)
+    pm = store_as(P32, D, dtype)
+    G = synth.gradient(D, 1e-2, seed=4, device="cuda", k=k, ldg=D + 3 + (4 - (D + 3) % 4) % 4)
+    S = twa.project(pm, G)
+    ref = orc.project(to_oracle(pm), G.cpu().numpy().astype(np.float64))
+    assert S.shape == (k, n)
+    err = rel_l2(S.cpu().numpy(), ref)
+    say("  rel_l2", err)
+    assert err <= REL_L2_TOL
+    # each gradient alone gives the same row
+    s0 = twa.project(pm, G[0, :D].contiguous())
+    assert rel_l2(S[0].cpu().numpy(), s0.cpu().numpy()) <= 1e-6
+
+
+# ------------------------------------------------------------------------------------------------ expand_update
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("D,n", [(300017, 100), (65536, 10), (1000, 1), (40000, 128), (123457, 37), (9, 3)])
+def test_expand_update_matches_oracle(dtype, D, n):
+    say("expand_update", NAMES[dtype], D, n)
+    P32 = random_basis_like(D, n, seed=31 + n)
+    pm = store_as(P32, D, dtype)
+    gen = torch.Generator().manual_seed(7)
+    s = (torch.randn(n, generator=gen) * 1e-2).cuda()
+    w0 = (torch.randn(D, generator=gen) * 0.05).cuda()
+    lr = 0.1
+    w = w0.clone()
+    gt = torch.empty(D, device="cuda")
+    twa.expand_update(pm, s, w, lr, gt)
+    wo = w0.cpu().numpy().astype(np.float64)
+    gto = orc.expand_update(to_oracle(pm), s.cpu().numpy().astype(np.float64), wo, lr, want_gt=True)
+    e_gt, e_w = rel_l2(gt.cpu().numpy(), gto), rel_l2(w.cpu().numpy(), wo)
+    say("  rel_l2 g~", e_gt, "w", e_w)
+    assert e_gt <= REL_L2_TOL and e_w <= REL_L2_TOL
+    # the update itself is one fused multiply-add per element: from the same fp32 w and the library's
+    # own g~ the new weight is the exactly computed w - lr*g~ rounded once (1 ulp allowed for the
+    # double rounding of this check)
+    lr32 = float(np.float32(lr))
+    exact = w0.cpu().numpy().astype(np.float64) - lr32 * gt.cpu().numpy().astype(np.float64)
+    ulp = np.spacing(np.abs(exact).astype(np.float32)).astype(np.float64)
+    assert np.all(np.abs(w.cpu().numpy().astype(np.float64) - exact) <= ulp)
+    # without the optional output the weights come out identical
+    w2 = w0.clone()
+    twa.expand_update(pm, s, w2, lr, None)
+    assert torch.equal(w, w2)
+
+
+def test_expand_update_does_not_touch_memory_past_D():
+    D, n = 1000 * 4 + 3, 5                     # D % 4 != 0: the last 128-bit store straddles the end
+    P32 = random_basis_like(D, n, seed=2)
+    pm = twa.wrap_f32(P32, D)
+    buf = torch.full((D + 61,), 7.0, device="cuda")
+    gbuf = torch.full((D + 61,), 9.0, device="cuda")
+    s = torch.ones(n, device="cuda")
+    twa.expand_update(pm, s, buf, 1.0, gbuf)
+    assert torch.all(buf[D:] == 7.0) and torch.all(gbuf[D:] == 9.0)
+    assert not torch.any(buf[:D] == 7.0)
+
+
+# ------------------------------------------------------------------------------------------------ chained steps
+@pytest.mark.parametrize("dtype", [twa.F32, twa.I8])
+def test_chained_steps_tiny_config(dtype):
+    # the small benchmark configuration at reduced D: trajectory checkpoints, basis on the GPU, T steps
+    wl = synth.WORKLOADS["tiny"]
+    D, n, T = 50021, wl.n, 20
+    W = synth.checkpoints(wl, seed=0, device="cuda", D=D)
+    P, _ = twa.build_basis(W, D)
+    pm = store_as(P, D, dtype)
+    po = to_oracle(pm)
+    w = W[:, :D].mean(dim=0).contiguous()
+    wo = w.cpu().numpy().astype(np.float64)
+    w_start = wo.copy()
+    ws = twa.Workspace(twa.project_workspace_bytes(n))
+    s = torch.empty(n, device="cuda")
+    for t in range(T):
+        g = synth.gradient(D, wl.sigma_g, seed=0, step=t, device="cuda")
+        twa.project(pm, g, s, ws)
+        twa.expand_update(pm, s, w, wl.lr)
+        so = orc.project(po, g.cpu().numpy().astype(np.float64))
+        assert rel_l2(s.cpu().numpy(), so) <= REL_L2_TOL
+        orc.expand_update(po, so, wo, wl.lr)
+    assert rel_l2(w.cpu().numpy(), wo) <= REL_L2_TOL
+    # displacement w_T - w_0: limited by the fp32 rounding of every in-place store, reported only
+    say("  displacement rel_l2", rel_l2(w.cpu().numpy().astype(np.float64) - w_start, wo - w_start))
+
+
+# ------------------------------------------------------------------------------------------------ build_basis
+def _basis_checks(W, P, R, D, n):
+    Wh = W[:, :D].cpu().numpy().astype(np.float64)
+    Ph = P[:, :D].cpu().numpy().astype(np.float64)
+    ortho = np.max(np.abs(Ph @ Ph.T - np.eye(n)))
+    say("  max|PtP-I|", ortho)
+    assert ortho <= ORTHO_TOL
+    Rh = R.numpy()
+    assert np.all(np.diag(Rh) > 0) and np.max(np.abs(np.tril(Rh, -1))) == 0.0
+    resid = np.linalg.norm(Wh - Rh.T @ Ph) / np.linalg.norm(Wh)
+    say("  |W-PR|/|W|", resid)
+    assert resid <= 1e-5
+    # R agrees with P^T W and the first vector is the first checkpoint normalised
+    Rchk = Ph @ Wh.T
+    assert np.max(np.abs(np.tril(Rchk, -1))) <= 1e-4 * np.max(np.abs(Rchk))
+    assert rel_l2(Ph[0], Wh[0] / np.linalg.norm(Wh[0])) <= 1e-5
+    return Wh, Ph
+
+
+@pytest.mark.parametrize("name,D,n", [("tiny", 200003, 10), ("cifar_resnet18", 60017, 100), ("large", 30011, 128),
+                                      ("vit_b16_finetune", 90001, 20), ("tiny", 64, 5)])
+def test_build_basis_invariants(name, D, n):
+    say("build_basis", name, D, n)
+    wl = synth.WORKLOADS[name]
+    W = synth.checkpoints(wl, seed=1, device="cuda", D=D, n=n)
+    P, R = twa.build_basis(W, D)
+    Wh, Ph = _basis_checks(W, P, R, D, n)
+    assert not P[:, D:].any()
+    # span(P) = span(W): each checkpoint is reproduced by its projection on P, and the oracle's basis
+    # (Householder, fp64) spans the same space: its vectors are reproduced by P as well
+    assert np.linalg.norm(Wh - (Wh @ Ph.T) @ Ph) <= 1e-5 * np.linalg.norm(Wh)
+    Po, Ro = orc.build_basis(Wh)
+    assert np.max(np.abs(Po - (Po @ Ph.T) @ Ph)) <= 2e-3          # conditioning-limited (kappa * eps32), reported
+    say("  max|P_oracle - proj|", np.max(np.abs(Po - (Po @ Ph.T) @ Ph)), " |R-R_oracle|/|R|",
+        np.linalg.norm(R.numpy() - Ro) / np.linalg.norm(Ro))
+    assert np.linalg.norm(R.numpy() - Ro) <= 1e-5 * np.linalg.norm(Ro)
+
+
+def test_build_basis_in_place_and_n1():
+    D = 40001
+    wl = synth.WORKLOADS["tiny"]
+    W = synth.checkpoints(wl, seed=2, device="cuda", D=D, n=10)
+    P_ref, R_ref = twa.build_basis(W, D)
+    W2 = W.clone()
+    P2, R2 = twa.build_basis(W2, D, out=W2)
+    assert P2.data_ptr() == W2.data_ptr()
+    assert torch.equal(P2, P_ref) and torch.equal(R2, R_ref)
+    # n = 1 closed form
+    w1 = W[:1].contiguous()
+    P1, R1 = twa.build_basis(w1, D)
+    nrm = float(np.linalg.norm(w1[0, :D].cpu().numpy().astype(np.float64)))
+    assert abs(R1[0, 0].item() - nrm) <= 1e-6 * nrm
+    assert rel_l2(P1[0, :D].cpu().numpy(), w1[0, :D].cpu().numpy().astype(np.float64) / nrm) <= 1e-6
+
+
+def test_build_basis_rank_deficient():
+    D, n = 5000, 6
+    W = random_basis_like(D, n, seed=8)
+    W[4] = 0.25 * W[1] - 3.0 * W[2]
+    with pytest.raises(twa.TwaError) as ei:
+        twa.build_basis(W, D)
+    assert ei.value.code == twa.ERR_RANK and "checkpoint 4" in str(ei.value)
+
+
+def test_projector_identities_on_gpu_basis():
+    wl = synth.WORKLOADS["tiny"]
+    D, n = 100003, 10
+    W = synth.checkpoints(wl, seed=3, device="cuda", D=D)
+    P, _ = twa.build_basis(W, D)
+    pm = twa.wrap_f32(P, D)
+    g = synth.gradient(D, 1e-2, seed=5, device="cuda")
+    s = twa.project(pm, g)
+    z = torch.zeros(D, device="cuda")
+    gt = torch.empty(D, device="cuda")
+    twa.expand_update(pm, s, z, 1.0, gt)
+    assert abs(gt.norm().item() - s.norm().item()) <= 1e-5 * s.norm().item()
+    assert s.norm().item() <= g.norm().item()
+    # idempotence: projecting g~ again returns g~
+    s2 = twa.project(pm, gt)
+    assert rel_l2(s2.cpu().numpy(), s.cpu().numpy()) <= 1e-5
+    # a checkpoint lies in the span: it is reproduced
+    v = W[3, :D].contiguous()
+    sv = twa.project(pm, v)
+    out = torch.empty(D, device="cuda")
+    twa.expand_update(pm, sv, torch.zeros(D, device="cuda"), 1.0, out)
+    assert rel_l2(out.cpu().numpy(), v.cpu().numpy()) <= 1e-5
+    # block identity of the distributed scheme (column partition of P)
+    acc = torch.zeros(D, device="cuda")
+    for part in (range(0, 5), range(5, 10)):
+        Pi = twa.wrap_f32(P[list(part)].contiguous(), D)
+        si = twa.project(Pi, g)
+        gi = torch.empty(D, device="cuda")
+        twa.expand_update(Pi, si, torch.zeros(D, device="cuda"), 1.0, gi)
+        acc += gi
+    assert rel_l2(acc.cpu().numpy(), gt.cpu().numpy()) <= 1e-5
