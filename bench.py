@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the TWA projected-gradient step on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic gradient:
+    s = P^T g   (twa_project)      then      g~ = P s, w -= lr g~   (twa_expand_update)
+enqueued back to back on one stream, s staying on the device.  The workload is the
+ResNet-50-sized configuration the metric is quoted on: D = 25,557,032, n = 100, P stored as int8
+codes with one fp32 absmax scale per 128 elements.  P is produced by the library itself from a
+synthetic checkpoint trajectory (twa_build_basis, then twa_quantize); all inputs are resident in
+HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = projected steps/s; `p_stream_GBps` = steps/s x 2 x (bytes of P);
+`roofline` = the slower of the two kernels against the 8 TB/s HBM peak, its duration measured here
+with device events on the stream the kernels run on; `cpu_baseline` = the fp64 oracle timed on the
+host cores on a bounded sample of the same stored P.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
+METRIC = "projected steps/s and P-stream HBM GB/s (% of peak), D=25.6M n=100 int8"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def read_traffic(kernel: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (profiles/hbm_traffic_*.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_imagenet_resnet50_int8.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split("#")[0].split()
+        if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel:
+            return float(parts[2])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="imagenet_resnet50", help="name in synth.WORKLOADS")
+    ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4"])
+    ap.add_argument("--D", type=int, default=0, help="override the parameter count (smoke runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is a single-GPU library (no collectives, no sharding); run with --gpus 1. "
+                 "How the path would shard over GPUs is described in DESIGN.md.")
+
+    import numpy as np
+    import torch
+    from paper_2205_13104_amd import binding as twa
+    from paper_2205_13104_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    twa.lib()   # fail loudly if the library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = synth.WORKLOADS[args.workload]
+    D = args.D or wl.D
+    n = wl.n
+    dtype = {"f32": twa.F32, "bf16": twa.BF16, "i8": twa.I8, "i4": twa.I4}[args.storage]
+
+    # ---- inputs: checkpoints -> orthonormal basis (in place) -> stored P ------------------------
+    t0 = time.time()
+    W = synth.checkpoints(wl, seed=args.seed, device=dev, D=D)
+    w = W[:, :D].mean(dim=0).contiguous()                  # the plain average: starting point of TWA
+    torch.cuda.synchronize()
+    t1 = time.time()
+    P32, _ = twa.build_basis(W, D, out=W, want_R=False)
+    torch.cuda.synchronize()
+    t2 = time.time()
+    pm = twa.wrap_f32(P32, D) if dtype == twa.F32 else twa.quantize(P32, D, dtype)
+    torch.cuda.synchronize()
+    t3 = time.time()
+    if dtype != twa.F32:
+        del W, P32
+        torch.cuda.empty_cache()
+    log(f"[bench] {wl.name}: D={D} n={n} storage={args.storage}; generate {t1 - t0:.2f}s, "
+        f"build_basis {t2 - t1:.3f}s, quantize {t3 - t2:.3f}s")
+    ring = [synth.gradient(D, wl.sigma_g, seed=args.seed, step=i, device=dev) for i in range(4)]
+    s = torch.empty(n, dtype=torch.float32, device=dev)
+    ws = twa.Workspace(twa.project_workspace_bytes(n), device=dev)
+    lr = wl.lr
+
+    def step(i):
+        twa.project(pm, ring[i & 3], s, ws)
+        twa.expand_update(pm, s, w, lr)
+
+    # ---- the timed region: exactly K steps --------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ms_total = e0.elapsed_time(e1)
+    ms_per_step = max(ms_total, wall * 1e3) / args.steps    # never report less than the host saw
+    steps_per_s = 1e3 / ms_per_step
+    p_bytes = pm.stream_bytes
+    p_stream_gbps = steps_per_s * 2 * p_bytes / 1e9
+
+    # ---- per-kernel launch durations (device events around every launch, same stream) ----------
+    K2 = min(args.steps, 200)
+
+    def timed_each(fn):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K2)]
+        for i, (a, b) in enumerate(evs):
+            a.record()
+            fn(i)
+            b.record()
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in evs) / K2
+
+    ms_project = timed_each(lambda i: twa.project(pm, ring[i & 3], s, ws))
+    ms_expand = timed_each(lambda i: twa.expand_update(pm, s, w, lr))
+    alg = {
+        "twa_project": p_bytes + 4 * D + 4 * n,                 # P once + g + s
+        "twa_expand_update": p_bytes + 8 * D + 4 * n,           # P once + w read + w write + s
+    }
+    dur = {"twa_project": ms_project, "twa_expand_update": ms_expand}
+    dom = max(dur, key=dur.get)
+    achieved = alg[dom] / (dur[dom] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(dom),
+                "algorithmic_bytes_per_launch": alg[dom], "avg_launch_ms": round(dur[dom], 5),
+                "other_kernel": {"kernel": min(dur, key=dur.get), "avg_launch_ms": round(min(dur.values()), 5),
+                                 "achieved": round(alg[min(dur, key=dur.get)] / (min(dur.values()) * 1e-3) / 1e9, 1)}}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same stored P ---------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import twa_oracle as orc
+        from oracle.bridge import to_oracle
+
+        g_h = ring[0].cpu().numpy().astype(np.float64)
+        w_h = w.cpu().numpy().astype(np.float64)
+
+        def oracle_step(cols):
+            po = to_oracle(pm, cols=cols)
+            t = time.perf_counter()
+            so = orc.project(po, g_h)
+            orc.expand_update(po, so, w_h.copy(), lr)
+            return time.perf_counter() - t
+
+        t_one = oracle_step([0])
+        m = int(max(1, min(n, round(args.cpu_seconds / max(t_one, 1e-6)))))
+        t_m = oracle_step(list(range(m))) if m > 1 else t_one
+        cpu = {"value": round(1.0 / (t_m * n / m), 5), "unit": "steps/s", "cores": orc.threads(), "kind": "oracle",
+               "sample": f"one full step (project + expand_update, fp64, on-the-fly dequantisation) over the first "
+                         f"{m} of {n} basis vectors at full D={D}: {t_m:.2f} s, scaled by {n}/{m}"}
+
+    out = {
+        "metric": METRIC, "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: D={D}, n={n}, P stored as {args.storage}"
+                               + (f" (block {pm.block}, {'fp32' if dtype == twa.I8 else 'fp16'} scales)"
+                                  if dtype in (twa.I8, twa.I4) else ""),
+                   "lr": lr, "sigma_g": wl.sigma_g, "gradient_ring": 4, "seed": args.seed},
+        "p_stream_GBps": round(p_stream_gbps, 1), "p_stream_pct_of_peak": round(100 * p_stream_gbps / HBM_PEAK_GBPS, 2),
+        "p_bytes_per_pass": p_bytes, "roofline": roofline, "cpu_baseline": cpu,
+        "setup_s": {"generate": round(t1 - t0, 3), "build_basis": round(t2 - t1, 4), "quantize": round(t3 - t2, 4)},
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

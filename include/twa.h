@@ -20,7 +20,9 @@
  *     run x[j*ld .. j*ld + D), ld >= D.  Elements [D, ld) of each run are padding.
  *   - Return value: TWA_OK (0) or a negative twa_status.  Argument errors are detected on
  *     the host before anything is enqueued (no GPU needed to get them).
- *   - Device base pointers must be 16-byte aligned and `ld` a multiple of 128 elements.
+ *   - Device base pointers must be 16-byte aligned; `ld` is a multiple of TWA_LD_MULTIPLE
+ *     (fp32, bf16) or of TWA_SCALE_SPAN (int8, int4) elements.  Padding elements must hold finite
+ *     values (the library's own producers write zeros there).
  *   - Limits: 1 <= n <= TWA_MAX_N, 1 <= k <= TWA_MAX_K, 1 <= D, and D * (bytes per stored
  *     element) < 2^32 for one vector (D <= 1.07e9 for fp32).
  */
@@ -36,13 +38,14 @@ extern "C" {
 
 #define TWA_MAX_N 128
 #define TWA_MAX_K 8
-#define TWA_LD_MULTIPLE 128
+#define TWA_LD_MULTIPLE 128   /* ld of fp32 / bf16 matrices is a multiple of this many elements   */
+#define TWA_SCALE_SPAN 2048   /* ld of int8 / int4 matrices is a multiple of this many elements   */
 
 typedef enum twa_status {
   TWA_OK = 0,
   TWA_ERR_NULL = -1,      /* a required pointer is NULL                                        */
   TWA_ERR_SHAPE = -2,     /* D, n, k, ld or block out of range                                 */
-  TWA_ERR_ALIGN = -3,     /* pointer not 16-byte aligned, or ld not a multiple of 128 / block  */
+  TWA_ERR_ALIGN = -3,     /* pointer not 16-byte aligned, or ld not a multiple of 128 / 2048   */
   TWA_ERR_DTYPE = -4,     /* unknown storage type, or one the call does not accept             */
   TWA_ERR_WORKSPACE = -5, /* workspace missing or smaller than the query reports               */
   TWA_ERR_RANK = -6,      /* checkpoints numerically linearly dependent (build_basis)          */
@@ -64,10 +67,15 @@ typedef enum twa_dtype {
  * Descriptor of a stored projection matrix P (Sec. 4.2: P = [e_1 .. e_n]; Sec. 4.6 for the
  * integer forms).  Filled by the caller; passed by pointer; never retained.
  *   data   : n runs of `ld` elements (F32: 4 B, BF16: 2 B, I8: 1 B, I4: 1/2 B per element).
- *   scales : I8: float[n][ld/block];  I4: binary16 bits, uint16_t[n][ld/block];  else NULL.
+ *   scales : one scale per block; I8: float, I4: binary16 bits (uint16_t); NULL for F32/BF16.
  *            Block b of vector j covers elements [b*block, min((b+1)*block, D)) of THAT
- *            vector.  The paper keeps one scale pair per layer (Sec. 4.6); the per-block
- *            grouping here is the finer-grained form used by the benchmark configuration.
+ *            vector.  Storage is "span interleaved": with G = TWA_SCALE_SPAN/block, the scale
+ *            of block b of vector j sits at index ((b / G) * n + j) * G + (b % G), i.e. an
+ *            array [ld/TWA_SCALE_SPAN][n][G].  The G scales that cover one 2048-element span
+ *            are contiguous and the spans of all n vectors follow each other, so a kernel tile
+ *            reads the scales of all vectors in one contiguous run.  (The paper keeps one
+ *            scale pair per layer, Sec. 4.6; the per-block grouping is the finer-grained form
+ *            of the benchmark configuration.)
  *   block  : power of two in {32, 64, 128, 256} (I8, I4); ignored for F32/BF16.
  *   gscale : I4 only: a power of two multiplying every binary16 scale so that the scales of
  *            a matrix with tiny entries (|p| ~ D^-1/2) stay normal binary16 numbers.

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtwa.so")
 
 F32, BF16, I8, I4 = 0, 1, 2, 3
-MAX_N, MAX_K, LD_MULTIPLE = 128, 8, 128
+MAX_N, MAX_K, LD_MULTIPLE, SCALE_SPAN = 128, 8, 128, 2048
 DEFAULT_BLOCK = {I8: 128, I4: 64}
 
 OK = 0
@@ -116,9 +116,15 @@ class Pmat:
     n: int
     ld: int
     data: torch.Tensor                      # (n, ld) values/codes; I4: (n, ld // 2) bytes
-    scales: Optional[torch.Tensor] = None   # (n, ld // block): float32 (I8) / float16 (I4)
+    scales: Optional[torch.Tensor] = None   # (ld // 2048, n, 2048 // block): float32 (I8) / float16 (I4)
     block: int = 0
     gscale: float = 1.0
+
+    def scales_by_vector(self) -> Optional[torch.Tensor]:
+        """The scales re-ordered (a copy, pure data movement) as (n, ld // block): row j = vector j."""
+        if self.scales is None:
+            return None
+        return self.scales.permute(1, 0, 2).reshape(self.n, -1).contiguous()
 
     def c_struct(self) -> _Pmat:
         return _Pmat(self.dtype, self.n, self.D, self.ld, _ptr(self.data), _ptr(self.scales), self.block,
@@ -147,7 +153,8 @@ def alloc_pmat(dtype: int, D: int, n: int, block: int = 0, device="cuda") -> Pma
     data = torch.empty((n, cols), dtype=_TORCH_OF[dtype], device=device)
     scales = None
     if dtype in (I8, I4):
-        scales = torch.empty((n, ld // block), dtype=torch.float32 if dtype == I8 else torch.float16, device=device)
+        scales = torch.empty((ld // SCALE_SPAN, n, SCALE_SPAN // block),
+                             dtype=torch.float32 if dtype == I8 else torch.float16, device=device)
     return Pmat(dtype, D, n, ld, data, scales, block if dtype in (I8, I4) else 0, 0.0 if dtype == I4 else 1.0)
 
 

@@ -44,6 +44,7 @@ int env_int(const char* name, int fallback) {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+static bool scaled(int dtype) { return dtype == TWA_I8 || dtype == TWA_I4; }
 static int bits_of(int dtype) {
   switch (dtype) {
     case TWA_F32: return 32;
@@ -53,13 +54,15 @@ static int bits_of(int dtype) {
     default: return 0;
   }
 }
-static bool scaled(int dtype) { return dtype == TWA_I8 || dtype == TWA_I4; }
 
-static int check_dims(int64_t D, int32_t n, int64_t ld, int bits) {
+static int64_t ld_multiple(int dtype) { return scaled(dtype) ? TWA_SCALE_SPAN : TWA_LD_MULTIPLE; }
+
+static int check_dims(int64_t D, int32_t n, int64_t ld, int dtype) {
+  const int bits = bits_of(dtype);
   if (D <= 0 || n <= 0 || n > TWA_MAX_N || ld < D) return TWA_ERR_SHAPE;
   if ((D * (int64_t)bits + 7) / 8 >= ((int64_t)1 << 32)) return TWA_ERR_SHAPE;
   if (D * 4 >= ((int64_t)1 << 32)) return TWA_ERR_SHAPE;          // g and w are fp32 vectors of length D
-  if (ld % TWA_LD_MULTIPLE != 0) return TWA_ERR_ALIGN;
+  if (ld % ld_multiple(dtype) != 0) return TWA_ERR_ALIGN;
   return TWA_OK;
 }
 
@@ -69,7 +72,7 @@ static int view_of(const twa_pmat* P, PView* v) {
   const int bits = bits_of(P->dtype);
   if (bits == 0) return TWA_ERR_DTYPE;
   if (!P->data) return TWA_ERR_NULL;
-  int rc = check_dims(P->D, P->n, P->ld, bits);
+  int rc = check_dims(P->D, P->n, P->ld, P->dtype);
   if (rc != TWA_OK) return rc;
   if (!aligned16(P->data)) return TWA_ERR_ALIGN;
   int shift = 0;
@@ -96,12 +99,14 @@ static int view_of(const twa_pmat* P, PView* v) {
   return TWA_OK;
 }
 
-static int persistent_grid(const char* env_name, int default_wgs_per_cu, int64_t max_useful) {
+// Upper bound of a persistent grid: `per_cu_x4`/4 workgroups per compute unit (a multiple of a
+// quarter), or the absolute value of the environment variable `env_name` when it is set.
+static int persistent_grid(const char* env_name, int per_cu_x4) {
   const int cus = device_cus();
   if (cus <= 0) return -1;
-  int64_t g = (int64_t)cus * env_int(env_name, default_wgs_per_cu);
+  int64_t g = env_int(env_name, 0);
+  if (g <= 0) g = (int64_t)cus * per_cu_x4 / 4;
   if (g > kMaxGrid) g = kMaxGrid;
-  if (g > max_useful) g = max_useful;
   if (g < 1) g = 1;
   return (int)g;
 }
@@ -155,7 +160,7 @@ const char* twa_strerror(int status) {
     case TWA_OK: return "success";
     case TWA_ERR_NULL: return "a required pointer is NULL";
     case TWA_ERR_SHAPE: return "D, n, k, ld, block or gscale out of range";
-    case TWA_ERR_ALIGN: return "pointer not 16-byte aligned, or ld not a multiple of 128 / of the block";
+    case TWA_ERR_ALIGN: return "pointer not 16-byte aligned, or ld not a multiple of 128 (fp32, bf16) / 2048 (int8, int4)";
     case TWA_ERR_DTYPE: return "unknown or unsupported storage type";
     case TWA_ERR_WORKSPACE: return "workspace missing or too small";
     case TWA_ERR_RANK: return "checkpoints are numerically linearly dependent";
@@ -174,8 +179,9 @@ int twa_pmat_bytes(int32_t dtype, int64_t D, int32_t n, int32_t block, int64_t* 
   if (bits == 0) return TWA_ERR_DTYPE;
   if (D <= 0 || n <= 0 || n > TWA_MAX_N) return TWA_ERR_SHAPE;
   if (scaled(dtype) && (!pow2(block) || block < 32 || block > 256)) return TWA_ERR_SHAPE;
-  const int64_t l = (D + TWA_LD_MULTIPLE - 1) / TWA_LD_MULTIPLE * TWA_LD_MULTIPLE;
-  int rc = check_dims(D, n, l, bits);
+  const int64_t mult = ld_multiple(dtype);
+  const int64_t l = (D + mult - 1) / mult * mult;
+  int rc = check_dims(D, n, l, dtype);
   if (rc != TWA_OK) return rc;
   *ld = l;
   *data_bytes = (size_t)n * (size_t)l * (size_t)bits / 8;
@@ -215,8 +221,7 @@ int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float
   if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
   if (!aligned16(ws)) return TWA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int64_t ntiles = (v.D + project_tile_elems(P->dtype) - 1) / project_tile_elems(P->dtype);
-  const int grid = persistent_grid("TWA_PROJECT_WGS_PER_CU", 3, ntiles);
+  const int grid = persistent_grid("TWA_PROJECT_GRID", 12);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   float* partial = static_cast<float*>(ws);
   if (k == 1) return launch_project(v, P->dtype, g, s, partial, grid, st);
@@ -231,11 +236,9 @@ int twa_expand_update(const twa_pmat* P, const float* s, float* w, float lr, flo
   if (!aligned16(w) || (g_tilde && !aligned16(g_tilde)) || (reinterpret_cast<uintptr_t>(s) & 3u))
     return TWA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int64_t min_tile = 64 * 4;   // never more waves than 256-element pieces of D
-  const int grid = persistent_grid("TWA_EXPAND_WGS_PER_CU", 3, (v.D + 4 * min_tile - 1) / (4 * min_tile));
+  const int grid = persistent_grid("TWA_EXPAND_GRID", 7);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
-  const bool reverse = env_int("TWA_EXPAND_REVERSE", 1) != 2;   // 2 switches the descending order off
-  return launch_expand_update(v, P->dtype, s, w, lr, g_tilde, grid, reverse, st);
+  return launch_expand_update(v, P->dtype, s, w, lr, g_tilde, grid, st);
 }
 
 int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* out, void* stream) {
@@ -243,9 +246,9 @@ int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* ou
   const int bits = bits_of(out->dtype);
   if (bits == 0) return TWA_ERR_DTYPE;
   if (out->D != D || out->n != n) return TWA_ERR_SHAPE;
-  int rc = check_dims(D, n, ldp, 32);
+  int rc = check_dims(D, n, ldp, TWA_F32);
   if (rc != TWA_OK) return rc;
-  rc = check_dims(D, n, out->ld, bits);
+  rc = check_dims(D, n, out->ld, out->dtype);
   if (rc != TWA_OK) return rc;
   if (!aligned16(P) || !aligned16(out->data)) return TWA_ERR_ALIGN;
   if (scaled(out->dtype)) {
@@ -286,9 +289,9 @@ int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* ou
 int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P, int64_t ldp, double* R_host,
                     void* ws, size_t ws_bytes, void* stream) {
   if (!W || !P) return TWA_ERR_NULL;
-  int rc = check_dims(D, n, ldw, 32);
+  int rc = check_dims(D, n, ldw, TWA_F32);
   if (rc != TWA_OK) return rc;
-  rc = check_dims(D, n, ldp, 32);
+  rc = check_dims(D, n, ldp, TWA_F32);
   if (rc != TWA_OK) return rc;
   if (n > D) return TWA_ERR_SHAPE;
   if (!aligned16(W) || !aligned16(P)) return TWA_ERR_ALIGN;

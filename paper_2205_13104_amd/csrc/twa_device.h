@@ -14,6 +14,13 @@ using rsrc_t = __amdgpu_buffer_rsrc_t;
 
 constexpr int kWave = 64;
 
+// Scales of the integer formats are stored "span interleaved": the scales of the blocks that cover
+// elements [kScaleSpan*t, kScaleSpan*(t+1)) of vector j are contiguous, at scale index
+// (t*n + j)*(kScaleSpan/block) + r.  A kernel tile of kScaleSpan elements then finds the scales of
+// all n vectors in one contiguous run (n * 64 B for block 128) instead of n separate 64-byte pieces.
+constexpr int kScaleSpan = 2048;
+constexpr int kScaleSpanShift = 11;
+
 // Raw (stride 0) buffer descriptor over [base, base+bytes).  A load whose byte offset lies
 // outside the range returns 0 and moves no data; a store outside it is dropped.  Every
 // streaming access in the hot kernels goes through such a descriptor, so ragged tails and
@@ -156,6 +163,14 @@ struct PView {
 __device__ __forceinline__ void split_range(int64_t total, int parts, int w, int64_t& lo, int64_t& hi) {
   lo = total * (int64_t)w / parts;
   hi = total * (int64_t)(w + 1) / parts;
+}
+
+// Wave-local ordering of LDS traffic: every lane's earlier LDS writes are visible to every lane's
+// later LDS reads of the same wave (no workgroup barrier: waves run different trip counts).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 }  // namespace twa

@@ -22,12 +22,14 @@ constexpr int kMaxGrid = 2048;
 int env_int(const char* name, int fallback);
 
 // Kernel launchers (defined next to their kernels).
-int project_tile_elems(int dtype);
-int launch_project(const PView& P, int dtype, const float* g, float* s, float* partial, int grid, hipStream_t st);
+// `max_grid`: upper bound of the persistent grid; the launchers pick the largest grid below it
+// that divides the tiles evenly.
+int launch_project(const PView& P, int dtype, const float* g, float* s, float* partial, int max_grid,
+                   hipStream_t st);
 int launch_project_batched(const PView& P, int dtype, const float* g, int64_t ldg, int k, float* s, float* partial,
-                           int grid, hipStream_t st);
-int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int grid,
-                         bool reverse, hipStream_t st);
+                           int max_grid, hipStream_t st);
+int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int max_grid,
+                         hipStream_t st);
 int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pmat& out, hipStream_t st);
 int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st);
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram, hipStream_t st);

@@ -2,8 +2,8 @@
 // model gradient projected on the basis).  A tall-skinny reduction over D that is bound by the
 // one pass over the stored P, so the kernel is a pure HBM stream:
 //
-//   * a persistent grid; workgroup b owns a contiguous, balanced range of D-tiles, so every
-//     workgroup streams the same number of bytes (+-1 tile) and they all finish together;
+//   * a persistent grid sized so that every workgroup owns the SAME number of consecutive D-tiles
+//     (only the last may own fewer): equal bytes per workgroup, so they all finish together;
 //   * the 4 waves of a workgroup share the tile (same slice of g, kept in registers) and split
 //     the n basis vectors between them, so a lane keeps <= 32 running sums in registers with
 //     compile-time indices;
@@ -24,18 +24,22 @@ namespace twa {
 // basis vector and tile.
 template <int DT, int KB, int U, int NCH, int VPL>
 __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __restrict__ g, int64_t ldg,
-                                                      int kvalid, float* __restrict__ partial, int cpw) {
+                                                      int kvalid, float* __restrict__ partial, int cpw,
+                                                      int tiles_per_wg) {
   using S = Store<DT>;
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
   constexpr int SLOTS = U * NCH;
+  static_assert(kScaleSpan % TILE == 0, "a tile never straddles two scale spans");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
   const int64_t D = P.D;
   const int64_t ntiles = (D + TILE - 1) / TILE;
-  int64_t t0, t1;
-  split_range(ntiles, (int)gridDim.x, (int)blockIdx.x, t0, t1);
+  // every workgroup owns the same number of consecutive tiles (the last one may own fewer)
+  const int64_t t0 = (int64_t)blockIdx.x * tiles_per_wg;
+  int64_t t1 = t0 + tiles_per_wg;
+  if (t1 > ntiles) t1 = ntiles;
 
   const int c0 = wave * cpw;
   int ncol = P.n - c0;
@@ -45,8 +49,8 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
   // is only partly inside, and the tail bytes are padding of the same vector (ld >= D, ld % 128 == 0)
   const uint32_t col_bytes = (uint32_t)((((D * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
   const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
-  const uint32_t nblk_valid = S::kScaled ? (uint32_t)((D + ((int64_t)1 << P.block_shift) - 1) >> P.block_shift) : 0u;
-  const int64_t nblk_ld = S::kScaled ? (P.ld >> P.block_shift) : 0;
+  const int gshift = kScaleSpanShift - P.block_shift;            // log2(scales per span and vector)
+  const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes : 0u;
   const uint32_t g_bytes = (uint32_t)(D * 4);
 
   float acc[SLOTS][KB];
@@ -93,6 +97,10 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
     }
 
     // ---- stream this wave's basis vectors over the tile ----------------------------------
+    rsrc_t rs = make_rsrc(g, 0u);
+    if constexpr (S::kScaled)
+      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, span_scale_bytes);
+    const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);   // tile offset inside its span
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
       u32x4 raw[U][VPL];
@@ -103,18 +111,19 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
         const bool valid = slot < ncol;
         const int col = valid ? c0 + slot : 0;
         const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
-        rsrc_t rs = rc;
-        if constexpr (S::kScaled)
-          rs = make_rsrc(P.scales + (int64_t)col * nblk_ld * S::kScaleBytes,
-                         valid ? nblk_valid * (uint32_t)S::kScaleBytes : 0u);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
-          const uint32_t elem = (uint32_t)e0 + (uint32_t)(v * kWave + lane) * EPV;
-          raw[u][v] = ld128_stream(rc, (uint32_t)(((uint64_t)elem * S::kBitsPerElem) >> 3));
-          if constexpr (S::kScaled)
-            sc[u][v] = load_scale<DT>(rs, (elem >> P.block_shift) * (uint32_t)S::kScaleBytes, P.gscale);
-          else
+          const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
+          raw[u][v] = ld128_stream(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
+          if constexpr (S::kScaled) {
+            // an unused column slot reads far outside the span's range and gets 0
+            const uint32_t soff =
+                valid ? (((uint32_t)col << gshift) + ((in_span + loc) >> P.block_shift)) * (uint32_t)S::kScaleBytes
+                      : 0x7fffff00u;
+            sc[u][v] = load_scale<DT>(rs, soff, P.gscale);
+          } else {
             sc[u][v] = 1.0f;
+          }
         }
       }
 #pragma unroll
@@ -166,14 +175,25 @@ __global__ __launch_bounds__(64) void project_reduce_kernel(const float* __restr
   if (lane == 0) s[idx] = (float)a;
 }
 
+// Exact division of the tiles: every workgroup gets `tiles_per_wg` consecutive tiles.
+static void divide_tiles(int64_t D, int tile, int max_grid, int* grid, int* tiles_per_wg) {
+  const int64_t ntiles = (D + tile - 1) / tile;
+  const int64_t per = (ntiles + max_grid - 1) / max_grid;
+  *tiles_per_wg = (int)per;
+  *grid = (int)((ntiles + per - 1) / per);
+}
+
 template <int DT, int KB, int VPL>
-static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kvalid, float* partial, int grid,
-                             hipStream_t st) {
+static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kvalid, float* partial, int max_grid,
+                             int* grid_out, hipStream_t st) {
   const int cpw = (P.n + 3) / 4;
+  int grid, tiles_per_wg;
+  divide_tiles(P.D, kWave * VPL * Store<DT>::kEPV, max_grid, &grid, &tiles_per_wg);
+  *grid_out = grid;
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
 #define TWA_LAUNCH(U_, NCH_)                                                                         \
   hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
-                     kvalid, partial, cpw)
+                     kvalid, partial, cpw, tiles_per_wg)
   if constexpr (KB > 1) {
     // the fused multi-gradient kernel is only used (and only built) for n <= 32
     if (cpw <= 4) TWA_LAUNCH(4, 1); else TWA_LAUNCH(4, 2);
@@ -197,23 +217,15 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   return hip_check(hipGetLastError());
 }
 
-int project_tile_elems(int dtype) {
+// k == 1 path.  `partial` holds (at most max_grid)*n floats.
+int launch_project(const PView& P, int dtype, const float* g, float* s, float* partial, int max_grid,
+                   hipStream_t st) {
+  int rc, grid = 0;
   switch (dtype) {
-    case TWA_F32: return kWave * 4 * Store<TWA_F32>::kEPV;
-    case TWA_BF16: return kWave * 2 * Store<TWA_BF16>::kEPV;
-    case TWA_I8: return kWave * 2 * Store<TWA_I8>::kEPV;
-    default: return kWave * 1 * Store<TWA_I4>::kEPV;
-  }
-}
-
-// k == 1 path.  `partial` holds grid*n floats.
-int launch_project(const PView& P, int dtype, const float* g, float* s, float* partial, int grid, hipStream_t st) {
-  int rc;
-  switch (dtype) {
-    case TWA_F32: rc = launch_project_dt<TWA_F32, 1, 4>(P, g, 0, 1, partial, grid, st); break;
-    case TWA_BF16: rc = launch_project_dt<TWA_BF16, 1, 2>(P, g, 0, 1, partial, grid, st); break;
-    case TWA_I8: rc = launch_project_dt<TWA_I8, 1, 2>(P, g, 0, 1, partial, grid, st); break;
-    case TWA_I4: rc = launch_project_dt<TWA_I4, 1, 1>(P, g, 0, 1, partial, grid, st); break;
+    case TWA_F32: rc = launch_project_dt<TWA_F32, 1, 4>(P, g, 0, 1, partial, max_grid, &grid, st); break;
+    case TWA_BF16: rc = launch_project_dt<TWA_BF16, 1, 2>(P, g, 0, 1, partial, max_grid, &grid, st); break;
+    case TWA_I8: rc = launch_project_dt<TWA_I8, 1, 2>(P, g, 0, 1, partial, max_grid, &grid, st); break;
+    case TWA_I4: rc = launch_project_dt<TWA_I4, 1, 1>(P, g, 0, 1, partial, max_grid, &grid, st); break;
     default: return TWA_ERR_DTYPE;
   }
   if (rc != TWA_OK) return rc;
@@ -227,29 +239,30 @@ int launch_project(const PView& P, int dtype, const float* g, float* s, float* p
 // launch at a time.
 template <int DT>
 static int launch_project_batched_dt(const PView& P, const float* g, int64_t ldg, int k, float* s, float* partial,
-                                     int grid, hipStream_t st) {
+                                     int max_grid, hipStream_t st) {
   if constexpr (DT != TWA_I4) {
     if (P.n <= 32) {
-      int rc = launch_project_dt<DT, TWA_MAX_K, 1>(P, g, ldg, k, partial, grid, st);
+      int grid = 0;
+      int rc = launch_project_dt<DT, TWA_MAX_K, 1>(P, g, ldg, k, partial, max_grid, &grid, st);
       if (rc != TWA_OK) return rc;
       hipLaunchKernelGGL(project_reduce_kernel, dim3(P.n * k), dim3(kWave), 0, st, partial, grid, P.n * k, s);
       return hip_check(hipGetLastError());
     }
   }
   for (int c = 0; c < k; ++c) {
-    int rc = launch_project(P, DT, g + (int64_t)c * ldg, s + (int64_t)c * P.n, partial, grid, st);
+    int rc = launch_project(P, DT, g + (int64_t)c * ldg, s + (int64_t)c * P.n, partial, max_grid, st);
     if (rc != TWA_OK) return rc;
   }
   return TWA_OK;
 }
 
 int launch_project_batched(const PView& P, int dtype, const float* g, int64_t ldg, int k, float* s, float* partial,
-                           int grid, hipStream_t st) {
+                           int max_grid, hipStream_t st) {
   switch (dtype) {
-    case TWA_F32: return launch_project_batched_dt<TWA_F32>(P, g, ldg, k, s, partial, grid, st);
-    case TWA_BF16: return launch_project_batched_dt<TWA_BF16>(P, g, ldg, k, s, partial, grid, st);
-    case TWA_I8: return launch_project_batched_dt<TWA_I8>(P, g, ldg, k, s, partial, grid, st);
-    case TWA_I4: return launch_project_batched_dt<TWA_I4>(P, g, ldg, k, s, partial, grid, st);
+    case TWA_F32: return launch_project_batched_dt<TWA_F32>(P, g, ldg, k, s, partial, max_grid, st);
+    case TWA_BF16: return launch_project_batched_dt<TWA_BF16>(P, g, ldg, k, s, partial, max_grid, st);
+    case TWA_I8: return launch_project_batched_dt<TWA_I8>(P, g, ldg, k, s, partial, max_grid, st);
+    case TWA_I4: return launch_project_batched_dt<TWA_I4>(P, g, ldg, k, s, partial, max_grid, st);
     default: return TWA_ERR_DTYPE;
   }
 }

@@ -32,13 +32,14 @@ __device__ __forceinline__ int code_of(float p, float inv, float qmax) {
 template <int DT>
 __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ P, int64_t D, int64_t ldp,
                                                        uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
-                                                       int64_t ld, int block_shift, float gscale, float inv_gscale) {
+                                                       int64_t ld, int block_shift, float gscale, float inv_gscale,
+                                                       int n) {
   constexpr int EL = (DT == TWA_I8) ? 4 : 8;
   constexpr float QMAX = (DT == TWA_I8) ? 127.0f : 7.0f;
   const int j = blockIdx.y;
   const int lanes_per_block = (1 << block_shift) / EL;
   const int64_t nvec = ld / EL;                 // lane-vectors per basis vector (padding included)
-  const int64_t nblk = ld >> block_shift;
+  const int gshift = kScaleSpanShift - block_shift;      // log2(blocks per scale span)
   const float* p = P + (int64_t)j * ldp;
   uint32_t* out = reinterpret_cast<uint32_t*>(codes + (((int64_t)j * ld * Store<DT>::kBitsPerElem) >> 3));
   for (int64_t vec = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; vec < (nvec + kWave - 1) / kWave * kWave;
@@ -86,11 +87,13 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
     if (vec < nvec) {
       out[vec] = word;
       if ((vec & (lanes_per_block - 1)) == 0) {
+        // span-interleaved: the scales of one 2048-element span of all n vectors are contiguous
         const int64_t b = i0 >> block_shift;
+        const int64_t idx = ((((b >> gshift) * n + j)) << gshift) + (b & (((int64_t)1 << gshift) - 1));
         if constexpr (DT == TWA_I8)
-          reinterpret_cast<float*>(scales)[(int64_t)j * nblk + b] = scale;
+          reinterpret_cast<float*>(scales)[idx] = scale;
         else
-          reinterpret_cast<uint16_t*>(scales)[(int64_t)j * nblk + b] = hbits;
+          reinterpret_cast<uint16_t*>(scales)[idx] = hbits;
       }
     }
   }
@@ -177,11 +180,11 @@ int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pma
       break;
     case TWA_I8:
       hipLaunchKernelGGL((quantize_kernel<TWA_I8>), dim3(grid_x_for(out.ld / 4, n), n), dim3(256), 0, st, P, D, ldp,
-                         data, scales, out.ld, shift, 1.0f, 1.0f);
+                         data, scales, out.ld, shift, 1.0f, 1.0f, n);
       break;
     case TWA_I4:
       hipLaunchKernelGGL((quantize_kernel<TWA_I4>), dim3(grid_x_for(out.ld / 8, n), n), dim3(256), 0, st, P, D, ldp,
-                         data, scales, out.ld, shift, out.gscale, 1.0f / out.gscale);
+                         data, scales, out.ld, shift, out.gscale, 1.0f / out.gscale, n);
       break;
     default:
       return TWA_ERR_DTYPE;

@@ -4,6 +4,7 @@ import numpy as np
 import torch
 
 from oracle import twa_oracle as orc
+from oracle.bridge import to_oracle  # noqa: F401  (re-exported for the tests)
 from paper_2205_13104_amd import binding as twa
 
 REL_L2_TOL = 1e-5          # s, g~, w against the fp64 oracle on the same stored P
@@ -15,26 +16,6 @@ def rel_l2(got, ref) -> float:
     ref = np.asarray(ref, dtype=np.float64).ravel()
     den = np.linalg.norm(ref)
     return float(np.linalg.norm(got - ref) / (den if den > 0 else 1.0))
-
-
-def to_oracle(pm: twa.Pmat, cols=None) -> orc.Pmat:
-    """The oracle's view of a device-resident projection matrix (optionally only some basis vectors)."""
-    data = pm.data if cols is None else pm.data[cols]
-    scales = None
-    if pm.scales is not None:
-        scales = pm.scales if cols is None else pm.scales[cols]
-    if pm.dtype == twa.F32:
-        return orc.Pmat(orc.F32, pm.D, np.ascontiguousarray(data.cpu().numpy()))
-    if pm.dtype == twa.BF16:
-        return orc.Pmat(orc.BF16, pm.D, np.ascontiguousarray(data.view(torch.int16).cpu().numpy().view(np.uint16)))
-    if pm.dtype == twa.I8:
-        return orc.Pmat(orc.I8, pm.D, np.ascontiguousarray(data.cpu().numpy()),
-                        np.ascontiguousarray(scales.cpu().numpy()), pm.block, 1.0)
-    if pm.dtype == twa.I4:
-        return orc.Pmat(orc.I4, pm.D, np.ascontiguousarray(data.cpu().numpy()),
-                        np.ascontiguousarray(scales.view(torch.int16).cpu().numpy().view(np.uint16)), pm.block,
-                        pm.gscale)
-    raise ValueError(pm.dtype)
 
 
 def random_basis_like(D, n, seed, device="cuda", ld=None):

@@ -34,9 +34,9 @@ def test_pmat_bytes_follow_the_memory_table():
     ld, db, sb = twa.pmat_bytes(twa.F32, D, n)
     assert ld == (D + 127) // 128 * 128 and db == 4 * n * ld and sb == 0
     ld, db, sb = twa.pmat_bytes(twa.I8, D, n, 128)
-    assert db == n * 8 * ld // 8 and sb == n * (ld // 128) * 4
+    assert ld == (D + 2047) // 2048 * 2048 and db == n * 8 * ld // 8 and sb == n * (ld // 128) * 4
     ld, db, sb = twa.pmat_bytes(twa.I4, D, n, 64)
-    assert db == n * 4 * ld // 8 and sb == n * (ld // 64) * 2
+    assert ld == (D + 2047) // 2048 * 2048 and db == n * 4 * ld // 8 and sb == n * (ld // 64) * 2
     ld, db, sb = twa.pmat_bytes(twa.BF16, D, n)
     assert db == 2 * n * ld
     with pytest.raises(twa.TwaError) as e:
@@ -81,11 +81,11 @@ def test_project_argument_errors():
     assert _project(_pm(), k=2, ldg=999) == twa.ERR_SHAPE    # ldg < D
     assert _project(_pm(), ws=0) == twa.ERR_WORKSPACE
     assert _project(_pm(), wsb=16) == twa.ERR_WORKSPACE
-    assert _project(_pm(dtype=twa.I8, block=128)) == twa.ERR_NULL          # scales missing
-    assert _project(_pm(dtype=twa.I8, block=100, scales=0x5000)) == twa.ERR_SHAPE
-    assert _project(_pm(dtype=twa.I8, block=256, scales=0x5000, ld=1152, D=1100)) == twa.ERR_ALIGN  # ld % block
-    assert _project(_pm(dtype=twa.I4, block=64, scales=0x5000, gscale=3.0)) == twa.ERR_SHAPE       # not a power of 2
-    assert _project(_pm(dtype=twa.I4, block=64, scales=0x5000, gscale=0.0)) == twa.ERR_SHAPE
+    assert _project(_pm(dtype=twa.I8, block=128, ld=2048)) == twa.ERR_NULL          # scales missing
+    assert _project(_pm(dtype=twa.I8, block=100, scales=0x5000, ld=2048)) == twa.ERR_SHAPE
+    assert _project(_pm(dtype=twa.I8, block=128, scales=0x5000, ld=1024)) == twa.ERR_ALIGN    # ld % 2048 for int8
+    assert _project(_pm(dtype=twa.I4, block=64, scales=0x5000, ld=2048, gscale=3.0)) == twa.ERR_SHAPE   # not 2^k
+    assert _project(_pm(dtype=twa.I4, block=64, scales=0x5000, ld=2048, gscale=0.0)) == twa.ERR_SHAPE
 
 
 def test_other_entry_points_argument_errors():
@@ -94,11 +94,11 @@ def test_other_entry_points_argument_errors():
     assert L.twa_expand_update(C.byref(pm), 0, 0x3000, 0.1, None, None) == twa.ERR_NULL
     assert L.twa_expand_update(C.byref(pm), 0x2000, 0, 0.1, None, None) == twa.ERR_NULL
     assert L.twa_expand_update(C.byref(pm), 0x2000, 0x3004, 0.1, None, None) == twa.ERR_ALIGN
-    out = _pm(dtype=twa.I8, block=128, scales=0x5000)
+    out = _pm(dtype=twa.I8, block=128, scales=0x5000, ld=2048)
     assert L.twa_quantize(None, 1000, 4, 1024, C.byref(out), None) == twa.ERR_NULL
     assert L.twa_quantize(0x6000, 1000, 5, 1024, C.byref(out), None) == twa.ERR_SHAPE     # n mismatch
     assert L.twa_quantize(0x6000, 1000, 4, 1000, C.byref(out), None) == twa.ERR_ALIGN     # ldp
-    bad = _pm(dtype=twa.I4, block=64, scales=0x5000, gscale=0.3)
+    bad = _pm(dtype=twa.I4, block=64, scales=0x5000, ld=2048, gscale=0.3)
     assert L.twa_quantize(0x6000, 1000, 4, 1024, C.byref(bad), None) == twa.ERR_SHAPE
     wsb = twa.build_basis_workspace_bytes(4)
     assert L.twa_build_basis(None, 1000, 4, 1024, 0x7000, 1024, None, 0x8000, wsb, None) == twa.ERR_NULL

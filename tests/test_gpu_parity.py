@@ -30,11 +30,11 @@ def test_quantize_i8_bit_exact(D, n, block):
     say("quantize_i8", D, n, block)
     P = random_basis_like(D, n, seed=D + n)
     P[0, 128:256] = 0.0 if D > 256 else P[0, 128:256]          # an all-zero block
-    ref = orc.quantize_i8(P.cpu().numpy(), D=D, block=block, ld=P.shape[1])
     pm = twa.quantize(P, D, twa.I8, block=block)
     torch.cuda.synchronize()
-    assert pm.ld == ref.ld
-    assert np.array_equal(pm.scales.cpu().numpy().view(np.uint32), ref.scales.view(np.uint32))
+    assert pm.ld % 2048 == 0 and pm.ld - D < 2048
+    ref = orc.quantize_i8(P.cpu().numpy(), D=D, block=block, ld=pm.ld)
+    assert np.array_equal(pm.scales_by_vector().cpu().numpy().view(np.uint32), ref.scales.view(np.uint32))
     assert np.array_equal(pm.data.cpu().numpy(), ref.data)
 
 
@@ -50,9 +50,9 @@ def test_quantize_i8_bit_exact_near_ties(mag):
     P[:, ::3] = base[:, ::3]
     P[:, 0] = amax
     P = (P * mag).contiguous().cuda()
-    ref = orc.quantize_i8(P.cpu().numpy())
     pm = twa.quantize(P, D, twa.I8)
-    assert np.array_equal(pm.scales.cpu().numpy().view(np.uint32), ref.scales.view(np.uint32))
+    ref = orc.quantize_i8(P.cpu().numpy(), ld=pm.ld)
+    assert np.array_equal(pm.scales_by_vector().cpu().numpy().view(np.uint32), ref.scales.view(np.uint32))
     assert np.array_equal(pm.data.cpu().numpy(), ref.data)
 
 
@@ -65,15 +65,15 @@ def test_quantize_i4_bit_exact(D, n, block):
         P[0, 128:256] = 0.0
     Pn = P.cpu().numpy()
     gs = orc.gscale_i4(Pn, D)
-    ref = orc.quantize_i4(Pn, D=D, block=block, ld=P.shape[1], gscale=gs)
     pm = twa.quantize(P, D, twa.I4, block=block)              # gscale chosen by the library
+    ref = orc.quantize_i4(Pn, D=D, block=block, ld=pm.ld, gscale=gs)
     assert pm.gscale == gs
-    assert np.array_equal(pm.scales.view(torch.int16).cpu().numpy().view(np.uint16), ref.scales)
+    assert np.array_equal(pm.scales_by_vector().view(torch.int16).cpu().numpy().view(np.uint16), ref.scales)
     assert np.array_equal(pm.data.cpu().numpy(), ref.data)
     # caller-supplied power of two: no synchronisation inside, same rules
     pm2 = twa.quantize(P, D, twa.I4, block=block, gscale=gs * 4)
-    ref2 = orc.quantize_i4(Pn, D=D, block=block, ld=P.shape[1], gscale=gs * 4)
-    assert np.array_equal(pm2.scales.view(torch.int16).cpu().numpy().view(np.uint16), ref2.scales)
+    ref2 = orc.quantize_i4(Pn, D=D, block=block, ld=pm.ld, gscale=gs * 4)
+    assert np.array_equal(pm2.scales_by_vector().view(torch.int16).cpu().numpy().view(np.uint16), ref2.scales)
     assert np.array_equal(pm2.data.cpu().numpy(), ref2.data)
 
 
