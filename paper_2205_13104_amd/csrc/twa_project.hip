@@ -61,9 +61,9 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
 
   for (int64_t t = t0; t < t1; ++t) {
     const int64_t e0 = t * TILE;
-    const bool ragged = (e0 + TILE > D);   // uniform: only the last tile of all
 
-    // ---- this lane's slice of the gradient(s) ------------------------------------------
+    // ---- this lane's slice of the gradient(s); the descriptor ends at element D, and the range
+    //      check is per dword, so elements past the ragged end arrive as 0 --------------------
     float gs[KB][VPL][EPV];
     float gcorr[KB][VPL];
 #pragma unroll
@@ -77,11 +77,6 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
           const u32x4 x = ld128(rg, (elem + 4u * q) * 4u);
 #pragma unroll
           for (int r = 0; r < 4; ++r) gs[c][v][4 * q + r] = as_f32(x[r]);
-        }
-        if (ragged) {
-#pragma unroll
-          for (int e = 0; e < EPV; ++e)
-            if ((int64_t)elem + e >= D) gs[c][v][e] = 0.0f;
         }
         if constexpr (DT == TWA_I4) {
           float sum = 0.0f;

@@ -6,8 +6,8 @@ produced with torch's seeded generators on the requested device (CPU or the GPU)
 side that did not generate them receives a copy, so both sides always see identical bits.
 
 The paper averages checkpoints of one training trajectory (one per epoch, n = 60..100,
-Sec. 5.1) or of several fine-tuning runs from one pre-trained model (Sec. 5.3) and notes
-that such weights are almost collinear (pairwise cosine ~0.99, Sec. 5.4.4).  The recipes
+Sec. 5.1) or of several fine-tuning runs from one pre-trained model (Sec. 5.2) and notes
+that such weights are almost collinear (pairwise cosine ~0.99, Sec. 5.3.4).  The recipes
 below reproduce the SHAPES (D = parameter count, n = number of checkpoints) and that
 correlation structure; none of the paper's data sets or trained weights is involved.
 

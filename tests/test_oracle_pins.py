@@ -446,7 +446,7 @@ def test_memory_formulas_of_the_paper():
                 rows[k.strip()] = float(v)
     n, D = int(rows["n"]), int(rows["D"])
     # 4nD bytes at 32 bits and nBD/8 at B bits (Sec. 4.6, table of memory required for P); the paper measures +6000 MB and +750 MB
-    # of device memory for fp32 and 4-bit P at this shape (Sec. 5.4.2, DDP table, one GPU).
+    # of device memory for fp32 and 4-bit P at this shape (Sec. 5.3.2, DDP table, one GPU).
     fp32_bytes = orc.pmat_f32(np.zeros((1, 128), dtype=np.float32)).data.itemsize * n * D
     assert fp32_bytes == 4 * n * D
     assert abs(fp32_bytes / 2 ** 20 - rows["fp32_extra_MB"]) / rows["fp32_extra_MB"] < 0.03
