@@ -1,0 +1,166 @@
+"""Parity at the benchmark configurations' FULL sizes, in the launch configuration bench.py times.
+
+The oracle cannot evaluate 2.5e9 products element by element in test time, so it computes sampled
+outputs one by one on the stored P the GPU used: a few coefficients s_j over the whole of D, and
+g~ / w on sampled 128-row blocks (first, last and random ones) for all n vectors.  Orthonormality
+of the full-size basis is checked with an fp64 library matmul over row chunks."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import twa_oracle as orc
+from oracle.bridge import to_oracle
+from paper_2205_13104_amd import binding as twa
+from paper_2205_13104_amd import synth
+from tests.gpu_common import ORTHO_TOL, REL_L2_TOL, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def gram_fp64(P, D, chunk=1 << 21):
+    n = P.shape[0]
+    G = torch.zeros((n, n), dtype=torch.float64, device=P.device)
+    for a in range(0, D, chunk):
+        x = P[:, a:min(D, a + chunk)].double()
+        G += x @ x.T
+    return G.cpu().numpy()
+
+
+def sampled_blocks_pmat(pm, block_ids, block):
+    """Oracle view of rows [b*block, (b+1)*block) for b in block_ids (all n vectors): bytes only."""
+    rows = torch.cat([torch.arange(b * block, (b + 1) * block) for b in block_ids]).to(pm.data.device)
+    nrows = int(rows.numel())
+    if pm.dtype == twa.F32:
+        return rows, orc.Pmat(orc.F32, nrows, np.ascontiguousarray(pm.data[:, rows].cpu().numpy()))
+    if pm.dtype == twa.BF16:
+        d = pm.data[:, rows].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return rows, orc.Pmat(orc.BF16, nrows, np.ascontiguousarray(d))
+    if pm.dtype == twa.I8:
+        sc = pm.scales_by_vector()[:, torch.tensor(block_ids, device=pm.data.device)].cpu().numpy()
+        return rows, orc.Pmat(orc.I8, nrows, np.ascontiguousarray(pm.data[:, rows].cpu().numpy()),
+                              np.ascontiguousarray(sc), block, 1.0)
+    raise ValueError(pm.dtype)
+
+
+def check_step_sampled(pm, D, n, g, w, lr, seed, cols, nblocks=48, block=128):
+    ws = twa.Workspace(twa.project_workspace_bytes(n))
+    s = torch.empty(n, device="cuda")
+    w0 = w.clone()
+    gt = torch.empty(D, device="cuda")
+    twa.project(pm, g, s, ws)
+    twa.expand_update(pm, s, w, lr, gt)
+    torch.cuda.synchronize()
+    # (1) sampled coefficients over the whole of D
+    so = orc.project(to_oracle(pm, cols=cols), g.cpu().numpy().astype(np.float64))
+    e_s = rel_l2(s[cols].cpu().numpy(), so)
+    say("  rel_l2 s[sampled]", e_s)
+    assert e_s <= REL_L2_TOL
+    # (2) g~ and w on sampled whole blocks: first, last full, the ragged last one, and random ones
+    nb = D // block
+    r = np.random.default_rng(seed)
+    ids = sorted(set([0, 1, nb - 1] + r.integers(0, nb, size=nblocks).tolist()))
+    rows, po = sampled_blocks_pmat(pm, ids, block)
+    wo = w0[rows].cpu().numpy().astype(np.float64)
+    gto = orc.expand_update(po, s.cpu().numpy().astype(np.float64), wo, lr, want_gt=True)
+    e_gt, e_w = rel_l2(gt[rows].cpu().numpy(), gto), rel_l2(w[rows].cpu().numpy(), wo)
+    say("  rel_l2 g~[sampled]", e_gt, "w[sampled]", e_w)
+    assert e_gt <= REL_L2_TOL and e_w <= REL_L2_TOL
+    # (3) the ragged tail (rows past the last full block) one by one
+    if D % block:
+        tail = torch.arange(nb * block, D, device="cuda")
+        dense_tail = to_oracle_tail(pm, nb * block, D)
+        gtail = s.cpu().numpy().astype(np.float64) @ dense_tail
+        assert rel_l2(gt[tail].cpu().numpy(), gtail) <= REL_L2_TOL
+    # (4) properties that hold at any size: nothing outside [0, D) was written, all of w moved
+    assert torch.isfinite(w).all() and torch.isfinite(gt).all()
+    return s
+
+
+def to_oracle_tail(pm, lo, hi):
+    """(n, hi-lo) exact stored values of the last, partial block, through the oracle's own dequantiser."""
+    if pm.dtype in (twa.I8,):
+        blk = lo // pm.block
+        codes = np.zeros((pm.n, pm.block), dtype=np.int8)
+        codes[:, :hi - lo] = pm.data[:, lo:hi].cpu().numpy()
+        sc = pm.scales_by_vector()[:, blk:blk + 1].cpu().numpy()
+        return orc.Pmat(orc.I8, hi - lo, codes, np.ascontiguousarray(sc), pm.block, 1.0).dense()
+    if pm.dtype == twa.F32:
+        return orc.Pmat(orc.F32, hi - lo, np.ascontiguousarray(pm.data[:, lo:hi].cpu().numpy())).dense()
+    d = pm.data[:, lo:hi].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return orc.Pmat(orc.BF16, hi - lo, np.ascontiguousarray(d)).dense()
+
+
+def test_imagenet_resnet50_int8_full_size():
+    wl = synth.WORKLOADS["imagenet_resnet50"]
+    D, n = wl.D, wl.n
+    say("full size", wl.name, D, n)
+    W = synth.checkpoints(wl, seed=0, device="cuda")
+    w = W[:, :D].mean(dim=0).contiguous()
+    P, R = twa.build_basis(W, D, out=W)
+    G = gram_fp64(P, D)
+    ortho = np.max(np.abs(G - np.eye(n)))
+    say("  max|PtP-I|", ortho)
+    assert ortho <= ORTHO_TOL
+    assert np.all(np.diag(R.numpy()) > 0) and np.max(np.abs(np.tril(R.numpy(), -1))) == 0.0
+    pm = twa.quantize(P, D, twa.I8)
+    # codes and scales bit-exact on sampled vectors (whole vectors through the oracle's quantiser)
+    for j in (0, 63, n - 1):
+        ref = orc.quantize_i8(P[j:j + 1].cpu().numpy(), D=D, ld=pm.ld)
+        assert np.array_equal(pm.data[j].cpu().numpy(), ref.data[0])
+        assert np.array_equal(pm.scales_by_vector()[j].cpu().numpy().view(np.uint32), ref.scales[0].view(np.uint32))
+    del W, P
+    torch.cuda.empty_cache()
+    g = synth.gradient(D, wl.sigma_g, seed=0, step=0, device="cuda")
+    s1 = check_step_sampled(pm, D, n, g, w, wl.lr, seed=1, cols=[0, 57, n - 1])
+    # rerun determinism at full size
+    s2 = twa.project(pm, g)
+    assert torch.equal(s1, s2)
+
+
+def test_cifar_resnet18_fp32_full_size():
+    wl = synth.WORKLOADS["cifar_resnet18"]
+    D, n = wl.D, wl.n
+    say("full size", wl.name, D, n)
+    W = synth.checkpoints(wl, seed=0, device="cuda")
+    w = W[:, :D].mean(dim=0).contiguous()
+    P, _ = twa.build_basis(W, D, out=W)
+    ortho = np.max(np.abs(gram_fp64(P, D) - np.eye(n)))
+    say("  max|PtP-I|", ortho)
+    assert ortho <= ORTHO_TOL
+    pm = twa.wrap_f32(P, D)
+    g = synth.gradient(D, wl.sigma_g, seed=0, step=0, device="cuda")
+    check_step_sampled(pm, D, n, g, w, wl.lr, seed=2, cols=[0, 31, n - 1])
+
+
+def test_vit_b16_bf16_batched_full_size():
+    wl = synth.WORKLOADS["vit_b16_finetune"]
+    D, n, k = wl.D, wl.n, wl.k
+    say("full size", wl.name, D, n, "k", k)
+    W = synth.checkpoints(wl, seed=0, device="cuda")
+    P, _ = twa.build_basis(W, D, out=W)
+    ortho = np.max(np.abs(gram_fp64(P, D) - np.eye(n)))
+    say("  max|PtP-I|", ortho)
+    assert ortho <= ORTHO_TOL
+    pm = twa.quantize(P, D, twa.BF16)
+    ref0 = orc.to_bf16(P[3:4].cpu().numpy(), D=D, ld=pm.ld)
+    assert np.array_equal(pm.data[3].view(torch.int16).cpu().numpy().view(np.uint16), ref0.data[0])
+    del W, P
+    torch.cuda.empty_cache()
+    ldg = (D + 3) // 4 * 4
+    G = synth.gradient(D, wl.sigma_g, seed=0, step=0, device="cuda", k=k, ldg=ldg)
+    S = twa.project(pm, G)
+    cols = [0, 11, n - 1]
+    po = to_oracle(pm, cols=cols)
+    for c in (0, k - 1):
+        so = orc.project(po, G[c, :D].cpu().numpy().astype(np.float64))
+        e = rel_l2(S[c, cols].cpu().numpy(), so)
+        say("  rel_l2 S[%d, sampled]" % c, e)
+        assert e <= REL_L2_TOL
+    # every gradient alone reproduces its row of the batched result
+    for c in (1, 5):
+        sc = twa.project(pm, G[c, :D].contiguous())
+        assert rel_l2(S[c].cpu().numpy(), sc.cpu().numpy()) <= 5e-6   # two summation orders, each within the bar
