@@ -111,8 +111,11 @@ template <> __device__ __forceinline__ void decode<TWA_I8>(const u32x4& v, float
 template <> __device__ __forceinline__ void decode<TWA_I4>(const u32x4& v, float* raw) {
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const uint32_t lo = v[q] & 0x0f0f0f0fu;               // even elements: q+8
-    const uint32_t hi = v[q] & 0xf0f0f0f0u;               // odd elements: 16*(q+8)
+    uint32_t lo = v[q] & 0x0f0f0f0fu;                     // even elements: q+8
+    uint32_t hi = v[q] & 0xf0f0f0f0u;                     // odd elements: 16*(q+8)
+    // keep the two masked words as they are: otherwise the optimiser re-derives every nibble
+    // from v[q] with a bit-field extract of its own (3 instructions per element instead of 2)
+    asm volatile("" : "+v"(lo), "+v"(hi));
     raw[8 * q + 0] = (float)(lo & 0xff);
     raw[8 * q + 1] = (float)(hi & 0xff);
     raw[8 * q + 2] = (float)((lo >> 8) & 0xff);

@@ -9,77 +9,47 @@
 //     basis vectors, U of them per loop trip (U*VPL 128-bit non-temporal loads in flight);
 //   * s_j is wave-uniform (scalar loads); the block scale is folded into t = s_j * scale once per
 //     (lane-vector, basis vector), then one convert + one FMA per stored element;
-//   * the tile's slice of w is fetched at the START of the tile with fully coalesced loads, the
-//     finished sums are transposed through a wave-private LDS buffer into the same coalesced
-//     shape, and w (and optionally g~) is written with full-line stores (fused update);
+//   * the finished sums are transposed through a wave-private LDS buffer into a fully coalesced
+//     shape, w is read, updated with one FMA per element and written with full-line stores
+//     (fused update); g~ is stored through a descriptor that is empty when it is not wanted;
 //   * buffer descriptors give the ragged end of D and the column remainder for free.
+//
+// Writing w is the expensive part: on MI355X a thin stream of writes mixed into a saturating read
+// stream costs several times its share of the bytes (102 MB of writes spread over the kernel
+// cost as much as ~600 MB of reads), whereas the same bytes written in one burst when the reads
+// are over cost about what their size suggests.  The kernel therefore keeps the finished sums
+// of its LAST `HOLD` rounds of tiles in registers and writes them all at the very end; only
+// earlier rounds (if the matrix is so long that a wave owns more tiles than it can hold) are
+// written as they complete.  One more round is held in LDS.
 #include "twa_device.h"
 #include "twa_host.h"
 
 namespace twa {
 
-template <int DT> struct ExpandCfg;
-template <> struct ExpandCfg<TWA_F32> { static constexpr int U = 8, VPL = 4; };
-template <> struct ExpandCfg<TWA_BF16> { static constexpr int U = 8, VPL = 2; };
-template <> struct ExpandCfg<TWA_I8> { static constexpr int U = 4, VPL = 2; };
-template <> struct ExpandCfg<TWA_I4> { static constexpr int U = 4, VPL = 1; };
-
-int expand_tile_elems(int dtype) {
-  switch (dtype) {
-    case TWA_F32: return kWave * ExpandCfg<TWA_F32>::VPL * Store<TWA_F32>::kEPV;
-    case TWA_BF16: return kWave * ExpandCfg<TWA_BF16>::VPL * Store<TWA_BF16>::kEPV;
-    case TWA_I8: return kWave * ExpandCfg<TWA_I8>::VPL * Store<TWA_I8>::kEPV;
-    default: return kWave * ExpandCfg<TWA_I4>::VPL * Store<TWA_I4>::kEPV;
-  }
-}
-
-template <int DT>
-__global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float* __restrict__ s,
-                                                            float* __restrict__ w, float lr,
-                                                            float* __restrict__ g_tilde, int tiles_per_wg) {
+template <int DT, int U, int VPL>
+struct Expander {
   using S = Store<DT>;
-  constexpr int EPV = S::kEPV;
-  constexpr int U = ExpandCfg<DT>::U;
-  constexpr int VPL = ExpandCfg<DT>::VPL;
-  constexpr int TILE = kWave * VPL * EPV;
-  constexpr int VEC = kWave * EPV;               // elements one wave-vector covers
-  constexpr int ROW = EPV + 4;                   // padded LDS row of one lane (bank-conflict free)
-  static_assert(!S::kScaled || TILE == kScaleSpan, "integer formats: one tile = one scale span");
-  __shared__ float tbuf[4][kWave * ROW];
+  static constexpr int EPV = S::kEPV;
+  static constexpr int TILE = kWave * VPL * EPV;
+  static constexpr int VEC = kWave * EPV;               // elements one wave-vector covers
+  static constexpr int ROW = EPV + 4;                   // padded LDS row of one lane (conflict free)
+  static constexpr int SPANS = TILE > kScaleSpan ? TILE / kScaleSpan : 1;
+  static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
 
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const PView& P;
+  const float* __restrict__ s;
+  int lane;
+  uint32_t col_bytes;
+  int64_t ld_bytes;
+  int gshift;
+  uint32_t span_scale_bytes;
+  rsrc_t rw, rgt;
+  float lr;
+  float* tb;                                            // this wave's LDS transpose buffer
 
-  const int64_t D = P.D;
-  const int n = P.n;
-  const int64_t ntiles = (D + TILE - 1) / TILE;
-  const int64_t wg_first = (int64_t)blockIdx.x * tiles_per_wg;
-  int64_t wg_end = wg_first + tiles_per_wg;
-  if (wg_end > ntiles) wg_end = ntiles;
-
-  // bytes of one stored vector, rounded up to whole dwords: the range check drops a dword that
-  // is only partly inside, and the tail bytes are padding of the same vector (ld >= D, ld % 128 == 0)
-  const uint32_t col_bytes = (uint32_t)((((D * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
-  const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
-  const int gshift = kScaleSpanShift - P.block_shift;            // log2(scales per span and vector)
-  const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)n << gshift) * (uint32_t)S::kScaleBytes : 0u;
-  const uint32_t w_bytes = (uint32_t)(D * 4);
-  const rsrc_t rw = make_rsrc(w, w_bytes);
-  const rsrc_t rgt = make_rsrc(g_tilde, g_tilde ? w_bytes : 0u);
-  float* tb = tbuf[wave];
-
-  for (int64_t t = wg_first + wave; t < wg_end; t += 4) {
-    const int64_t e0 = t * TILE;
-
-    // ---- this tile's slice of w, coalesced: lane l holds floats (q*64 + l)*4 .. +3 of each vector
-    u32x4 wv[VPL][EPV / 4];
-#pragma unroll
-    for (int v = 0; v < VPL; ++v)
-#pragma unroll
-      for (int q = 0; q < EPV / 4; ++q)
-        wv[v][q] = ld128(rw, ((uint32_t)e0 + (uint32_t)(v * VEC + (q * kWave + lane) * 4)) * 4u);
-
-    float acc[VPL][EPV];
+  // sums of tile e0 over all basis vectors (for I4 the bias / nibble corrections are applied at the end)
+  __device__ __forceinline__ void accumulate(int64_t e0, float (&acc)[VPL][EPV]) const {
+    const int n = P.n;
     float tsum[VPL];
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
@@ -89,7 +59,8 @@ __global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float
     }
     rsrc_t rs = rw;
     if constexpr (S::kScaled)
-      rs = make_rsrc(P.scales + t * (int64_t)span_scale_bytes, span_scale_bytes);
+      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, SPANS * span_scale_bytes);
+    const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);   // tile offset inside its first span
 
     for (int j0 = 0; j0 < n; j0 += U) {
       u32x4 raw[U][VPL];
@@ -106,9 +77,13 @@ __global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float
           const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
           raw[u][v] = ld128_stream(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
           if constexpr (S::kScaled) {
-            // an unused column slot reads far outside the span's range and gets 0
-            const uint32_t soff = valid ? (((uint32_t)col << gshift) + (loc >> P.block_shift)) * (uint32_t)S::kScaleBytes
-                                        : 0x7fffff00u;
+            // scale index inside the tile's run of spans: [span][vector][block in span];
+            // an unused column slot reads far outside the range and gets 0
+            const uint32_t pos = in_span + loc;
+            const uint32_t soff =
+                valid ? ((((pos >> kScaleSpanShift) * (uint32_t)n + (uint32_t)col) << gshift) +
+                         ((pos & (uint32_t)(kScaleSpan - 1)) >> P.block_shift)) * (uint32_t)S::kScaleBytes
+                      : 0x7fffff00u;
             tj[u][v] = sj * load_scale<DT>(rs, soff, P.gscale);
           } else {
             tj[u][v] = sj;
@@ -127,79 +102,194 @@ __global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float
         }
       }
     }
-
-    // ---- epilogue: transpose the sums into the coalesced shape, update w, store --------------
+    if constexpr (DT == TWA_I4) {
+      // even nibbles were decoded as q+8, odd nibbles as 16*(q+8)
 #pragma unroll
-    for (int v = 0; v < VPL; ++v) {
-      if constexpr (DT == TWA_I4) {
-        // even nibbles were decoded as q+8, odd nibbles as 16*(q+8)
+      for (int v = 0; v < VPL; ++v)
 #pragma unroll
         for (int e = 0; e < EPV; ++e)
           acc[v][e] = ((e & 1) ? acc[v][e] * 0.0625f : acc[v][e]) - 8.0f * tsum[v];
-      }
-      if constexpr (EPV > 4) {
+    }
+  }
+
+  // coalesced position of this lane's q-th 128-bit piece of wave-vector v: floats (q*64 + lane)*4 ..
+  __device__ __forceinline__ uint32_t piece(int64_t e0, int v, int q) const {
+    return (uint32_t)e0 + (uint32_t)(v * VEC + (q * kWave + lane) * 4);
+  }
+
+  __device__ __forceinline__ void load_w(int64_t e0, u32x4 (&wv)[VPL][EPV / 4]) const {
 #pragma unroll
-        for (int q = 0; q < EPV / 4; ++q)
-          *reinterpret_cast<float4*>(tb + lane * ROW + 4 * q) =
-              make_float4(acc[v][4 * q], acc[v][4 * q + 1], acc[v][4 * q + 2], acc[v][4 * q + 3]);
-        wave_lds_sync();
-      }
+    for (int v = 0; v < VPL; ++v)
 #pragma unroll
-      for (int q = 0; q < EPV / 4; ++q) {
-        const uint32_t m = (uint32_t)(q * kWave + lane) * 4u;       // element inside the wave-vector
-        float4 gt;
-        if constexpr (EPV > 4)
-          gt = *reinterpret_cast<const float4*>(tb + (m / EPV) * ROW + (m % EPV));
-        else
-          gt = make_float4(acc[v][0], acc[v][1], acc[v][2], acc[v][3]);
-        const uint32_t el = (uint32_t)e0 + (uint32_t)(v * VEC) + m;
-        const uint32_t off = el * 4u;
-        const u32x4 gv = {as_u32(gt.x), as_u32(gt.y), as_u32(gt.z), as_u32(gt.w)};
-        u32x4 nw;
-        nw[0] = as_u32(__builtin_fmaf(-lr, gt.x, as_f32(wv[v][q][0])));
-        nw[1] = as_u32(__builtin_fmaf(-lr, gt.y, as_f32(wv[v][q][1])));
-        nw[2] = as_u32(__builtin_fmaf(-lr, gt.z, as_f32(wv[v][q][2])));
-        nw[3] = as_u32(__builtin_fmaf(-lr, gt.w, as_f32(wv[v][q][3])));
-        if ((int64_t)el + 4 <= D) {
-          st128(rw, off, nw);
-          st128(rgt, off, gv);          // empty descriptor when g~ is not wanted: dropped
-        } else {
+      for (int q = 0; q < EPV / 4; ++q) wv[v][q] = ld128(rw, piece(e0, v, q) * 4u);
+  }
+
+  // lane's EPV sums of one wave-vector -> its padded row of an LDS buffer of kWave*ROW floats
+  __device__ __forceinline__ void rows_to_lds(const float (&a)[EPV], float* buf) const {
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if ((int64_t)el + r < D) {
-              st32(rw, off + 4u * r, nw[r]);
-              st32(rgt, off + 4u * r, gv[r]);
-            }
+    for (int q = 0; q < EPV / 4; ++q)
+      *reinterpret_cast<float4*>(buf + lane * ROW + 4 * q) = make_float4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
+  }
+
+  // q-th coalesced 128-bit piece of wave-vector v: w <- w - lr * g~, store w (and g~)
+  __device__ __forceinline__ void finish_piece(int64_t e0, int v, int q, float4 gt, const u32x4& wq) const {
+    const int64_t D = P.D;
+    const uint32_t el = piece(e0, v, q);
+    const uint32_t off = el * 4u;
+    const u32x4 gv = {as_u32(gt.x), as_u32(gt.y), as_u32(gt.z), as_u32(gt.w)};
+    u32x4 nw;
+    nw[0] = as_u32(__builtin_fmaf(-lr, gt.x, as_f32(wq[0])));
+    nw[1] = as_u32(__builtin_fmaf(-lr, gt.y, as_f32(wq[1])));
+    nw[2] = as_u32(__builtin_fmaf(-lr, gt.z, as_f32(wq[2])));
+    nw[3] = as_u32(__builtin_fmaf(-lr, gt.w, as_f32(wq[3])));
+    if ((int64_t)el + 4 <= D) {
+      st128(rw, off, nw);
+      st128(rgt, off, gv);          // empty descriptor when g~ is not wanted: dropped
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if ((int64_t)el + r < D) {
+          st32(rw, off + 4u * r, nw[r]);
+          st32(rgt, off + 4u * r, gv[r]);
         }
+    }
+  }
+
+  // all pieces of wave-vector v, the sums read back from LDS rows in the coalesced (transposed) order
+  __device__ __forceinline__ void finish_from_rows(int64_t e0, int v, const float* buf,
+                                                   const u32x4 (&wq)[EPV / 4]) const {
+#pragma unroll
+    for (int q = 0; q < EPV / 4; ++q) {
+      const uint32_t m = (uint32_t)(q * kWave + lane) * 4u;       // element inside the wave-vector
+      const float4 gt = *reinterpret_cast<const float4*>(buf + (m / EPV) * ROW + (m % EPV));
+      finish_piece(e0, v, q, gt, wq[q]);
+    }
+  }
+
+  // transpose the sums of a tile into the coalesced shape and finish it
+  __device__ __forceinline__ void update_store(int64_t e0, const float (&acc)[VPL][EPV],
+                                               const u32x4 (&wv)[VPL][EPV / 4]) const {
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      if constexpr (EPV > 4) {
+        rows_to_lds(acc[v], tb);
+        wave_lds_sync();
+        finish_from_rows(e0, v, tb, wv[v]);
+        wave_lds_sync();
+      } else {
+        finish_piece(e0, v, 0, make_float4(acc[v][0], acc[v][1], acc[v][2], acc[v][3]), wv[v][0]);
       }
-      if constexpr (EPV > 4) wave_lds_sync();
+    }
+  }
+};
+
+// A wave owns `rounds` tiles: tile index = first tile of the workgroup + 4*round + wave.  The
+// sums of the last HOLD of them are kept in registers, those of the one before in LDS (LH = 1), and
+// all of them are written when the wave has finished reading.
+template <int DT, int U, int VPL, int HOLD, int LH>
+__global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float* __restrict__ s,
+                                                            float* __restrict__ w, float lr,
+                                                            float* __restrict__ g_tilde, int rounds) {
+  using X = Expander<DT, U, VPL>;
+  constexpr int EPV = X::EPV;
+  __shared__ float tbuf[4][kWave * X::ROW];
+  __shared__ float lhold[LH ? 4 : 1][LH ? VPL : 1][LH ? kWave * X::ROW : 1];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t D = P.D;
+  const int64_t ntiles = (D + X::TILE - 1) / X::TILE;
+  const int64_t first = (int64_t)blockIdx.x * 4 * rounds + wave;
+  const uint32_t w_bytes = (uint32_t)(D * 4);
+  // bytes of one stored vector, rounded up to whole dwords: the range check drops a dword that
+  // is only partly inside, and the tail bytes are padding of the same vector (ld >= D, ld % 128 == 0)
+  const X x{P,
+            s,
+            lane,
+            (uint32_t)((((D * X::S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3),
+            (P.ld * X::S::kBitsPerElem) >> 3,
+            kScaleSpanShift - P.block_shift,
+            X::S::kScaled ? ((uint32_t)P.n << (kScaleSpanShift - P.block_shift)) * (uint32_t)X::S::kScaleBytes : 0u,
+            make_rsrc(w, w_bytes),
+            make_rsrc(g_tilde, g_tilde ? w_bytes : 0u),
+            lr,
+            tbuf[wave]};
+
+  // ---- early rounds (only when a wave owns more tiles than it can hold): written as they finish
+  const int early = rounds > HOLD + LH ? rounds - HOLD - LH : 0;
+  for (int r = 0; r < early; ++r) {
+    const int64_t t = first + 4 * (int64_t)r;
+    if (t >= ntiles) break;
+    const int64_t e0 = t * X::TILE;
+    u32x4 wv[VPL][EPV / 4];
+    x.load_w(e0, wv);                     // issued before the stream of P, consumed after it
+    float acc[VPL][EPV];
+    x.accumulate(e0, acc);
+    x.update_store(e0, acc, wv);
+  }
+
+  // ---- the round before the last HOLD ones: its sums wait in LDS ...
+  const int64_t t_lds = first + 4 * (int64_t)early;
+  const bool lds_tile = LH && rounds > HOLD && t_lds < ntiles;
+  if (lds_tile) {
+    float acc[VPL][EPV];
+    x.accumulate(t_lds * X::TILE, acc);
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) x.rows_to_lds(acc[v], lhold[wave][v]);
+  }
+  const int reg0 = (LH && rounds > HOLD) ? early + 1 : early;      // first round whose sums stay in registers
+
+  // ---- ... the last rounds: their sums stay in registers ...
+  float held[HOLD][VPL][EPV];
+#pragma unroll
+  for (int i = 0; i < HOLD; ++i) {
+    const int64_t t = first + 4 * (int64_t)(reg0 + i);
+    if (reg0 + i < rounds && t < ntiles) x.accumulate(t * X::TILE, held[i]);
+  }
+  // ---- ... and everything is written in one burst once this wave has finished reading
+  if (lds_tile) {
+    const int64_t e0 = t_lds * X::TILE;
+    u32x4 wv[VPL][EPV / 4];
+    x.load_w(e0, wv);
+    wave_lds_sync();
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) x.finish_from_rows(e0, v, lhold[wave][v], wv[v]);
+  }
+#pragma unroll
+  for (int i = 0; i < HOLD; ++i) {
+    const int64_t t = first + 4 * (int64_t)(reg0 + i);
+    if (reg0 + i < rounds && t < ntiles) {
+      const int64_t e0 = t * X::TILE;
+      u32x4 wv[VPL][EPV / 4];
+      x.load_w(e0, wv);
+      x.update_store(e0, held[i], wv);
     }
   }
 }
 
+template <int DT, int U, int VPL, int HOLD, int LH>
+static void launch_expand_cfg(const PView& P, const float* s, float* w, float lr, float* g_tilde, int max_grid,
+                              hipStream_t st) {
+  const int tile = kWave * VPL * Store<DT>::kEPV;
+  const int64_t ntiles = (P.D + tile - 1) / tile;
+  const int64_t rounds = (ntiles + 4 * (int64_t)max_grid - 1) / (4 * (int64_t)max_grid);   // tiles per wave
+  const int grid = (int)((ntiles + 4 * rounds - 1) / (4 * rounds));
+  hipLaunchKernelGGL((expand_update_kernel<DT, U, VPL, HOLD, LH>), dim3(grid), dim3(256), 0, st, P, s, w, lr, g_tilde,
+                     (int)rounds);
+}
+
 int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int max_grid,
                          hipStream_t st) {
-  const int tile = expand_tile_elems(dtype);
-  const int64_t ntiles = (P.D + tile - 1) / tile;
-  int64_t tiles_per_wg = (ntiles + max_grid - 1) / max_grid;
-  tiles_per_wg = (tiles_per_wg + 3) / 4 * 4;                      // whole rounds of the 4 waves
-  const int grid = (int)((ntiles + tiles_per_wg - 1) / tiles_per_wg);
-  const int tpw = (int)tiles_per_wg;
+  const int lh = env_int("TWA_EXPAND_LH", 1);
   switch (dtype) {
-    case TWA_F32:
-      hipLaunchKernelGGL((expand_update_kernel<TWA_F32>), dim3(grid), dim3(256), 0, st, P, s, w, lr, g_tilde, tpw);
-      break;
-    case TWA_BF16:
-      hipLaunchKernelGGL((expand_update_kernel<TWA_BF16>), dim3(grid), dim3(256), 0, st, P, s, w, lr, g_tilde, tpw);
-      break;
+    case TWA_F32: launch_expand_cfg<TWA_F32, 8, 4, 6, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
+    case TWA_BF16: launch_expand_cfg<TWA_BF16, 8, 2, 8, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
     case TWA_I8:
-      hipLaunchKernelGGL((expand_update_kernel<TWA_I8>), dim3(grid), dim3(256), 0, st, P, s, w, lr, g_tilde, tpw);
+      if (lh == 2) launch_expand_cfg<TWA_I8, 4, 2, 6, 0>(P, s, w, lr, g_tilde, max_grid, st);
+      else launch_expand_cfg<TWA_I8, 4, 2, 6, 1>(P, s, w, lr, g_tilde, max_grid, st);
       break;
-    case TWA_I4:
-      hipLaunchKernelGGL((expand_update_kernel<TWA_I4>), dim3(grid), dim3(256), 0, st, P, s, w, lr, g_tilde, tpw);
-      break;
-    default:
-      return TWA_ERR_DTYPE;
+    case TWA_I4: launch_expand_cfg<TWA_I4, 4, 2, 2, 0>(P, s, w, lr, g_tilde, max_grid, st); break;
+    default: return TWA_ERR_DTYPE;
   }
   return hip_check(hipGetLastError());
 }

@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
   constexpr int SLOTS = U * NCH;
-  static_assert(kScaleSpan % TILE == 0, "a tile never straddles two scale spans");
+  static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
         const uint32_t elem = (uint32_t)e0 + (uint32_t)(v * kWave + lane) * EPV;
 #pragma unroll
         for (int q = 0; q < EPV / 4; ++q) {
-          const u32x4 x = ld128(rg, (elem + 4u * q) * 4u);
+          const u32x4 x = ld128(rg, (elem + 4u * q) * 4u);   // shared by the 4 waves: keep it cacheable
 #pragma unroll
           for (int r = 0; r < 4; ++r) gs[c][v][4 * q + r] = as_f32(x[r]);
         }
@@ -93,13 +93,12 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
 
     // ---- stream this wave's basis vectors over the tile ----------------------------------
     rsrc_t rs = make_rsrc(g, 0u);
+    constexpr int SPANS = TILE > kScaleSpan ? TILE / kScaleSpan : 1;       // scale spans one tile touches
     if constexpr (S::kScaled)
-      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, span_scale_bytes);
-    const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);   // tile offset inside its span
-#pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) {
-      u32x4 raw[U][VPL];
-      float sc[U][VPL];
+      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, SPANS * span_scale_bytes);
+    const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);   // tile offset inside its first span
+    // chunk ch = column slots [ch*U, (ch+1)*U): fetch (128-bit codes/values + block scales) ...
+    auto load_chunk = [&](int ch, u32x4 (&raw)[U][VPL], float (&sc)[U][VPL]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int slot = ch * U + u;
@@ -111,9 +110,12 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
           const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
           raw[u][v] = ld128_stream(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
           if constexpr (S::kScaled) {
-            // an unused column slot reads far outside the span's range and gets 0
+            // scale index inside the tile's run of spans: [span][vector][block in span];
+            // an unused column slot reads far outside the range and gets 0
+            const uint32_t pos = in_span + loc;
             const uint32_t soff =
-                valid ? (((uint32_t)col << gshift) + ((in_span + loc) >> P.block_shift)) * (uint32_t)S::kScaleBytes
+                valid ? ((((pos >> kScaleSpanShift) * (uint32_t)P.n + (uint32_t)col) << gshift) +
+                         ((pos & (uint32_t)(kScaleSpan - 1)) >> P.block_shift)) * (uint32_t)S::kScaleBytes
                       : 0x7fffff00u;
             sc[u][v] = load_scale<DT>(rs, soff, P.gscale);
           } else {
@@ -121,6 +123,9 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
           }
         }
       }
+    };
+    // ... and fold it into the running sums of its slots
+    auto compute_chunk = [&](int ch, const u32x4 (&raw)[U][VPL], const float (&sc)[U][VPL]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int slot = ch * U + u;
@@ -144,6 +149,17 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
           }
         }
       }
+    };
+    // double buffered: the loads of chunk ch+1 are issued before chunk ch is consumed
+    u32x4 rawA[U][VPL], rawB[U][VPL];
+    float scA[U][VPL], scB[U][VPL];
+    load_chunk(0, rawA, scA);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ch += 2) {
+      if (ch + 1 < NCH) load_chunk(ch + 1, rawB, scB);
+      compute_chunk(ch, rawA, scA);
+      if (ch + 2 < NCH) load_chunk(ch + 2, rawA, scA);
+      if (ch + 1 < NCH) compute_chunk(ch + 1, rawB, scB);
     }
   }
 
@@ -220,7 +236,10 @@ int launch_project(const PView& P, int dtype, const float* g, float* s, float* p
     case TWA_F32: rc = launch_project_dt<TWA_F32, 1, 4>(P, g, 0, 1, partial, max_grid, &grid, st); break;
     case TWA_BF16: rc = launch_project_dt<TWA_BF16, 1, 2>(P, g, 0, 1, partial, max_grid, &grid, st); break;
     case TWA_I8: rc = launch_project_dt<TWA_I8, 1, 2>(P, g, 0, 1, partial, max_grid, &grid, st); break;
-    case TWA_I4: rc = launch_project_dt<TWA_I4, 1, 1>(P, g, 0, 1, partial, max_grid, &grid, st); break;
+    case TWA_I4:
+      rc = env_int("TWA_I4_PROJECT_VPL", 1) == 2 ? launch_project_dt<TWA_I4, 1, 2>(P, g, 0, 1, partial, max_grid, &grid, st)
+                                                 : launch_project_dt<TWA_I4, 1, 1>(P, g, 0, 1, partial, max_grid, &grid, st);
+      break;
     default: return TWA_ERR_DTYPE;
   }
   if (rc != TWA_OK) return rc;
