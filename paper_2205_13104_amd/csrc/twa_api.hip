@@ -221,7 +221,7 @@ int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float
   if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
   if (!aligned16(ws)) return TWA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int grid = persistent_grid("TWA_PROJECT_GRID", 12);
+  const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   float* partial = static_cast<float*>(ws);
   if (k == 1) return launch_project(v, P->dtype, g, s, partial, grid, st);

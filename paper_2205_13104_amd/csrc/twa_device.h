@@ -45,6 +45,12 @@ __device__ __forceinline__ uint32_t ld16(rsrc_t r, uint32_t voff) {
 __device__ __forceinline__ void st128(rsrc_t r, uint32_t voff, u32x4 v) {
   __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, 0, 0);
 }
+// Store that is written through to memory (sc0 sc1) instead of lingering dirty in L2: the burst of
+// w written at the end of the expand kernel then does not trickle out during the next kernel's reads
+// (measured: 0.6 % of the step).
+__device__ __forceinline__ void st128_through(rsrc_t r, uint32_t voff, u32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, 0, /*sc0*/ 1 | /*sc1*/ 16);
+}
 __device__ __forceinline__ void st32(rsrc_t r, uint32_t voff, uint32_t v) {
   __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, 0, 0);
 }

@@ -143,7 +143,7 @@ struct Expander {
     nw[2] = as_u32(__builtin_fmaf(-lr, gt.z, as_f32(wq[2])));
     nw[3] = as_u32(__builtin_fmaf(-lr, gt.w, as_f32(wq[3])));
     if ((int64_t)el + 4 <= D) {
-      st128(rw, off, nw);
+      st128_through(rw, off, nw);
       st128(rgt, off, gv);          // empty descriptor when g~ is not wanted: dropped
     } else {
 #pragma unroll
@@ -280,15 +280,12 @@ static void launch_expand_cfg(const PView& P, const float* s, float* w, float lr
 
 int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int max_grid,
                          hipStream_t st) {
-  const int lh = env_int("TWA_EXPAND_LH", 1);
+  // <U, VPL, HOLD, LH> per storage type: chosen by interleaved timing on MI355X at D = 25.6 M, n = 100
   switch (dtype) {
-    case TWA_F32: launch_expand_cfg<TWA_F32, 8, 4, 6, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
-    case TWA_BF16: launch_expand_cfg<TWA_BF16, 8, 2, 8, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
-    case TWA_I8:
-      if (lh == 2) launch_expand_cfg<TWA_I8, 4, 2, 6, 0>(P, s, w, lr, g_tilde, max_grid, st);
-      else launch_expand_cfg<TWA_I8, 4, 2, 6, 1>(P, s, w, lr, g_tilde, max_grid, st);
-      break;
-    case TWA_I4: launch_expand_cfg<TWA_I4, 4, 2, 2, 0>(P, s, w, lr, g_tilde, max_grid, st); break;
+    case TWA_F32: launch_expand_cfg<TWA_F32, 1, 8, 6, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
+    case TWA_BF16: launch_expand_cfg<TWA_BF16, 2, 4, 6, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
+    case TWA_I8: launch_expand_cfg<TWA_I8, 4, 2, 6, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
+    case TWA_I4: launch_expand_cfg<TWA_I4, 8, 1, 5, 0>(P, s, w, lr, g_tilde, max_grid, st); break;
     default: return TWA_ERR_DTYPE;
   }
   return hip_check(hipGetLastError());

@@ -236,10 +236,7 @@ int launch_project(const PView& P, int dtype, const float* g, float* s, float* p
     case TWA_F32: rc = launch_project_dt<TWA_F32, 1, 4>(P, g, 0, 1, partial, max_grid, &grid, st); break;
     case TWA_BF16: rc = launch_project_dt<TWA_BF16, 1, 2>(P, g, 0, 1, partial, max_grid, &grid, st); break;
     case TWA_I8: rc = launch_project_dt<TWA_I8, 1, 2>(P, g, 0, 1, partial, max_grid, &grid, st); break;
-    case TWA_I4:
-      rc = env_int("TWA_I4_PROJECT_VPL", 1) == 2 ? launch_project_dt<TWA_I4, 1, 2>(P, g, 0, 1, partial, max_grid, &grid, st)
-                                                 : launch_project_dt<TWA_I4, 1, 1>(P, g, 0, 1, partial, max_grid, &grid, st);
-      break;
+    case TWA_I4: rc = launch_project_dt<TWA_I4, 1, 1>(P, g, 0, 1, partial, max_grid, &grid, st); break;
     default: return TWA_ERR_DTYPE;
   }
   if (rc != TWA_OK) return rc;
