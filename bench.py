@@ -48,8 +48,9 @@ def read_traffic(kernel: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=1000,
+                    help="untimed steps; the device needs ~0.5 s of this load before the step time settles")
     ap.add_argument("--workload", default="imagenet_resnet50", help="name in synth.WORKLOADS")
     ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4"])
     ap.add_argument("--D", type=int, default=0, help="override the parameter count (smoke runs)")

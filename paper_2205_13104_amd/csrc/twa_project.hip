@@ -175,6 +175,162 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
   }
 }
 
+// S = P^T G for up to TWA_MAX_K gradients in ONE pass over P (n <= 32 basis vectors; not int4).
+// The gradients are 44 % of the bytes at k = 8, n = 20, so they must not be fetched once per wave:
+// the workgroup loads each tile of G once, coalesced, into a double-buffered LDS tile (the loads of
+// tile t+1 are issued before tile t is consumed), and every wave reads its k slices from there.
+// Columns are split over the 4 waves and streamed exactly as in project_kernel (VPL = 1).
+template <int DT, int U, int NCH>
+__global__ __launch_bounds__(256) void project_batched_kernel(PView P, const float* __restrict__ G, int64_t ldg,
+                                                              int kvalid, float* __restrict__ partial, int cpw,
+                                                              int tiles_per_wg) {
+  using S = Store<DT>;
+  constexpr int KB = TWA_MAX_K;
+  constexpr int EPV = S::kEPV;
+  constexpr int TILE = kWave * EPV;
+  constexpr int SLOTS = U * NCH;
+  constexpr int F4 = TILE / 4;                       // 128-bit pieces per gradient and tile
+  constexpr int NLD = KB * F4 / 256;                 // pieces each thread stages per tile
+  static_assert(kScaleSpan % TILE == 0, "a tile lies inside one scale span");
+  static_assert(F4 % kWave == 0 && (KB * F4) % 256 == 0, "staging pieces are wave-uniform in the gradient index");
+  __shared__ float gl[2][KB][TILE];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t D = P.D;
+  const int64_t ntiles = (D + TILE - 1) / TILE;
+  const int64_t t0 = (int64_t)blockIdx.x * tiles_per_wg;
+  int64_t t1 = t0 + tiles_per_wg;
+  if (t1 > ntiles) t1 = ntiles;
+
+  const int c0 = wave * cpw;
+  int ncol = P.n - c0;
+  ncol = ncol < 0 ? 0 : (ncol > cpw ? cpw : ncol);
+  const uint32_t col_bytes = (uint32_t)((((D * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
+  const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
+  const int gshift = kScaleSpanShift - P.block_shift;
+  const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes : 0u;
+  const uint32_t g_bytes = (uint32_t)(D * 4);
+
+  // piece r of this thread: gradient (wave-uniform) and position inside the tile
+  auto stage_load = [&](int64_t t, u32x4 (&pre)[NLD]) {
+#pragma unroll
+    for (int r = 0; r < NLD; ++r) {
+      const int f = (int)threadIdx.x + 256 * r;
+      const int c = __builtin_amdgcn_readfirstlane(f / F4);
+      const int pos = f % F4;
+      const rsrc_t rg = make_rsrc(G + (int64_t)c * ldg, c < kvalid ? g_bytes : 0u);   // past D and past k: zeros
+      pre[r] = ld128(rg, ((uint32_t)(t * TILE) + 4u * (uint32_t)pos) * 4u);
+    }
+  };
+  auto stage_store = [&](int buf, const u32x4 (&pre)[NLD]) {
+#pragma unroll
+    for (int r = 0; r < NLD; ++r) {
+      const int f = (int)threadIdx.x + 256 * r;
+      *reinterpret_cast<u32x4*>(&gl[buf][f / F4][4 * (f % F4)]) = pre[r];
+    }
+  };
+
+  float acc[SLOTS][KB];
+#pragma unroll
+  for (int sl = 0; sl < SLOTS; ++sl)
+#pragma unroll
+    for (int c = 0; c < KB; ++c) acc[sl][c] = 0.0f;
+
+  if (t0 < t1) {
+    u32x4 pre[NLD];
+    stage_load(t0, pre);
+    stage_store(0, pre);
+  }
+  __syncthreads();
+
+  for (int64_t t = t0; t < t1; ++t) {
+    const int64_t e0 = t * TILE;
+    const int cur = (int)(t - t0) & 1;
+    const bool more = t + 1 < t1;                      // uniform
+    u32x4 pre[NLD];
+    if (more) stage_load(t + 1, pre);
+
+    float gs[KB][EPV];
+#pragma unroll
+    for (int c = 0; c < KB; ++c)
+#pragma unroll
+      for (int q = 0; q < EPV / 4; ++q) {
+        const float4 x = *reinterpret_cast<const float4*>(&gl[cur][c][lane * EPV + 4 * q]);
+        gs[c][4 * q] = x.x; gs[c][4 * q + 1] = x.y; gs[c][4 * q + 2] = x.z; gs[c][4 * q + 3] = x.w;
+      }
+
+    rsrc_t rs = make_rsrc(G, 0u);
+    if constexpr (S::kScaled)
+      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, span_scale_bytes);
+    const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);
+    auto load_chunk = [&](int ch, u32x4 (&raw)[U], float (&sc)[U]) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int slot = ch * U + u;
+        const bool valid = slot < ncol;
+        const int col = valid ? c0 + slot : 0;
+        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
+        const uint32_t loc = (uint32_t)lane * EPV;
+        raw[u] = ld128_stream(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
+        if constexpr (S::kScaled) {
+          const uint32_t soff = valid ? ((((uint32_t)col) << gshift) + ((in_span + loc) >> P.block_shift)) *
+                                            (uint32_t)S::kScaleBytes
+                                      : 0x7fffff00u;
+          sc[u] = load_scale<DT>(rs, soff, P.gscale);
+        } else {
+          sc[u] = 1.0f;
+        }
+      }
+    };
+    auto compute_chunk = [&](int ch, const u32x4 (&raw)[U], const float (&sc)[U]) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int slot = ch * U + u;
+        float x[EPV];
+        decode<DT>(raw[u], x);
+#pragma unroll
+        for (int c = 0; c < KB; ++c) {
+          if constexpr (S::kScaled) {
+            float d = 0.0f;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) d = __builtin_fmaf(x[e], gs[c][e], d);
+            acc[slot][c] = __builtin_fmaf(d, sc[u], acc[slot][c]);
+          } else {
+            float d = acc[slot][c];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) d = __builtin_fmaf(x[e], gs[c][e], d);
+            acc[slot][c] = d;
+          }
+        }
+      }
+    };
+    u32x4 rawA[U], rawB[U];
+    float scA[U], scB[U];
+    load_chunk(0, rawA, scA);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ch += 2) {
+      if (ch + 1 < NCH) load_chunk(ch + 1, rawB, scB);
+      compute_chunk(ch, rawA, scA);
+      if (ch + 2 < NCH) load_chunk(ch + 2, rawA, scA);
+      if (ch + 1 < NCH) compute_chunk(ch + 1, rawB, scB);
+    }
+
+    if (more) stage_store(cur ^ 1, pre);
+    __syncthreads();      // tile t+1 of G is in LDS; every wave is done reading tile t
+  }
+
+#pragma unroll
+  for (int sl = 0; sl < SLOTS; ++sl) {
+#pragma unroll
+    for (int c = 0; c < KB; ++c) {
+      const float tot = wave_sum(acc[sl][c]);
+      if (lane == 0 && sl < ncol && c < kvalid)
+        partial[((int64_t)blockIdx.x * kvalid + c) * P.n + c0 + sl] = tot;
+    }
+  }
+}
+
 // s[c*n + j] = sum over workgroups, in workgroup order, accumulated in fp64.
 __global__ __launch_bounds__(64) void project_reduce_kernel(const float* __restrict__ partial, int nparts, int kn,
                                                             float* __restrict__ s) {
@@ -205,10 +361,7 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
 #define TWA_LAUNCH(U_, NCH_)                                                                         \
   hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
                      kvalid, partial, cpw, tiles_per_wg)
-  if constexpr (KB > 1) {
-    // the fused multi-gradient kernel is only used (and only built) for n <= 32
-    if (cpw <= 4) TWA_LAUNCH(4, 1); else TWA_LAUNCH(4, 2);
-  } else {
+  {
     if (cpw == 25) {
       TWA_LAUNCH(5, 5);
     } else {
@@ -245,16 +398,26 @@ int launch_project(const PView& P, int dtype, const float* g, float* s, float* p
 }
 
 // k > 1 gradients.  Up to 32 basis vectors (and not int4, whose 32-element vectors leave no
-// registers for k gradient slices): one pass over P serves all k gradients -- each lane keeps k
-// slices of G and k running sums per column slot.  Otherwise the gradients are projected one
-// launch at a time.
+// registers for k gradient slices): one pass over P serves all k gradients (project_batched_kernel).
+// Otherwise the gradients are projected one launch at a time.
 template <int DT>
 static int launch_project_batched_dt(const PView& P, const float* g, int64_t ldg, int k, float* s, float* partial,
                                      int max_grid, hipStream_t st) {
   if constexpr (DT != TWA_I4) {
     if (P.n <= 32) {
-      int grid = 0;
-      int rc = launch_project_dt<DT, TWA_MAX_K, 1>(P, g, ldg, k, partial, max_grid, &grid, st);
+      const int cpw = (P.n + 3) / 4;
+      int grid, tiles_per_wg;
+      divide_tiles(P.D, kWave * Store<DT>::kEPV, max_grid, &grid, &tiles_per_wg);
+#define TWA_LAUNCH_B(U_, NCH_)                                                                              \
+  hipLaunchKernelGGL((project_batched_kernel<DT, U_, NCH_>), dim3(grid), dim3(256), 0, st, P, g, ldg, k, partial, \
+                     cpw, tiles_per_wg)
+      if (cpw <= 3) TWA_LAUNCH_B(3, 1);
+      else if (cpw == 4) TWA_LAUNCH_B(4, 1);
+      else if (cpw == 5) TWA_LAUNCH_B(5, 1);
+      else if (cpw == 6) TWA_LAUNCH_B(3, 2);
+      else TWA_LAUNCH_B(4, 2);
+#undef TWA_LAUNCH_B
+      int rc = hip_check(hipGetLastError());
       if (rc != TWA_OK) return rc;
       hipLaunchKernelGGL(project_reduce_kernel, dim3(P.n * k), dim3(kWave), 0, st, partial, grid, P.n * k, s);
       return hip_check(hipGetLastError());
