@@ -164,3 +164,73 @@ def test_vit_b16_bf16_batched_full_size():
     for c in (1, 5):
         sc = twa.project(pm, G[c, :D].contiguous())
         assert rel_l2(S[c].cpu().numpy(), sc.cpu().numpy()) <= 5e-6   # two summation orders, each within the bar
+
+
+def test_large_int4_int8_full_size():
+    """D = 350 M, n = 128: basis in place on the 179 GB checkpoint matrix, int4 and int8 storage, one step each."""
+    wl = synth.WORKLOADS["large"]
+    D, n = wl.D, wl.n
+    free, total = torch.cuda.mem_get_info()
+    need = 4 * n * (D + 2048) + n * (D + 2048) * 3 // 2 + 20 * D + (8 << 30)
+    if free < need:
+        pytest.skip(f"needs {need / 2**30:.0f} GiB of device memory, {free / 2**30:.0f} GiB free")
+    say("full size", wl.name, D, n, f"free {free / 2**30:.0f} GiB")
+    W = synth.checkpoints(wl, seed=0, device="cuda")
+    w = W[:, :D].mean(dim=0).contiguous()
+    P, R = twa.build_basis(W, D, out=W)
+    del W
+    ortho = np.max(np.abs(gram_fp64(P, D) - np.eye(n)))
+    say("  max|PtP-I|", ortho)
+    assert ortho <= ORTHO_TOL
+    assert np.all(np.diag(R.numpy()) > 0)
+    amax = max(float(P[j, :D].abs().max().item()) for j in range(n))      # row by row: no 167 GiB temporary
+    gs_ref = orc.gscale_i4(np.array([[amax]], dtype=np.float32))       # gscale depends on the largest |p| only
+    g = synth.gradient(D, wl.sigma_g, seed=0, step=0, device="cuda")
+    for dtype in (twa.I4, twa.I8):
+        pm = twa.quantize(P, D, dtype)
+        if dtype == twa.I4:
+            assert pm.gscale == gs_ref
+        # one whole vector through the oracle's quantiser: bit-exact codes and scales
+        j = 77
+        col = P[j:j + 1].cpu().numpy()
+        if dtype == twa.I4:
+            ref = orc.quantize_i4(col, D=D, ld=pm.ld, gscale=pm.gscale)
+            assert np.array_equal(pm.scales_by_vector()[j].view(torch.int16).cpu().numpy().view(np.uint16), ref.scales[0])
+        else:
+            ref = orc.quantize_i8(col, D=D, ld=pm.ld)
+            assert np.array_equal(pm.scales_by_vector()[j].cpu().numpy().view(np.uint32), ref.scales[0].view(np.uint32))
+        assert np.array_equal(pm.data[j].cpu().numpy(), ref.data[0])
+        del col, ref
+        # one step: sampled coefficients over the whole of D, g~ / w on sampled blocks
+        ws = twa.Workspace(twa.project_workspace_bytes(n))
+        s = torch.empty(n, device="cuda")
+        w1 = w.clone()
+        gt = torch.empty(D, device="cuda")
+        twa.project(pm, g, s, ws)
+        twa.expand_update(pm, s, w1, wl.lr, gt)
+        torch.cuda.synchronize()
+        cols = [0, n - 1]
+        so = orc.project(to_oracle(pm, cols=cols), g.cpu().numpy().astype(np.float64))
+        e_s = rel_l2(s[cols].cpu().numpy(), so)
+        say("  dtype", dtype, "rel_l2 s[sampled]", e_s)
+        assert e_s <= REL_L2_TOL
+        blk = pm.block
+        nb = D // blk
+        r = np.random.default_rng(5)
+        ids = sorted(set([0, nb - 1] + r.integers(0, nb, size=32).tolist()))
+        rows = torch.cat([torch.arange(b * blk, (b + 1) * blk) for b in ids]).cuda()
+        scv = pm.scales_by_vector()[:, torch.tensor(ids, device="cuda")]
+        if dtype == twa.I8:
+            po = orc.Pmat(orc.I8, int(rows.numel()), np.ascontiguousarray(pm.data[:, rows].cpu().numpy()),
+                          np.ascontiguousarray(scv.cpu().numpy()), blk, 1.0)
+        else:
+            bytes_ = torch.cat([torch.arange(b * blk // 2, (b + 1) * blk // 2) for b in ids]).cuda()
+            po = orc.Pmat(orc.I4, int(rows.numel()), np.ascontiguousarray(pm.data[:, bytes_].cpu().numpy()),
+                          np.ascontiguousarray(scv.view(torch.int16).cpu().numpy().view(np.uint16)), blk, pm.gscale)
+        wo = w[rows].cpu().numpy().astype(np.float64)
+        gto = orc.expand_update(po, s.cpu().numpy().astype(np.float64), wo, wl.lr, want_gt=True)
+        e_gt, e_w = rel_l2(gt[rows].cpu().numpy(), gto), rel_l2(w1[rows].cpu().numpy(), wo)
+        say("  dtype", dtype, "rel_l2 g~[sampled]", e_gt, "w[sampled]", e_w)
+        assert e_gt <= REL_L2_TOL and e_w <= REL_L2_TOL
+        del pm, w1, gt, ws
+        torch.cuda.empty_cache()
