@@ -318,6 +318,105 @@ int twa_oracle_centre_normalise(const double* W, int64_t D, int32_t n, int64_t l
 }
 
 /* ------------------------------------------------------------------------- */
+/* Sec. 4.5 (layer-wise processing) and Alg. 1.  The D parameters are cut     */
+/* into L consecutive groups; layer l covers elements [off[l], off[l+1]),     */
+/* off[0] = 0, off[L] = D, empty layers allowed.  Every layer has its own     */
+/* block P^l (rows off[l]..off[l+1] of the stored matrix) and its own n       */
+/* coefficients, kept as row l of an L x n array.                             */
+/* ------------------------------------------------------------------------- */
+static int layers_ok(const int64_t* off, int32_t L, int64_t D) {
+  if (!off || L < 1 || off[0] != 0 || off[L] != D) return 0;
+  for (int32_t l = 0; l < L; ++l) if (off[l + 1] < off[l]) return 0;
+  return 1;
+}
+
+/* Alg. 1, coefficient gradient of layer l:  S[l][j] = sum_{i in layer l} P_ij g_i */
+int twa_oracle_project_layers(const orc_pmat* P, const double* g, const int64_t* off, int32_t L,
+                              double* S) {
+  if (!P || !g || !S || !layers_ok(off, L, P->D)) return ORC_ERR_ARG;
+  const int32_t n = P->n;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int32_t l = 0; l < L; ++l)
+    for (int32_t j = 0; j < n; ++j) {
+      double acc = 0.0;
+      for (int64_t i = off[l]; i < off[l + 1]; ++i) acc += deq(P, i, j) * g[i];
+      S[(int64_t)l * n + j] = acc;
+    }
+  return ORC_OK;
+}
+
+/* Weight-space form of the layer-wise step with lambda = 0:                  */
+/*   g~_i = sum_j P_ij S[l(i)][j] ;  w_i <- w_i - eta g~_i                     */
+int twa_oracle_expand_update_layers(const orc_pmat* P, const double* S, const int64_t* off, int32_t L,
+                                    double* w, double eta, double* g_tilde) {
+  if (!P || !S || !w || !layers_ok(off, L, P->D)) return ORC_ERR_ARG;
+  const int32_t n = P->n;
+  for (int32_t l = 0; l < L; ++l) {
+    const double* sl = S + (int64_t)l * n;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = off[l]; i < off[l + 1]; ++i) {
+      double gt = 0.0;
+      for (int32_t j = 0; j < n; ++j) gt += deq(P, i, j) * sl[j];
+      if (g_tilde) g_tilde[i] = gt;
+      w[i] = w[i] - eta * gt;
+    }
+  }
+  return ORC_OK;
+}
+
+/* Alg. 1, "update variables":  beta <- (1 - eta*lambda) beta - eta s   (count = L*n entries) */
+int twa_oracle_beta_step(double* beta, const double* s, int64_t count, double eta, double lambda) {
+  if (!beta || !s || count < 0) return ORC_ERR_ARG;
+  for (int64_t q = 0; q < count; ++q) beta[q] = (1.0 - eta * lambda) * beta[q] - eta * s[q];
+  return ORC_OK;
+}
+
+/* Alg. 1, "update weights":  w^l = wbar^l + P^l beta^l */
+int twa_oracle_weights_from_beta(const orc_pmat* P, const double* beta, const int64_t* off, int32_t L,
+                                 const double* wbar, double* w) {
+  if (!P || !beta || !wbar || !w || !layers_ok(off, L, P->D)) return ORC_ERR_ARG;
+  const int32_t n = P->n;
+  for (int32_t l = 0; l < L; ++l) {
+    const double* bl = beta + (int64_t)l * n;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = off[l]; i < off[l + 1]; ++i) {
+      double acc = 0.0;
+      for (int32_t j = 0; j < n; ++j) acc += deq(P, i, j) * bl[j];
+      w[i] = wbar[i] + acc;
+    }
+  }
+  return ORC_OK;
+}
+
+/* Sec. 4.5, layer-wise basis:  wbar = mean_i w_i ;                            */
+/*   e_i^l = (w_i^l - wbar^l) / ||w_i^l - wbar^l||_2 .                          */
+/* A (layer, checkpoint) pair whose centred part is exactly zero gives a zero  */
+/* vector (the paper does not say; a zero direction changes nothing).          */
+/* nrm (may be NULL) receives the L x n norms.                                 */
+int twa_oracle_centre_normalise_layers(const double* W, int64_t D, int32_t n, int64_t ldw,
+                                       const int64_t* off, int32_t L, double* E, int64_t lde,
+                                       double* wbar, double* nrm) {
+  if (!W || !E || !wbar || D <= 0 || n <= 0 || ldw < D || lde < D || !layers_ok(off, L, D)) return ORC_ERR_ARG;
+  for (int64_t i = 0; i < D; ++i) {
+    double m = 0.0;
+    for (int32_t j = 0; j < n; ++j) m += W[(int64_t)j * ldw + i];
+    wbar[i] = m / (double)n;
+  }
+  for (int32_t l = 0; l < L; ++l)
+    for (int32_t j = 0; j < n; ++j) {
+      double ss = 0.0;
+      for (int64_t i = off[l]; i < off[l + 1]; ++i) { double d = W[(int64_t)j * ldw + i] - wbar[i]; ss += d * d; }
+      const double nr = sqrt(ss);
+      if (nrm) nrm[(int64_t)l * n + j] = nr;
+      for (int64_t i = off[l]; i < off[l + 1]; ++i)
+        E[(int64_t)j * lde + i] = (nr > 0.0) ? (W[(int64_t)j * ldw + i] - wbar[i]) / nr : 0.0;
+    }
+  for (int32_t j = 0; j < n; ++j)
+    for (int64_t i = D; i < lde; ++i) E[(int64_t)j * lde + i] = 0.0;
+  return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Block-absmax quantiser.  Recipe (every step one correctly rounded binary32 */
 /* operation; f(.) below = "round the exact result once to binary32"):        */
 /*   block b of vector j = elements i in [b*block, min((b+1)*block, D))       */

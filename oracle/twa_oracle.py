@@ -77,6 +77,14 @@ def lib():
         L.twa_oracle_quantize_minmax.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_int32,
                                                  C.c_void_p, C.c_int32, C.c_void_p, C.c_int64,
                                                  C.c_void_p, C.c_void_p]
+        L.twa_oracle_project_layers.argtypes = [P, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.twa_oracle_expand_update_layers.argtypes = [P, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                                      C.c_double, C.c_void_p]
+        L.twa_oracle_beta_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_double]
+        L.twa_oracle_weights_from_beta.argtypes = [P, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.twa_oracle_centre_normalise_layers.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int64,
+                                                         C.c_void_p, C.c_int32, C.c_void_p, C.c_int64,
+                                                         C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -209,6 +217,69 @@ def centre_normalise(W: np.ndarray):
     wbar = np.empty(D, dtype=np.float64)
     _check(lib().twa_oracle_centre_normalise(_ptr(W), D, n, D, _ptr(E), D, _ptr(wbar)), "centre_normalise")
     return E, wbar
+
+
+def _off(layer_off, D: int) -> np.ndarray:
+    off = np.ascontiguousarray(layer_off, dtype=np.int64)
+    assert off.ndim == 1 and off.size >= 2 and off[0] == 0 and off[-1] == D
+    return off
+
+
+def project_layers(P: Pmat, g: np.ndarray, layer_off) -> np.ndarray:
+    """S[l, j] = sum over the elements i of layer l of P[i, j] g[i] -- Sec. 4.5 / Alg. 1.  Returns (L, n)."""
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    assert g.shape == (P.D,)
+    off = _off(layer_off, P.D)
+    S = np.empty((off.size - 1, P.n), dtype=np.float64)
+    st = P._struct()
+    _check(lib().twa_oracle_project_layers(C.byref(st), _ptr(g), _ptr(off), off.size - 1, _ptr(S)), "project_layers")
+    return S
+
+
+def expand_update_layers(P: Pmat, S: np.ndarray, layer_off, w: np.ndarray, eta: float, want_gt: bool = False):
+    """g~_i = sum_j P[i, j] S[l(i), j]; w <- w - eta g~ in place -- Sec. 4.5, lambda = 0."""
+    off = _off(layer_off, P.D)
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    assert S.shape == (off.size - 1, P.n)
+    assert w.dtype == np.float64 and w.flags.c_contiguous and w.shape == (P.D,)
+    gt = np.empty(P.D, dtype=np.float64) if want_gt else None
+    st = P._struct()
+    _check(lib().twa_oracle_expand_update_layers(C.byref(st), _ptr(S), _ptr(off), off.size - 1, _ptr(w), float(eta),
+                                                 _ptr(gt)), "expand_update_layers")
+    return gt
+
+
+def beta_step(beta: np.ndarray, s: np.ndarray, eta: float, lam: float) -> None:
+    """beta <- (1 - eta*lam) beta - eta s in place -- Alg. 1, "update variables"."""
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    assert beta.dtype == np.float64 and beta.flags.c_contiguous and beta.shape == s.shape
+    _check(lib().twa_oracle_beta_step(_ptr(beta), _ptr(s), beta.size, float(eta), float(lam)), "beta_step")
+
+
+def weights_from_beta(P: Pmat, beta: np.ndarray, layer_off, wbar: np.ndarray) -> np.ndarray:
+    """w^l = wbar^l + P^l beta^l -- Alg. 1, "update weights".  beta: (L, n).  Returns w (D,)."""
+    off = _off(layer_off, P.D)
+    beta = np.ascontiguousarray(beta, dtype=np.float64)
+    wbar = np.ascontiguousarray(wbar, dtype=np.float64)
+    assert beta.shape == (off.size - 1, P.n) and wbar.shape == (P.D,)
+    w = np.empty(P.D, dtype=np.float64)
+    st = P._struct()
+    _check(lib().twa_oracle_weights_from_beta(C.byref(st), _ptr(beta), _ptr(off), off.size - 1, _ptr(wbar), _ptr(w)),
+           "weights_from_beta")
+    return w
+
+
+def centre_normalise_layers(W: np.ndarray, layer_off):
+    """Layer-wise basis of Sec. 4.5: returns (E (n, D), wbar (D,), norms (L, n))."""
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    n, D = W.shape
+    off = _off(layer_off, D)
+    E = np.empty((n, D), dtype=np.float64)
+    wbar = np.empty(D, dtype=np.float64)
+    nrm = np.empty((off.size - 1, n), dtype=np.float64)
+    _check(lib().twa_oracle_centre_normalise_layers(_ptr(W), D, n, D, _ptr(off), off.size - 1, _ptr(E), D,
+                                                    _ptr(wbar), _ptr(nrm)), "centre_normalise_layers")
+    return E, wbar, nrm
 
 
 def _pad_ld(D: int, mult: int) -> int:
