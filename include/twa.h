@@ -176,6 +176,58 @@ int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float
 int twa_expand_update(const twa_pmat* P, const float* s, float* w, float lr, float* g_tilde,
                       void* stream);
 
+/*
+ * Layer-wise processing (Sec. 4.5; Alg. 1, the loop over l = 1..L).  The D parameters are cut
+ * into L consecutive layers, layer l = elements [layer_off[l], layer_off[l+1]); every layer has its
+ * own block P^l (those rows of the stored matrix) and its own n coefficients, so the coefficient
+ * arrays are L x n (row l = layer l).  The stored matrix, its dtype and its scale blocks are the
+ * same as in the whole-model calls: layers need not be aligned to anything, and a quantisation block
+ * may straddle a boundary.
+ *
+ * The layer table is turned ONCE into a device-side plan (the layers of a model do not change
+ * during training); the step calls take the plan.  In the plan the kernels' tiles are cut per layer,
+ * so a tile never meets two layers and the stream over P is the branch-free one of the whole-model
+ * step, at the price of at most one extra tile per layer.
+ */
+#define TWA_MAX_LAYERS 65536
+
+/* Bytes of the device buffer that holds a plan for L layers. */
+int twa_layer_plan_bytes(int32_t L, size_t* bytes);
+
+/*
+ * Build the plan.
+ *   layer_off [in]  L+1 int64 values in DEVICE memory: layer_off[0] = 0, non-decreasing (empty layers
+ *                   allowed), layer_off[L] = D.  The table is read on the device only; a table that
+ *                   breaks these rules is clamped into one that keeps them (unspecified layers, but
+ *                   no access out of range later on).
+ *   plan [out]      device buffer of at least twa_layer_plan_bytes(L), 8-byte aligned; it must stay
+ *                   intact as long as step calls use it, and is valid for any stored matrix with
+ *                   the same D (every dtype).
+ * 1 <= L <= TWA_MAX_LAYERS.  Asynchronous on `stream`.
+ */
+int twa_layer_plan(const int64_t* layer_off, int32_t L, int64_t D, void* plan, size_t plan_bytes, void* stream);
+
+/* Workspace (device bytes) needed by twa_project_layers for n vectors and L layers. */
+int twa_project_layers_workspace_bytes(int32_t n, int32_t L, size_t* bytes);
+
+/*
+ * S[l][j] = sum over the elements i of layer l of value(P)_ij * g[i]   (Alg. 1: (P^l)^T g^l).
+ *   g    [in]  D floats (device).      S [out] L*n floats (device); the row of an empty layer is 0.
+ *   plan [in]  built by twa_layer_plan with the same L and D = P->D.
+ *   ws, ws_bytes  device workspace of at least twa_project_layers_workspace_bytes(n, L).
+ * Same pass over P, same arithmetic and the same fixed reduction order as twa_project.
+ */
+int twa_project_layers(const twa_pmat* P, const float* g, const void* plan, int32_t L, float* S, void* ws,
+                       size_t ws_bytes, void* stream);
+
+/*
+ * g~_i = sum_j value(P)_ij * S[l(i)][j] ; w <- w - lr * g~   (Alg. 1 with lambda = 0 in weight
+ * space; l(i) = the layer of element i).
+ *   S  [in]     L*n floats (device).     w [in/out] D floats.     g_tilde [out, optional] D floats.
+ */
+int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan, int32_t L, float* w, float lr,
+                             float* g_tilde, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

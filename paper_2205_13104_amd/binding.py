@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtwa.so")
 
 F32, BF16, I8, I4 = 0, 1, 2, 3
-MAX_N, MAX_K, LD_MULTIPLE, SCALE_SPAN = 128, 8, 128, 2048
+MAX_N, MAX_K, LD_MULTIPLE, SCALE_SPAN, MAX_LAYERS = 128, 8, 128, 2048, 65536
 DEFAULT_BLOCK = {I8: 128, I4: 64}
 
 OK = 0
@@ -61,6 +61,14 @@ def lib():
         L.twa_quantize.argtypes = [vp, i64, i32, i64, C.POINTER(_Pmat), vp]
         L.twa_project.argtypes = [C.POINTER(_Pmat), vp, i32, i64, vp, vp, C.c_size_t, vp]
         L.twa_expand_update.argtypes = [C.POINTER(_Pmat), vp, vp, f32, vp, vp]
+        L.twa_project_layers_workspace_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
+        L.twa_project_layers.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, vp, C.c_size_t, vp]
+        L.twa_expand_update_layers.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, f32, vp, vp]
+        L.twa_layer_plan_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
+        L.twa_layer_plan.argtypes = [vp, i32, i64, vp, C.c_size_t, vp]
+        for f in (L.twa_project_layers_workspace_bytes, L.twa_project_layers, L.twa_expand_update_layers,
+                  L.twa_layer_plan_bytes, L.twa_layer_plan):
+            f.restype = C.c_int
         for f in (L.twa_pmat_bytes, L.twa_project_workspace_bytes, L.twa_build_basis_workspace_bytes,
                   L.twa_build_basis, L.twa_quantize, L.twa_project, L.twa_expand_update):
             f.restype = C.c_int
@@ -207,6 +215,71 @@ def expand_update(P: Pmat, s: torch.Tensor, w: torch.Tensor, lr: float, g_tilde:
     st = P.c_struct()
     _check(lib().twa_expand_update(C.byref(st), _ptr(s), _ptr(w), float(lr), _ptr(g_tilde), _stream()),
            "twa_expand_update")
+
+
+def project_layers_workspace_bytes(n: int, L: int) -> int:
+    b = C.c_size_t()
+    _check(lib().twa_project_layers_workspace_bytes(n, L, C.byref(b)), "twa_project_layers_workspace_bytes")
+    return int(b.value)
+
+
+class LayerPlan:
+    """twa_layer_plan: the device-side plan of a layer table (L+1 int64 offsets on the device, or any
+    sequence of ints, which is copied there).  Built once per model; valid for every stored matrix
+    of the same D."""
+
+    def __init__(self, layer_off, D: int, device="cuda"):
+        if not isinstance(layer_off, torch.Tensor):
+            layer_off = torch.tensor(list(layer_off), dtype=torch.int64)
+        assert layer_off.dtype == torch.int64 and layer_off.dim() == 1
+        self.layer_off = layer_off.to(device).contiguous()
+        self.L = int(self.layer_off.numel()) - 1
+        self.D = int(D)
+        nb = C.c_size_t()
+        _check(lib().twa_layer_plan_bytes(self.L, C.byref(nb)), "twa_layer_plan_bytes")
+        self.buf = torch.empty(int(nb.value) // 8 + 1, dtype=torch.int64, device=device)
+        _check(lib().twa_layer_plan(_ptr(self.layer_off), self.L, self.D, _ptr(self.buf), self.buf.numel() * 8,
+                                    _stream()), "twa_layer_plan")
+
+    @property
+    def ptr(self) -> int:
+        return int(self.buf.data_ptr())
+
+    def tables(self):
+        """(off, first2048, first1024) copied to the host, for inspection."""
+        raw = self.buf.cpu()
+        n = self.L + 1
+        off = raw[:n].clone()
+        rest = raw[n:].view(torch.int32)
+        return off, rest[:n].clone(), rest[n:2 * n].clone()
+
+
+def project_layers(P: Pmat, g: torch.Tensor, plan: LayerPlan, S: Optional[torch.Tensor] = None,
+                   ws: Optional[Workspace] = None) -> torch.Tensor:
+    """twa_project_layers: S[l] = (P^l)^T g^l.  Returns S: (L, n)."""
+    assert g.dtype == torch.float32 and g.is_contiguous() and g.dim() == 1
+    assert plan.D == P.D
+    L = plan.L
+    if S is None:
+        S = torch.empty((L, P.n), dtype=torch.float32, device=g.device)
+    if ws is None:
+        ws = Workspace(project_layers_workspace_bytes(P.n, L), device=g.device)
+    st = P.c_struct()
+    _check(lib().twa_project_layers(C.byref(st), _ptr(g), plan.ptr, L, _ptr(S), ws.ptr, ws.nbytes, _stream()),
+           "twa_project_layers")
+    return S
+
+
+def expand_update_layers(P: Pmat, S: torch.Tensor, plan: LayerPlan, w: torch.Tensor, lr: float,
+                         g_tilde: Optional[torch.Tensor] = None) -> None:
+    """twa_expand_update_layers: g~_i = sum_j P_ij S[l(i), j]; w -= lr * g~ (in place)."""
+    L = plan.L
+    assert plan.D == P.D
+    assert S.dtype == torch.float32 and S.is_contiguous() and tuple(S.shape) == (L, P.n)
+    assert w.dtype == torch.float32 and w.is_contiguous()
+    st = P.c_struct()
+    _check(lib().twa_expand_update_layers(C.byref(st), _ptr(S), plan.ptr, L, _ptr(w), float(lr),
+                                          _ptr(g_tilde), _stream()), "twa_expand_update_layers")
 
 
 def build_basis(W: torch.Tensor, D: int, out: Optional[torch.Tensor] = None, want_R: bool = True,

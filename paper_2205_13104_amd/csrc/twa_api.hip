@@ -241,6 +241,73 @@ int twa_expand_update(const twa_pmat* P, const float* s, float* w, float lr, flo
   return launch_expand_update(v, P->dtype, s, w, lr, g_tilde, grid, st);
 }
 
+int twa_project_layers_workspace_bytes(int32_t n, int32_t L, size_t* bytes) {
+  if (!bytes) return TWA_ERR_NULL;
+  if (n <= 0 || n > TWA_MAX_N || L <= 0 || L > TWA_MAX_LAYERS) return TWA_ERR_SHAPE;
+  *bytes = ((size_t)kMaxGrid + (size_t)L) * (size_t)n * sizeof(float);
+  return TWA_OK;
+}
+
+int twa_layer_plan_bytes(int32_t L, size_t* bytes) {
+  if (!bytes) return TWA_ERR_NULL;
+  if (L <= 0 || L > TWA_MAX_LAYERS) return TWA_ERR_SHAPE;
+  *bytes = layer_plan_bytes(L);
+  return TWA_OK;
+}
+
+int twa_layer_plan(const int64_t* layer_off, int32_t L, int64_t D, void* plan, size_t plan_bytes, void* stream) {
+  if (!layer_off || !plan) return TWA_ERR_NULL;
+  if (L <= 0 || L > TWA_MAX_LAYERS) return TWA_ERR_SHAPE;
+  int rc = check_dims(D, 1, (D + TWA_LD_MULTIPLE - 1) / TWA_LD_MULTIPLE * TWA_LD_MULTIPLE, TWA_F32);
+  if (rc != TWA_OK) return rc;
+  if (plan_bytes < layer_plan_bytes(L)) return TWA_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(layer_off) & 7u) || (reinterpret_cast<uintptr_t>(plan) & 7u)) return TWA_ERR_ALIGN;
+  if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_layer_plan(layer_off, L, D, plan, static_cast<hipStream_t>(stream));
+}
+
+static int check_plan(const void* plan, int32_t L) {
+  if (!plan) return TWA_ERR_NULL;
+  if (L <= 0 || L > TWA_MAX_LAYERS) return TWA_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(plan) & 7u) return TWA_ERR_ALIGN;
+  return TWA_OK;
+}
+
+int twa_project_layers(const twa_pmat* P, const float* g, const void* plan, int32_t L, float* S, void* ws,
+                       size_t ws_bytes, void* stream) {
+  PView v;
+  int rc = view_of(P, &v);
+  if (rc != TWA_OK) return rc;
+  if (!g || !S) return TWA_ERR_NULL;
+  rc = check_plan(plan, L);
+  if (rc != TWA_OK) return rc;
+  if (!aligned16(g) || (reinterpret_cast<uintptr_t>(S) & 3u)) return TWA_ERR_ALIGN;
+  size_t need = 0;
+  twa_project_layers_workspace_bytes(v.n, L, &need);
+  if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
+  if (!aligned16(ws)) return TWA_ERR_ALIGN;
+  const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_project_layers(v, P->dtype, g, plan, L, S, static_cast<float*>(ws), grid,
+                               static_cast<hipStream_t>(stream));
+}
+
+int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan, int32_t L, float* w, float lr,
+                             float* g_tilde, void* stream) {
+  PView v;
+  int rc = view_of(P, &v);
+  if (rc != TWA_OK) return rc;
+  if (!S || !w) return TWA_ERR_NULL;
+  rc = check_plan(plan, L);
+  if (rc != TWA_OK) return rc;
+  if (!aligned16(w) || (g_tilde && !aligned16(g_tilde)) || (reinterpret_cast<uintptr_t>(S) & 3u))
+    return TWA_ERR_ALIGN;
+  // the per-layer tiling adds up to one tile per layer: let the grid grow to two workgroups per compute unit
+  const int grid = persistent_grid("TWA_EXPAND_LAYERS_GRID", 8);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_expand_update_layers(v, P->dtype, S, plan, L, w, lr, g_tilde, grid, static_cast<hipStream_t>(stream));
+}
+
 int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* out, void* stream) {
   if (!P || !out || !out->data) return TWA_ERR_NULL;
   const int bits = bits_of(out->dtype);

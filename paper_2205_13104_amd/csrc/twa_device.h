@@ -151,6 +151,24 @@ __device__ __forceinline__ float wave_sum(float x) {
   for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, kWave);
   return x;
 }
+// The same sum with data-parallel-primitive adds instead of cross-lane shuffles (no LDS traffic, a
+// few cycles per step): an inclusive scan inside each row of 16 lanes (row_shr 1, 2, 4, 8; lanes
+// without a source add 0), then row_bcast:15 hands each row total to the next row (rows 1 and 3)
+// and row_bcast:31 hands the total of the first half to the second.  LANE 63 ends with the sum of
+// all 64 lanes; the other lanes hold partial sums.  Fixed order: identical bits on every call.
+constexpr int kSumLane = 63;
+__device__ __forceinline__ float wave_sum_to_last_lane(float x) {
+#define TWA_DPP_ADD(ctrl, rows)                                                                              \
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, rows, 0xf, false))
+  TWA_DPP_ADD(0x111, 0xf);
+  TWA_DPP_ADD(0x112, 0xf);
+  TWA_DPP_ADD(0x114, 0xf);
+  TWA_DPP_ADD(0x118, 0xf);
+  TWA_DPP_ADD(0x142, 0xa);
+  TWA_DPP_ADD(0x143, 0xc);
+#undef TWA_DPP_ADD
+  return x;
+}
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, kWave);
@@ -166,6 +184,59 @@ struct PView {
   int32_t n;
   int32_t block_shift;   // log2(block)
   float gscale;
+};
+
+// Layer-wise processing (Sec. 4.5): the tiles of the step kernels are cut per layer.  Layer l =
+// elements [off[l], off[l+1]) is covered by tiles of T elements that start at its first element
+// rounded down to kLayerAlign, so a tile belongs to one layer; the elements of a tile that lie
+// outside its layer (before the start in the layer's first tile, past the end in its last) are
+// masked.  first[l] = index of the first tile of layer l in the global numbering, first[L] = the
+// number of tiles.  The plan is built on the device from the caller's offsets, which it clamps into
+// a non-decreasing table inside [0, D]: the kernels can trust it.
+constexpr int kLayerAlign = 2048;        // elements (= kScaleSpan = the larger tile): the tiles stay on the grid of
+                                         // the whole-model kernels, so loads stay aligned to memory lines and a
+                                         // tile's scales stay one contiguous run; a grid cell that holds a layer
+                                         // boundary simply is a tile of each layer it meets
+struct LayerPlan {
+  const int64_t* off;      // L+1 clamped offsets
+  const int32_t* first;    // L+1 tile indices for the tile size of the kernel at hand
+  int32_t L;
+};
+// Largest l in [0, L-1] with first[l] <= t: the layer that owns tile t (empty layers own none).
+__device__ __forceinline__ int layer_of_tile(const LayerPlan& plan, int64_t t) {
+  int a = 0, b = plan.L - 1;
+  while (a < b) {
+    const int mid = (a + b + 1) >> 1;
+    if (plan.first[mid] <= t) a = mid; else b = mid - 1;
+  }
+  return a;
+}
+
+// Cursor over the layers for a walk through increasing tile indices.  The layer's numbers are kept in
+// registers and re-read only when the walk enters another layer, so finding a tile's place costs
+// no memory access (a dependent scalar load in front of every tile cost 5 % of the projection).
+struct LayerCursor {
+  int cur;
+  int32_t first_cur, first_next;     // tiles [first_cur, first_next) belong to layer cur
+  int64_t lo, hi;                    // its elements
+  __device__ __forceinline__ void load(const LayerPlan& plan, int l) {
+    cur = l;
+    first_cur = plan.first[l];
+    first_next = plan.first[l + 1];
+    lo = plan.off[l];
+    hi = plan.off[l + 1];
+  }
+  // true if tile t lies in a later layer than the cursor (the caller may want to act before moving on)
+  __device__ __forceinline__ bool behind(const LayerPlan& plan, int64_t t) const {
+    return cur < plan.L - 1 && first_next <= t;
+  }
+  __device__ __forceinline__ void seek(const LayerPlan& plan, int64_t t) {
+    while (behind(plan, t)) load(plan, cur + 1);
+  }
+  // first element of tile t of the cursor's layer
+  __device__ __forceinline__ int64_t tile_start(int64_t t, int tile) const {
+    return (lo & ~(int64_t)(kLayerAlign - 1)) + (t - first_cur) * tile;
+  }
 };
 
 // Balanced split of `total` units over `parts` workers: worker w owns [lo, hi).

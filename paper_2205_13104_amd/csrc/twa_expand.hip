@@ -26,7 +26,7 @@
 
 namespace twa {
 
-template <int DT, int U, int VPL>
+template <int DT, int U, int VPL, bool LAYERED>
 struct Expander {
   using S = Store<DT>;
   static constexpr int EPV = S::kEPV;
@@ -37,9 +37,9 @@ struct Expander {
   static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
 
   const PView& P;
-  const float* __restrict__ s;
   int lane;
   uint32_t col_bytes;
+  uint32_t total_spans;
   int64_t ld_bytes;
   int gshift;
   uint32_t span_scale_bytes;
@@ -47,8 +47,9 @@ struct Expander {
   float lr;
   float* tb;                                            // this wave's LDS transpose buffer
 
-  // sums of tile e0 over all basis vectors (for I4 the bias / nibble corrections are applied at the end)
-  __device__ __forceinline__ void accumulate(int64_t e0, float (&acc)[VPL][EPV]) const {
+  // sums of tile e0 over all basis vectors with the coefficients sv[0..n) (for I4 the bias / nibble
+  // corrections are applied at the end)
+  __device__ __forceinline__ void accumulate(int64_t e0, float (&acc)[VPL][EPV], const float* __restrict__ sv) const {
     const int n = P.n;
     float tsum[VPL];
 #pragma unroll
@@ -58,8 +59,13 @@ struct Expander {
       for (int e = 0; e < EPV; ++e) acc[v][e] = 0.0f;
     }
     rsrc_t rs = rw;
-    if constexpr (S::kScaled)
-      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, SPANS * span_scale_bytes);
+    if constexpr (S::kScaled) {
+      // a layer-wise tile need not start on a span boundary: one more span, but never past the array
+      const uint32_t span0 = (uint32_t)(e0 >> kScaleSpanShift);
+      uint32_t spans = SPANS + (LAYERED ? 1 : 0);
+      if constexpr (LAYERED) spans = span0 + spans <= total_spans ? spans : total_spans - span0;
+      rs = make_rsrc(P.scales + (int64_t)span0 * span_scale_bytes, spans * span_scale_bytes);
+    }
     const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);   // tile offset inside its first span
 
     for (int j0 = 0; j0 < n; j0 += U) {
@@ -70,7 +76,7 @@ struct Expander {
         const int j = j0 + u;
         const bool valid = j < n;
         const int col = valid ? j : 0;
-        const float sj = valid ? s[col] : 0.0f;
+        const float sj = valid ? sv[col] : 0.0f;
         const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
@@ -131,9 +137,10 @@ struct Expander {
       *reinterpret_cast<float4*>(buf + lane * ROW + 4 * q) = make_float4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
   }
 
-  // q-th coalesced 128-bit piece of wave-vector v: w <- w - lr * g~, store w (and g~)
-  __device__ __forceinline__ void finish_piece(int64_t e0, int v, int q, float4 gt, const u32x4& wq) const {
-    const int64_t D = P.D;
+  // q-th coalesced 128-bit piece of wave-vector v: w <- w - lr * g~, store w (and g~); only the
+  // elements [lo, hi) are written (the whole vector, or the tile's layer)
+  __device__ __forceinline__ void finish_piece(int64_t e0, int v, int q, float4 gt, const u32x4& wq, uint32_t lo,
+                                               uint32_t hi) const {
     const uint32_t el = piece(e0, v, q);
     const uint32_t off = el * 4u;
     const u32x4 gv = {as_u32(gt.x), as_u32(gt.y), as_u32(gt.z), as_u32(gt.w)};
@@ -142,13 +149,13 @@ struct Expander {
     nw[1] = as_u32(__builtin_fmaf(-lr, gt.y, as_f32(wq[1])));
     nw[2] = as_u32(__builtin_fmaf(-lr, gt.z, as_f32(wq[2])));
     nw[3] = as_u32(__builtin_fmaf(-lr, gt.w, as_f32(wq[3])));
-    if ((int64_t)el + 4 <= D) {
+    if (el >= lo && el + 4 <= hi) {
       st128_through(rw, off, nw);
       st128(rgt, off, gv);          // empty descriptor when g~ is not wanted: dropped
     } else {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        if ((int64_t)el + r < D) {
+        if (el + r >= lo && el + r < hi) {
           st32(rw, off + 4u * r, nw[r]);
           st32(rgt, off + 4u * r, gv[r]);
         }
@@ -156,28 +163,28 @@ struct Expander {
   }
 
   // all pieces of wave-vector v, the sums read back from LDS rows in the coalesced (transposed) order
-  __device__ __forceinline__ void finish_from_rows(int64_t e0, int v, const float* buf,
-                                                   const u32x4 (&wq)[EPV / 4]) const {
+  __device__ __forceinline__ void finish_from_rows(int64_t e0, int v, const float* buf, const u32x4 (&wq)[EPV / 4],
+                                                   uint32_t lo, uint32_t hi) const {
 #pragma unroll
     for (int q = 0; q < EPV / 4; ++q) {
       const uint32_t m = (uint32_t)(q * kWave + lane) * 4u;       // element inside the wave-vector
       const float4 gt = *reinterpret_cast<const float4*>(buf + (m / EPV) * ROW + (m % EPV));
-      finish_piece(e0, v, q, gt, wq[q]);
+      finish_piece(e0, v, q, gt, wq[q], lo, hi);
     }
   }
 
   // transpose the sums of a tile into the coalesced shape and finish it
   __device__ __forceinline__ void update_store(int64_t e0, const float (&acc)[VPL][EPV],
-                                               const u32x4 (&wv)[VPL][EPV / 4]) const {
+                                               const u32x4 (&wv)[VPL][EPV / 4], uint32_t lo, uint32_t hi) const {
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       if constexpr (EPV > 4) {
         rows_to_lds(acc[v], tb);
         wave_lds_sync();
-        finish_from_rows(e0, v, tb, wv[v]);
+        finish_from_rows(e0, v, tb, wv[v], lo, hi);
         wave_lds_sync();
       } else {
-        finish_piece(e0, v, 0, make_float4(acc[v][0], acc[v][1], acc[v][2], acc[v][3]), wv[v][0]);
+        finish_piece(e0, v, 0, make_float4(acc[v][0], acc[v][1], acc[v][2], acc[v][3]), wv[v][0], lo, hi);
       }
     }
   }
@@ -186,11 +193,14 @@ struct Expander {
 // A wave owns `rounds` tiles: tile index = first tile of the workgroup + 4*round + wave.  The
 // sums of the last HOLD of them are kept in registers, those of the one before in LDS (LH = 1), and
 // all of them are written when the wave has finished reading.
-template <int DT, int U, int VPL, int HOLD, int LH>
-__global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float* __restrict__ s,
-                                                            float* __restrict__ w, float lr,
-                                                            float* __restrict__ g_tilde, int rounds) {
-  using X = Expander<DT, U, VPL>;
+// LAYERED (Sec. 4.5): the tiles are cut per layer (see LayerPlan); a tile takes the coefficient row
+// of its layer, and only the elements of its layer are written.
+template <int DT, int U, int VPL, int HOLD, int LH, bool LAYERED>
+__global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const float* __restrict__ s,
+                                                               float* __restrict__ w, float lr,
+                                                               float* __restrict__ g_tilde, int rounds,
+                                                               LayerPlan plan) {
+  using X = Expander<DT, U, VPL, LAYERED>;
   constexpr int EPV = X::EPV;
   __shared__ float tbuf[4][kWave * X::ROW];
   __shared__ float lhold[LH ? 4 : 1][LH ? VPL : 1][LH ? kWave * X::ROW : 1];
@@ -198,15 +208,17 @@ __global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t D = P.D;
-  const int64_t ntiles = (D + X::TILE - 1) / X::TILE;
+  const int64_t ntiles = LAYERED ? (int64_t)plan.first[LAYERED ? plan.L : 0] : (D + X::TILE - 1) / X::TILE;
+  // the number of per-layer tiles is known on the device only: there the tiles per wave are set here
+  if constexpr (LAYERED) rounds = (int)((ntiles + 4 * (int64_t)gridDim.x - 1) / (4 * (int64_t)gridDim.x));
   const int64_t first = (int64_t)blockIdx.x * 4 * rounds + wave;
   const uint32_t w_bytes = (uint32_t)(D * 4);
   // bytes of one stored vector, rounded up to whole dwords: the range check drops a dword that
   // is only partly inside, and the tail bytes are padding of the same vector (ld >= D, ld % 128 == 0)
   const X x{P,
-            s,
             lane,
             (uint32_t)((((D * X::S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3),
+            (uint32_t)(P.ld >> kScaleSpanShift),
             (P.ld * X::S::kBitsPerElem) >> 3,
             kScaleSpanShift - P.block_shift,
             X::S::kScaled ? ((uint32_t)P.n << (kScaleSpanShift - P.block_shift)) * (uint32_t)X::S::kScaleBytes : 0u,
@@ -215,25 +227,50 @@ __global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float
             lr,
             tbuf[wave]};
 
+  // where tile t lies, which elements of it are written and which coefficients it takes.  The
+  // tiles of a wave only move forward, so a layer cursor follows them.
+  struct Where {
+    int64_t e0;
+    uint32_t lo, hi;
+    const float* sv;
+  };
+  // (the plan is read again for every tile: keeping a layer's numbers in registers across the
+  //  tiles costs registers this kernel does not have, and a tile is long enough to hide the loads)
+  const int cur0 = LAYERED && first < ntiles ? layer_of_tile(plan, first) : 0;
+  auto locate = [&](int64_t t, int& c) -> Where {
+    if constexpr (LAYERED) {
+      while (c < plan.L - 1 && plan.first[c + 1] <= t) ++c;
+      const int64_t lo = plan.off[c];
+      int64_t hi = plan.off[c + 1];
+      hi = hi < D ? hi : D;
+      const int64_t e0 = (lo & ~(int64_t)(kLayerAlign - 1)) + (t - plan.first[c]) * X::TILE;
+      return Where{e0, (uint32_t)lo, (uint32_t)hi, s + (int64_t)c * P.n};
+    } else {
+      return Where{t * X::TILE, 0u, (uint32_t)D, s};
+    }
+  };
+  int cur = cur0;                       // cursor of the reading phases
+
   // ---- early rounds (only when a wave owns more tiles than it can hold): written as they finish
   const int early = rounds > HOLD + LH ? rounds - HOLD - LH : 0;
   for (int r = 0; r < early; ++r) {
     const int64_t t = first + 4 * (int64_t)r;
     if (t >= ntiles) break;
-    const int64_t e0 = t * X::TILE;
+    const Where at = locate(t, cur);
     u32x4 wv[VPL][EPV / 4];
-    x.load_w(e0, wv);                     // issued before the stream of P, consumed after it
+    x.load_w(at.e0, wv);                  // issued before the stream of P, consumed after it
     float acc[VPL][EPV];
-    x.accumulate(e0, acc);
-    x.update_store(e0, acc, wv);
+    x.accumulate(at.e0, acc, at.sv);
+    x.update_store(at.e0, acc, wv, at.lo, at.hi);
   }
 
   // ---- the round before the last HOLD ones: its sums wait in LDS ...
   const int64_t t_lds = first + 4 * (int64_t)early;
   const bool lds_tile = LH && rounds > HOLD && t_lds < ntiles;
   if (lds_tile) {
+    const Where at = locate(t_lds, cur);
     float acc[VPL][EPV];
-    x.accumulate(t_lds * X::TILE, acc);
+    x.accumulate(at.e0, acc, at.sv);
 #pragma unroll
     for (int v = 0; v < VPL; ++v) x.rows_to_lds(acc[v], lhold[wave][v]);
   }
@@ -244,51 +281,73 @@ __global__ __launch_bounds__(256) void expand_update_kernel(PView P, const float
 #pragma unroll
   for (int i = 0; i < HOLD; ++i) {
     const int64_t t = first + 4 * (int64_t)(reg0 + i);
-    if (reg0 + i < rounds && t < ntiles) x.accumulate(t * X::TILE, held[i]);
+    if (reg0 + i < rounds && t < ntiles) {
+      const Where at = locate(t, cur);
+      x.accumulate(at.e0, held[i], at.sv);
+    }
   }
-  // ---- ... and everything is written in one burst once this wave has finished reading
+  // ---- ... and everything is written in one burst once this wave has finished reading (the same
+  //      tiles again, found with a cursor of its own)
+  int cur_w = cur0;
   if (lds_tile) {
-    const int64_t e0 = t_lds * X::TILE;
+    const Where at = locate(t_lds, cur_w);
     u32x4 wv[VPL][EPV / 4];
-    x.load_w(e0, wv);
+    x.load_w(at.e0, wv);
     wave_lds_sync();
 #pragma unroll
-    for (int v = 0; v < VPL; ++v) x.finish_from_rows(e0, v, lhold[wave][v], wv[v]);
+    for (int v = 0; v < VPL; ++v) x.finish_from_rows(at.e0, v, lhold[wave][v], wv[v], at.lo, at.hi);
   }
 #pragma unroll
   for (int i = 0; i < HOLD; ++i) {
     const int64_t t = first + 4 * (int64_t)(reg0 + i);
     if (reg0 + i < rounds && t < ntiles) {
-      const int64_t e0 = t * X::TILE;
+      const Where at = locate(t, cur_w);
       u32x4 wv[VPL][EPV / 4];
-      x.load_w(e0, wv);
-      x.update_store(e0, held[i], wv);
+      x.load_w(at.e0, wv);
+      x.update_store(at.e0, held[i], wv, at.lo, at.hi);
     }
   }
 }
 
-template <int DT, int U, int VPL, int HOLD, int LH>
+template <int DT, int U, int VPL, int HOLD, int LH, bool LAYERED>
 static void launch_expand_cfg(const PView& P, const float* s, float* w, float lr, float* g_tilde, int max_grid,
-                              hipStream_t st) {
-  const int tile = kWave * VPL * Store<DT>::kEPV;
+                              hipStream_t st, const void* plan_dev, int L) {
+  constexpr int tile = kWave * VPL * Store<DT>::kEPV;
+  LayerPlan plan{nullptr, nullptr, 1};
   const int64_t ntiles = (P.D + tile - 1) / tile;
   const int64_t rounds = (ntiles + 4 * (int64_t)max_grid - 1) / (4 * (int64_t)max_grid);   // tiles per wave
-  const int grid = (int)((ntiles + 4 * rounds - 1) / (4 * rounds));
-  hipLaunchKernelGGL((expand_update_kernel<DT, U, VPL, HOLD, LH>), dim3(grid), dim3(256), 0, st, P, s, w, lr, g_tilde,
-                     (int)rounds);
+  int grid = (int)((ntiles + 4 * rounds - 1) / (4 * rounds));
+  if constexpr (LAYERED) {
+    plan = plan_view(plan_dev, L, tile);
+    grid = max_grid;                  // the kernel divides the plan's tiles over the grid itself
+  }
+  hipLaunchKernelGGL((expand_update_kernel<DT, U, VPL, HOLD, LH, LAYERED>), dim3(grid), dim3(256), 0, st, P, s, w, lr,
+                     g_tilde, (int)rounds, plan);
+}
+
+// <U, VPL, HOLD, LH> per storage type: chosen by interleaved timing on MI355X at D = 25.6 M, n = 100
+template <bool LAYERED>
+static int launch_expand_any(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde,
+                             int max_grid, hipStream_t st, const void* plan_dev, int L) {
+  switch (dtype) {
+    case TWA_F32: launch_expand_cfg<TWA_F32, 1, 8, 6, 1, LAYERED>(P, s, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_BF16: launch_expand_cfg<TWA_BF16, 2, 4, 6, 1, LAYERED>(P, s, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_I8: launch_expand_cfg<TWA_I8, 4, 2, 6, 1, LAYERED>(P, s, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_I4: launch_expand_cfg<TWA_I4, 8, 1, 5, 0, LAYERED>(P, s, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    default: return TWA_ERR_DTYPE;
+  }
+  return hip_check(hipGetLastError());
 }
 
 int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int max_grid,
                          hipStream_t st) {
-  // <U, VPL, HOLD, LH> per storage type: chosen by interleaved timing on MI355X at D = 25.6 M, n = 100
-  switch (dtype) {
-    case TWA_F32: launch_expand_cfg<TWA_F32, 1, 8, 6, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
-    case TWA_BF16: launch_expand_cfg<TWA_BF16, 2, 4, 6, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
-    case TWA_I8: launch_expand_cfg<TWA_I8, 4, 2, 6, 1>(P, s, w, lr, g_tilde, max_grid, st); break;
-    case TWA_I4: launch_expand_cfg<TWA_I4, 8, 1, 5, 0>(P, s, w, lr, g_tilde, max_grid, st); break;
-    default: return TWA_ERR_DTYPE;
-  }
-  return hip_check(hipGetLastError());
+  return launch_expand_any<false>(P, dtype, s, w, lr, g_tilde, max_grid, st, nullptr, 1);
+}
+
+// Layer-wise: s is L x n, row l holds the coefficients of layer l; `plan_dev` is the device plan.
+int launch_expand_update_layers(const PView& P, int dtype, const float* s, const void* plan_dev, int L, float* w,
+                                float lr, float* g_tilde, int max_grid, hipStream_t st) {
+  return launch_expand_any<true>(P, dtype, s, w, lr, g_tilde, max_grid, st, plan_dev, L);
 }
 
 }  // namespace twa

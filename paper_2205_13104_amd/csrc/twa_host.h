@@ -30,6 +30,15 @@ int launch_project_batched(const PView& P, int dtype, const float* g, int64_t ld
                            int max_grid, hipStream_t st);
 int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int max_grid,
                          hipStream_t st);
+// Layer-wise step: the device plan (see twa_layers.hip) and the kernels that use it.
+struct LayerPlan;
+size_t layer_plan_bytes(int L);
+LayerPlan plan_view(const void* plan_dev, int L, int tile);
+int launch_layer_plan(const int64_t* layer_off, int L, int64_t D, void* plan_dev, hipStream_t st);
+int launch_project_layers(const PView& P, int dtype, const float* g, const void* plan_dev, int L, float* S,
+                          float* partial, int max_grid, hipStream_t st);
+int launch_expand_update_layers(const PView& P, int dtype, const float* s, const void* plan_dev, int L, float* w,
+                                float lr, float* g_tilde, int max_grid, hipStream_t st);
 int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pmat& out, hipStream_t st);
 int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st);
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram, hipStream_t st);

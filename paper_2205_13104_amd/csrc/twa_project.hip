@@ -22,10 +22,18 @@ namespace twa {
 // KB = gradients handled together (1 or TWA_MAX_K slots), U = column slots per chunk,
 // NCH = chunks, so a wave owns up to U*NCH basis vectors; VPL = 128-bit vectors per lane per
 // basis vector and tile.
-template <int DT, int KB, int U, int NCH, int VPL>
+//
+// LAYERED (Sec. 4.5, Alg. 1): every layer has its own n sums.  The tiles are cut per layer (see
+// LayerPlan), so a tile belongs to one layer and the stream over P is the same as for the whole
+// model; the gradient is read through a descriptor that ends with the layer, and the few elements in
+// front of a layer's unaligned start are zeroed in that layer's first tile.  When the workgroup
+// walks into the next layer it reduces its running sums and writes them to partial slot
+// (workgroup + layer): along the walk both indices only grow, so the slot is unique, and the
+// reduction kernel knows from the plan which workgroups contributed to a layer.
+template <int DT, int KB, int U, int NCH, int VPL, bool LAYERED>
 __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __restrict__ g, int64_t ldg,
                                                       int kvalid, float* __restrict__ partial, int cpw,
-                                                      int tiles_per_wg) {
+                                                      int tiles_per_wg, LayerPlan plan) {
   using S = Store<DT>;
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
@@ -35,8 +43,10 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
   const int64_t D = P.D;
-  const int64_t ntiles = (D + TILE - 1) / TILE;
-  // every workgroup owns the same number of consecutive tiles (the last one may own fewer)
+  const int64_t ntiles = LAYERED ? (int64_t)plan.first[LAYERED ? plan.L : 0] : (D + TILE - 1) / TILE;
+  // every workgroup owns the same number of consecutive tiles (the last ones may own fewer); the
+  // number of per-layer tiles is known on the device only, so there the split is made here
+  if constexpr (LAYERED) tiles_per_wg = (int)((ntiles + gridDim.x - 1) / gridDim.x);
   const int64_t t0 = (int64_t)blockIdx.x * tiles_per_wg;
   int64_t t1 = t0 + tiles_per_wg;
   if (t1 > ntiles) t1 = ntiles;
@@ -51,7 +61,7 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
   const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
   const int gshift = kScaleSpanShift - P.block_shift;            // log2(scales per span and vector)
   const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes : 0u;
-  const uint32_t g_bytes = (uint32_t)(D * 4);
+  const uint32_t total_spans = (uint32_t)(P.ld >> kScaleSpanShift);
 
   float acc[SLOTS][KB];
 #pragma unroll
@@ -59,11 +69,42 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
 #pragma unroll
     for (int c = 0; c < KB; ++c) acc[sl][c] = 0.0f;
 
-  for (int64_t t = t0; t < t1; ++t) {
-    const int64_t e0 = t * TILE;
+  // one reduction over the wave's lanes, then the partial sums of row `slot_row`
+  auto flush = [&](int slot_row) {
+#pragma unroll
+    for (int sl = 0; sl < SLOTS; ++sl) {
+#pragma unroll
+      for (int c = 0; c < KB; ++c) {
+        const float tot = wave_sum_to_last_lane(acc[sl][c]);
+        if (lane == kSumLane && sl < ncol && c < kvalid)
+          partial[((int64_t)slot_row * kvalid + c) * P.n + c0 + sl] = tot;
+        if constexpr (LAYERED) acc[sl][c] = 0.0f;
+      }
+    }
+  };
 
-    // ---- this lane's slice of the gradient(s); the descriptor ends at element D, and the range
-    //      check is per dword, so elements past the ragged end arrive as 0 --------------------
+  LayerCursor lc{0, 0, 0, 0, 0};        // layer of the tile at hand
+  if constexpr (LAYERED) {
+    if (t0 < t1) lc.load(plan, layer_of_tile(plan, t0));
+  }
+
+  for (int64_t t = t0; t < t1; ++t) {
+    int64_t e0 = t * TILE;
+    uint32_t g_bytes = (uint32_t)(D * 4);
+    uint32_t head = 0;                  // elements of this tile in front of its layer's first element
+    if constexpr (LAYERED) {
+      if (lc.behind(plan, t)) {                                  // this tile starts the next (non-empty) layer
+        flush((int)blockIdx.x + lc.cur);                         // a workgroup never holds a layer without tiles
+        lc.seek(plan, t);
+      }
+      const int64_t hi = lc.hi < D ? lc.hi : D;
+      e0 = lc.tile_start(t, TILE);
+      g_bytes = (uint32_t)(hi * 4);                              // the gradient ends with the layer
+      head = lc.lo > e0 ? (uint32_t)(lc.lo - e0 < TILE ? lc.lo - e0 : TILE) : 0u;
+    }
+
+    // ---- this lane's slice of the gradient(s); the descriptor ends at element D (at the end of
+    //      the layer), and the range check is per dword, so elements past that end arrive as 0 --
     float gs[KB][VPL][EPV];
     float gcorr[KB][VPL];
 #pragma unroll
@@ -77,6 +118,13 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
           const u32x4 x = ld128(rg, (elem + 4u * q) * 4u);   // shared by the 4 waves: keep it cacheable
 #pragma unroll
           for (int r = 0; r < 4; ++r) gs[c][v][4 * q + r] = as_f32(x[r]);
+        }
+        if constexpr (LAYERED) {
+          if (head != 0) {                                   // first tile of a layer with an unaligned start
+            const uint32_t rel = (uint32_t)(v * kWave + lane) * EPV;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) gs[c][v][e] = rel + e >= head ? gs[c][v][e] : 0.0f;
+          }
         }
         if constexpr (DT == TWA_I4) {
           float sum = 0.0f;
@@ -93,9 +141,14 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
 
     // ---- stream this wave's basis vectors over the tile ----------------------------------
     rsrc_t rs = make_rsrc(g, 0u);
-    constexpr int SPANS = TILE > kScaleSpan ? TILE / kScaleSpan : 1;       // scale spans one tile touches
-    if constexpr (S::kScaled)
-      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, SPANS * span_scale_bytes);
+    // scale spans one tile touches (a layer-wise tile need not start on a span boundary)
+    constexpr int SPANS = (TILE > kScaleSpan ? TILE / kScaleSpan : 1) + (LAYERED ? 1 : 0);
+    if constexpr (S::kScaled) {
+      const uint32_t span0 = (uint32_t)(e0 >> kScaleSpanShift);
+      uint32_t spans = SPANS;
+      if constexpr (LAYERED) spans = span0 + spans <= total_spans ? spans : total_spans - span0;   // stay inside the array
+      rs = make_rsrc(P.scales + (int64_t)span0 * span_scale_bytes, spans * span_scale_bytes);
+    }
     const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);   // tile offset inside its first span
     // chunk ch = column slots [ch*U, (ch+1)*U): fetch (128-bit codes/values + block scales) ...
     auto load_chunk = [&](int ch, u32x4 (&raw)[U][VPL], float (&sc)[U][VPL]) {
@@ -163,15 +216,10 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
     }
   }
 
-  // ---- one reduction over the wave's lanes, then the per-workgroup partial sums -----------
-#pragma unroll
-  for (int sl = 0; sl < SLOTS; ++sl) {
-#pragma unroll
-    for (int c = 0; c < KB; ++c) {
-      const float tot = wave_sum(acc[sl][c]);
-      if (lane == 0 && sl < ncol && c < kvalid)
-        partial[((int64_t)blockIdx.x * kvalid + c) * P.n + c0 + sl] = tot;
-    }
+  if constexpr (LAYERED) {
+    if (t0 < t1) flush((int)blockIdx.x + lc.cur);
+  } else {
+    flush((int)blockIdx.x);
   }
 }
 
@@ -324,8 +372,8 @@ __global__ __launch_bounds__(256) void project_batched_kernel(PView P, const flo
   for (int sl = 0; sl < SLOTS; ++sl) {
 #pragma unroll
     for (int c = 0; c < KB; ++c) {
-      const float tot = wave_sum(acc[sl][c]);
-      if (lane == 0 && sl < ncol && c < kvalid)
+      const float tot = wave_sum_to_last_lane(acc[sl][c]);
+      if (lane == kSumLane && sl < ncol && c < kvalid)
         partial[((int64_t)blockIdx.x * kvalid + c) * P.n + c0 + sl] = tot;
     }
   }
@@ -350,17 +398,19 @@ static void divide_tiles(int64_t D, int tile, int max_grid, int* grid, int* tile
   *grid = (int)((ntiles + per - 1) / per);
 }
 
-template <int DT, int KB, int VPL>
+template <int DT, int KB, int VPL, bool LAYERED = false>
 static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kvalid, float* partial, int max_grid,
-                             int* grid_out, hipStream_t st) {
+                             int* grid_out, hipStream_t st, LayerPlan plan = LayerPlan{nullptr, nullptr, 1}) {
   const int cpw = (P.n + 3) / 4;
+  constexpr int tile = kWave * VPL * Store<DT>::kEPV;
   int grid, tiles_per_wg;
-  divide_tiles(P.D, kWave * VPL * Store<DT>::kEPV, max_grid, &grid, &tiles_per_wg);
+  divide_tiles(P.D, tile, max_grid, &grid, &tiles_per_wg);
+  if (LAYERED) grid = max_grid;      // the kernel divides the plan's tiles over the grid itself
   *grid_out = grid;
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
 #define TWA_LAUNCH(U_, NCH_)                                                                         \
-  hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
-                     kvalid, partial, cpw, tiles_per_wg)
+  hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL, LAYERED>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
+                     kvalid, partial, cpw, tiles_per_wg, plan)
   {
     if (cpw == 25) {
       TWA_LAUNCH(5, 5);
@@ -395,6 +445,49 @@ int launch_project(const PView& P, int dtype, const float* g, float* s, float* p
   if (rc != TWA_OK) return rc;
   hipLaunchKernelGGL(project_reduce_kernel, dim3(P.n), dim3(kWave), 0, st, partial, grid, P.n, s);
   return hip_check(hipGetLastError());
+}
+
+// S[l][j] = sum of the partial slots (b + l) of the workgroups b that own tiles of layer l, in
+// workgroup order, accumulated in fp64.  One block per layer, one thread per basis vector.
+__global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_kernel(const float* __restrict__ partial, int n,
+                                                                         LayerPlan plan, int grid,
+                                                                         float* __restrict__ S) {
+  const int l = blockIdx.x;
+  const int j = threadIdx.x;
+  if (j >= n) return;
+  const int ntiles = plan.first[plan.L];
+  const int tiles_per_wg = ntiles > 0 ? (ntiles + grid - 1) / grid : 1;      // as in project_kernel
+  const int32_t ta = plan.first[l], tb = plan.first[l + 1];          // tiles [ta, tb)
+  double a = 0.0;
+  if (tb > ta) {
+    const int b0 = ta / tiles_per_wg, b1 = (tb - 1) / tiles_per_wg;
+    for (int b = b0; b <= b1; ++b) a += (double)partial[(int64_t)(b + l) * n + j];
+  }
+  S[(int64_t)l * n + j] = (float)a;
+}
+
+template <int DT, int VPL>
+static int launch_project_layers_dt(const PView& P, const float* g, const void* plan_dev, int L, float* S,
+                                    float* partial, int max_grid, hipStream_t st) {
+  constexpr int tile = kWave * VPL * Store<DT>::kEPV;
+  const LayerPlan plan = plan_view(plan_dev, L, tile);
+  int grid = 0;
+  int rc = launch_project_dt<DT, 1, VPL, true>(P, g, 0, 1, partial, max_grid, &grid, st, plan);
+  if (rc != TWA_OK) return rc;
+  hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, S);
+  return hip_check(hipGetLastError());
+}
+
+// Layer-wise projection.  `partial` holds (max_grid + L) * n floats.
+int launch_project_layers(const PView& P, int dtype, const float* g, const void* plan_dev, int L, float* S,
+                          float* partial, int max_grid, hipStream_t st) {
+  switch (dtype) {
+    case TWA_F32: return launch_project_layers_dt<TWA_F32, 4>(P, g, plan_dev, L, S, partial, max_grid, st);
+    case TWA_BF16: return launch_project_layers_dt<TWA_BF16, 2>(P, g, plan_dev, L, S, partial, max_grid, st);
+    case TWA_I8: return launch_project_layers_dt<TWA_I8, 2>(P, g, plan_dev, L, S, partial, max_grid, st);
+    case TWA_I4: return launch_project_layers_dt<TWA_I4, 1>(P, g, plan_dev, L, S, partial, max_grid, st);
+    default: return TWA_ERR_DTYPE;
+  }
 }
 
 // k > 1 gradients.  Up to 32 basis vectors (and not int4, whose 32-element vectors leave no

@@ -118,3 +118,75 @@ def gradient(D: int, sigma: float, seed: int, step: int = 0, device="cpu", k: in
     for c in range(k):
         G[c, :D] = torch.randn(D, generator=gen, device=device, dtype=torch.float32) * sigma
     return G
+
+
+# --------------------------------------------------------------------------- layer structure (Sec. 4.5)
+def _bn(c):
+    return [c, c]                                   # scale and shift of one normalisation layer
+
+
+def resnet_bottleneck_sizes(blocks=(3, 4, 6, 3), classes=1000):
+    """Sizes of the parameter tensors, in definition order, of a bottleneck residual network with a
+    7x7 stem (stage widths 64/128/256/512, expansion 4).  blocks = (3, 4, 6, 3) is the ResNet-50
+    shape: 161 tensors, 25,557,032 parameters -- convolutions next to 64-element normalisation
+    vectors, which is what makes the layer-wise reduction ragged."""
+    sizes = [64 * 3 * 7 * 7] + _bn(64)
+    cin = 64
+    for stage, nb in enumerate(blocks):
+        p = 64 << stage
+        for b in range(nb):
+            sizes += [cin * p] + _bn(p) + [p * p * 9] + _bn(p) + [p * 4 * p] + _bn(4 * p)
+            if b == 0:
+                sizes += [cin * 4 * p] + _bn(4 * p)     # projection shortcut
+            cin = 4 * p
+    return sizes + [cin * classes, classes]
+
+
+def resnet_basic_sizes(blocks=(2, 2, 2, 2), classes=10):
+    """Same for a basic-block residual network with a 3x3 stem (the CIFAR ResNet-18 shape:
+    62 tensors, 11,173,962 parameters at 10 classes)."""
+    sizes = [64 * 3 * 9] + _bn(64)
+    cin = 64
+    for stage, nb in enumerate(blocks):
+        p = 64 << stage
+        for b in range(nb):
+            sizes += [cin * p * 9] + _bn(p) + [p * p * 9] + _bn(p)
+            if cin != p:
+                sizes += [cin * p] + _bn(p)
+            cin = p
+    return sizes + [cin * classes, classes]
+
+
+def random_layer_sizes(D: int, L: int, seed: int = 0):
+    """L layer sizes that add up to D, log-uniform between tiny and large, a few of them empty."""
+    gen = _gen(seed, "cpu")
+    wgt = torch.exp(torch.rand(L, generator=gen, dtype=torch.float64) * 9.0)
+    wgt[torch.rand(L, generator=gen) < 0.05] = 0.0
+    if float(wgt.sum()) == 0.0:
+        wgt[0] = 1.0
+    cuts = torch.floor(torch.cumsum(wgt, 0) / wgt.sum() * D).to(torch.int64)
+    cuts[-1] = D
+    prev = torch.cat([torch.zeros(1, dtype=torch.int64), cuts[:-1]])
+    return [int(x) for x in (cuts - prev)]
+
+
+def layer_offsets(sizes) -> torch.Tensor:
+    """Offsets (L+1 int64 values, CPU): layer l covers elements [off[l], off[l+1])."""
+    off = torch.zeros(len(sizes) + 1, dtype=torch.int64)
+    off[1:] = torch.cumsum(torch.tensor(list(sizes), dtype=torch.int64), 0)
+    return off
+
+
+def workload_layers(name: str) -> torch.Tensor:
+    """Layer offsets of a benchmark workload: the architecture's own tensors where the parameter
+    count identifies it, otherwise 150 seeded ragged layers."""
+    wl = WORKLOADS[name]
+    if name == "imagenet_resnet50":
+        sizes = resnet_bottleneck_sizes()
+    elif name == "cifar_resnet18":
+        sizes = resnet_basic_sizes()
+    else:
+        sizes = random_layer_sizes(wl.D, 150 if wl.D > 10_000_000 else 12, seed=11)
+    off = layer_offsets(sizes)
+    assert int(off[-1]) == wl.D, (name, int(off[-1]), wl.D)
+    return off

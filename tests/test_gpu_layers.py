@@ -1,0 +1,167 @@
+"""Parity of the layer-wise calls (Sec. 4.5, Alg. 1) of the HIP library against the fp64 oracle on the
+same stored P: S (L x n), g~ and w within a relative L2 error of 1e-5, for every storage type, with
+layer tables that put boundaries at odd positions, several boundaries into one tile and into one
+128-bit vector, one-element and empty layers, and layers that span many tiles and workgroups."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import twa_oracle as orc
+from paper_2205_13104_amd import binding as twa
+from paper_2205_13104_amd import synth
+from tests.gpu_common import REL_L2_TOL, random_basis_like, rel_l2, store_as, to_oracle
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [twa.F32, twa.BF16, twa.I8, twa.I4]
+NAMES = {twa.F32: "f32", twa.BF16: "bf16", twa.I8: "i8", twa.I4: "i4"}
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def hand_made_sizes(D):
+    """Boundaries inside one 128-bit vector, one-element and empty layers, then long layers."""
+    head = [5, 1, 1, 0, 2, 30, 64, 64, 0, 0, 3, 2048, 1000, 4097, 17]
+    assert D > sum(head) + 10
+    rest = D - sum(head)
+    return head + [rest // 2, 0, rest - rest // 2 - 1, 1]
+
+
+def layer_tables(D):
+    yield "hand", hand_made_sizes(D)
+    yield "random40", synth.random_layer_sizes(D, 40, seed=D % 97)
+    yield "random700", synth.random_layer_sizes(D, 700, seed=5)
+    yield "one", [D]
+    yield "ends_empty", [0, D, 0]
+
+
+def check_layers(D, n, dtype, name, sizes, seed):
+    off_cpu = synth.layer_offsets(sizes)
+    L = len(sizes)
+    off = twa.LayerPlan(off_cpu, D)
+    P32 = random_basis_like(D, n, seed=seed)
+    pm = store_as(P32, D, dtype)
+    po = to_oracle(pm)
+    g = synth.gradient(D, 1e-2, seed=seed, device="cuda")
+    say("layers", NAMES[dtype], "D", D, "n", n, name, "L", L)
+
+    S = twa.project_layers(pm, g, off)
+    torch.cuda.synchronize()
+    S_ref = orc.project_layers(po, g.cpu().numpy().astype(np.float64), off_cpu.numpy())
+    Sg = S.cpu().numpy()
+    assert Sg.shape == (L, n)
+    assert rel_l2(Sg, S_ref) <= REL_L2_TOL
+    scale = np.abs(S_ref).max()
+    for l in range(L):
+        if sizes[l] == 0:
+            assert np.all(Sg[l] == 0.0)
+        else:
+            # row by row, against the row's own size or (for rows that cancel to almost nothing) the largest entry
+            assert np.linalg.norm(Sg[l] - S_ref[l]) <= REL_L2_TOL * max(np.linalg.norm(S_ref[l]), scale), (l, sizes[l])
+
+    # expansion with coefficients of its own (not the projection's output): every row matters
+    gen = torch.Generator().manual_seed(seed + 1)
+    S2 = torch.randn((L, n), generator=gen, dtype=torch.float32).cuda()
+    w0 = synth.gradient(D, 0.05, seed=seed + 2, device="cuda")
+    for want_gt in (True, False):
+        w = w0.clone()
+        gt = torch.full((D,), float("nan"), device="cuda") if want_gt else None
+        twa.expand_update_layers(pm, S2, off, w, 0.1, gt)
+        torch.cuda.synchronize()
+        w_ref = w0.cpu().numpy().astype(np.float64)
+        gt_ref = orc.expand_update_layers(po, S2.cpu().numpy().astype(np.float64), off_cpu.numpy(), w_ref,
+                                          float(np.float32(0.1)), want_gt=True)
+        if want_gt:
+            assert rel_l2(gt.cpu().numpy(), gt_ref) <= REL_L2_TOL
+            # layer by layer as well: a wrong row for a small layer must not hide in the total
+            # (against the layer's own norm, or for a few elements that cancel to almost nothing the typical size)
+            gg = gt.cpu().numpy()
+            rms = float(np.sqrt(np.mean(gt_ref ** 2)))
+            for l in range(L):
+                a, b = int(off_cpu[l]), int(off_cpu[l + 1])
+                if b > a:
+                    bound = max(np.linalg.norm(gt_ref[a:b]), rms * (b - a) ** 0.5)
+                    assert np.linalg.norm(gg[a:b] - gt_ref[a:b]) <= 2 * REL_L2_TOL * bound, (l, a, b)
+        assert rel_l2(w.cpu().numpy(), w_ref) <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=[NAMES[d] for d in DTYPES])
+@pytest.mark.parametrize("D,n", [(70001, 7), (300_017, 100), (1_234_567, 33)])
+def test_layers_match_oracle(dtype, D, n):
+    for name, sizes in layer_tables(D):
+        check_layers(D, n, dtype, name, sizes, seed=D % 1000 + n)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=[NAMES[d] for d in DTYPES])
+def test_layers_n128_many_workgroups(dtype):
+    D = 9_000_011
+    check_layers(D, 128, dtype, "random40", synth.random_layer_sizes(D, 40, seed=3), seed=77)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=[NAMES[d] for d in DTYPES])
+def test_one_layer_reproduces_the_whole_model_calls_bit_for_bit(dtype):
+    D, n = 2_000_003, 100
+    pm = store_as(random_basis_like(D, n, seed=9), D, dtype)
+    g = synth.gradient(D, 1e-2, seed=9, device="cuda")
+    off = twa.LayerPlan([0, D], D)
+    s = twa.project(pm, g)
+    S = twa.project_layers(pm, g, off)
+    assert torch.equal(S[0], s)
+    w1 = synth.gradient(D, 0.05, seed=10, device="cuda")
+    w2 = w1.clone()
+    twa.expand_update(pm, s, w1, 0.25)
+    twa.expand_update_layers(pm, S, off, w2, 0.25)
+    assert torch.equal(w1, w2)
+
+
+def test_layer_rows_add_up_to_the_whole_model_projection():
+    D, n = 3_000_017, 100
+    pm = store_as(random_basis_like(D, n, seed=12), D, twa.I8)
+    g = synth.gradient(D, 1e-2, seed=12, device="cuda")
+    off = twa.LayerPlan(synth.layer_offsets(synth.random_layer_sizes(D, 300, seed=1)), D)
+    S = twa.project_layers(pm, g, off)
+    s = twa.project(pm, g)
+    assert rel_l2(S.double().sum(0).cpu().numpy(), s.double().cpu().numpy()) <= 1e-6
+    # deterministic: same bits on every call
+    assert torch.equal(S, twa.project_layers(pm, g, off))
+
+
+def test_plan_tables():
+    D = 10_000
+    plan = twa.LayerPlan([0, 5, 5, 40, 2100, 2100, 9000, D], D)
+    off, f2048, f1024 = plan.tables()
+    assert off.tolist() == [0, 5, 5, 40, 2100, 2100, 9000, D]
+    # tiles start at the layer's first element rounded down to 2048 elements
+    assert f2048.tolist() == [0, 1, 1, 2, 4, 4, 8, 9]
+    assert f1024.tolist() == [0, 1, 1, 2, 5, 5, 12, 14]
+    # a table that breaks the rules is clamped into one that keeps them
+    bad = twa.LayerPlan([7, 50, 20, -3, 99999, D], D)
+    off, f2048, _ = bad.tables()
+    assert off.tolist() == [0, 50, 50, 50, D, D]
+    assert f2048.tolist()[-1] == 1 + 5
+
+
+def test_layer_argument_errors():
+    import ctypes as C
+    D, n = 5000, 4
+    pm = store_as(random_basis_like(D, n, seed=1), D, twa.F32)
+    g = torch.zeros(D, device="cuda")
+    plan = twa.LayerPlan([0, 100, D], D)
+    S = torch.zeros((2, n), device="cuda")
+    ws = twa.Workspace(twa.project_layers_workspace_bytes(n, 2))
+    st = pm.c_struct()
+    L = twa.lib()
+    assert L.twa_project_layers(C.byref(st), g.data_ptr(), None, 2, S.data_ptr(), ws.ptr, ws.nbytes, None) == twa.ERR_NULL
+    assert L.twa_project_layers(C.byref(st), g.data_ptr(), plan.ptr, 0, S.data_ptr(), ws.ptr, ws.nbytes,
+                                None) == twa.ERR_SHAPE
+    assert L.twa_project_layers(C.byref(st), g.data_ptr(), plan.ptr, twa.MAX_LAYERS + 1, S.data_ptr(), ws.ptr,
+                                ws.nbytes, None) == twa.ERR_SHAPE
+    assert L.twa_project_layers(C.byref(st), g.data_ptr(), plan.ptr, 2, S.data_ptr(), ws.ptr, 64,
+                                None) == twa.ERR_WORKSPACE
+    assert L.twa_expand_update_layers(C.byref(st), S.data_ptr(), None, 2, g.data_ptr(), 0.1, None, None) == twa.ERR_NULL
+    assert L.twa_expand_update_layers(C.byref(st), S.data_ptr(), plan.ptr + 4, 2, g.data_ptr(), 0.1, None,
+                                      None) == twa.ERR_ALIGN
+    assert L.twa_layer_plan(plan.layer_off.data_ptr(), 2, D, plan.ptr, 8, None) == twa.ERR_WORKSPACE
+    assert L.twa_layer_plan(None, 2, D, plan.ptr, 1 << 20, None) == twa.ERR_NULL
