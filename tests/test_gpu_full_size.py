@@ -119,6 +119,40 @@ def test_imagenet_resnet50_int8_full_size():
     # rerun determinism at full size
     s2 = twa.project(pm, g)
     assert torch.equal(s1, s2)
+    check_layer_step_sampled(pm, D, n, g, w, wl.lr, synth.workload_layers(wl.name), seed=3, cols=[0, 57, n - 1])
+
+
+def check_layer_step_sampled(pm, D, n, g, w, lr, off_cpu, seed, cols, nblocks=48, block=128):
+    """The layer-wise step (Sec. 4.5) at full size with the architecture's own layer table: sampled columns of
+    S over the whole of D, g~ / w on sampled blocks next to layer boundaries and random ones."""
+    L = int(off_cpu.numel()) - 1
+    plan = twa.LayerPlan(off_cpu, D)
+    S = twa.project_layers(pm, g, plan)
+    w0 = w.clone()
+    gt = torch.empty(D, device="cuda")
+    twa.expand_update_layers(pm, S, plan, w, lr, gt)
+    torch.cuda.synchronize()
+    offs = off_cpu.numpy()
+    So = orc.project_layers(to_oracle(pm, cols=cols), g.cpu().numpy().astype(np.float64), offs)
+    e_s = rel_l2(S[:, cols].cpu().numpy(), So)
+    say("  layer-wise: L", L, "rel_l2 S[:, sampled]", e_s)
+    assert e_s <= REL_L2_TOL
+    nb = D // block
+    r = np.random.default_rng(seed)
+    near = [int(o) // block for o in offs[1:-1]] + [max(0, int(o) // block - 1) for o in offs[1:-1]]
+    ids = sorted(set([0, nb - 1] + r.integers(0, nb, size=nblocks).tolist() + r.choice(near, size=40).tolist()))
+    rows, po = sampled_blocks_pmat(pm, ids, block)
+    rows_np = rows.cpu().numpy()
+    off_sub = np.searchsorted(rows_np, offs, side="left").astype(np.int64)     # the layer table of the sampled rows
+    wo = w0[rows].cpu().numpy().astype(np.float64)
+    gto = orc.expand_update_layers(po, S.cpu().numpy().astype(np.float64), off_sub, wo, lr, want_gt=True)
+    e_gt, e_w = rel_l2(gt[rows].cpu().numpy(), gto), rel_l2(w[rows].cpu().numpy(), wo)
+    say("  layer-wise: rel_l2 g~[sampled]", e_gt, "w[sampled]", e_w)
+    assert e_gt <= REL_L2_TOL and e_w <= REL_L2_TOL
+    # the rows of S add up to the whole-model coefficients
+    s = twa.project(pm, g)
+    assert rel_l2(S.double().sum(0).cpu().numpy(), s.double().cpu().numpy()) <= 1e-6
+    assert torch.isfinite(w).all() and torch.isfinite(gt).all()
 
 
 def test_cifar_resnet18_fp32_full_size():
