@@ -228,6 +228,47 @@ int twa_project_layers(const twa_pmat* P, const float* g, const void* plan, int3
 int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan, int32_t L, float* w, float lr,
                              float* g_tilde, void* stream);
 
+/*
+ * The paper's default basis and the coefficient form of the step (Sec. 4.1, extraction of base
+ * vectors; Sec. 4.3, initialisation; Sec. 4.5; Alg. 1).  With one layer (L = 1) these are the
+ * whole-model forms.
+ */
+
+/* Workspace (device bytes) needed by twa_centre_normalise. */
+int twa_centre_normalise_workspace_bytes(int64_t D, int32_t n, int32_t L, size_t* bytes);
+
+/*
+ * wbar = (1/n) sum_j w_j ;  e_j^l = (w_j^l - wbar^l) / ||w_j^l - wbar^l||_2   for every layer l
+ * (Sec. 4.1 / 4.5).  The vectors of a layer are NOT orthogonal and sum to zero after scaling by their
+ * norms (rank <= n-1 per layer); a (layer, checkpoint) pair whose centred part is exactly zero gives
+ * a zero vector (the paper does not say; a zero direction changes nothing).
+ *   W     [in]  n checkpoints, fp32, checkpoint j at W[j*ldw .. j*ldw + D).
+ *   wbar  [out] D floats: the mean (the SWA point the averaging starts from, Sec. 4.3); the sum is
+ *               accumulated in fp64 in checkpoint order and rounded once.
+ *   E     [out] n vectors with leading dimension lde, padding zeroed; E == W (lde == ldw) works
+ *               in place, any other overlap is an error.  Feed it to twa_quantize.
+ *   norms [out, optional] L*n floats: ||w_j^l - wbar^l||_2.
+ *   ws, ws_bytes  device workspace of at least twa_centre_normalise_workspace_bytes(D, n, L).
+ * Asynchronous on `stream`; a few passes over W.
+ */
+int twa_centre_normalise(const float* W, int64_t D, int32_t n, int64_t ldw, const void* plan, int32_t L, float* wbar,
+                         float* E, int64_t lde, float* norms, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * beta <- (1 - lr*lambda) * beta - lr * s   (Alg. 1, "update variables"; `count` = L*n entries).
+ * `s` is what twa_project_layers returned, or that after the caller's momentum / Adam.  The decay
+ * acts on the coefficients, i.e. on w - wbar.
+ */
+int twa_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, void* stream);
+
+/*
+ * w^l = wbar^l + P^l beta^l   (Alg. 1, "update weights"; Sec. 4.3).  The same pass over P as
+ * twa_expand_update_layers.
+ *   beta [in] L*n floats.   wbar [in] D floats.   w [out] D floats (may be wbar's buffer).
+ */
+int twa_weights_from_beta(const twa_pmat* P, const float* beta, const void* plan, int32_t L, const float* wbar,
+                          float* w, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

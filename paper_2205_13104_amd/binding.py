@@ -66,8 +66,13 @@ def lib():
         L.twa_expand_update_layers.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, f32, vp, vp]
         L.twa_layer_plan_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
         L.twa_layer_plan.argtypes = [vp, i32, i64, vp, C.c_size_t, vp]
+        L.twa_centre_normalise_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(C.c_size_t)]
+        L.twa_centre_normalise.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp, i64, vp, vp, C.c_size_t, vp]
+        L.twa_beta_update.argtypes = [vp, vp, i64, f32, f32, vp]
+        L.twa_weights_from_beta.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, vp, vp]
         for f in (L.twa_project_layers_workspace_bytes, L.twa_project_layers, L.twa_expand_update_layers,
-                  L.twa_layer_plan_bytes, L.twa_layer_plan):
+                  L.twa_layer_plan_bytes, L.twa_layer_plan, L.twa_centre_normalise_workspace_bytes,
+                  L.twa_centre_normalise, L.twa_beta_update, L.twa_weights_from_beta):
             f.restype = C.c_int
         for f in (L.twa_pmat_bytes, L.twa_project_workspace_bytes, L.twa_build_basis_workspace_bytes,
                   L.twa_build_basis, L.twa_quantize, L.twa_project, L.twa_expand_update):
@@ -280,6 +285,45 @@ def expand_update_layers(P: Pmat, S: torch.Tensor, plan: LayerPlan, w: torch.Ten
     st = P.c_struct()
     _check(lib().twa_expand_update_layers(C.byref(st), _ptr(S), plan.ptr, L, _ptr(w), float(lr),
                                           _ptr(g_tilde), _stream()), "twa_expand_update_layers")
+
+
+def centre_normalise(W: torch.Tensor, D: int, plan: LayerPlan, out: Optional[torch.Tensor] = None,
+                     want_norms: bool = True):
+    """twa_centre_normalise: the paper's default (layer-wise) basis.  W: (n, ldw) float32 device tensor.
+
+    out=None allocates E; out=W works in place.  Returns (E, wbar (D,), norms (L, n) or None)."""
+    assert W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous() and plan.D == D
+    n, ldw = W.shape
+    E = torch.empty_like(W) if out is None else out
+    wbar = torch.empty(D, dtype=torch.float32, device=W.device)
+    norms = torch.empty((plan.L, n), dtype=torch.float32, device=W.device) if want_norms else None
+    nb = C.c_size_t()
+    _check(lib().twa_centre_normalise_workspace_bytes(D, n, plan.L, C.byref(nb)), "twa_centre_normalise_workspace_bytes")
+    ws = Workspace(int(nb.value), device=W.device)
+    _check(lib().twa_centre_normalise(_ptr(W), D, n, ldw, plan.ptr, plan.L, _ptr(wbar), _ptr(E), int(E.shape[1]),
+                                      _ptr(norms), ws.ptr, ws.nbytes, _stream()), "twa_centre_normalise")
+    return E, wbar, norms
+
+
+def beta_update(beta: torch.Tensor, s: torch.Tensor, lr: float, lam: float = 0.0) -> None:
+    """twa_beta_update: beta <- (1 - lr*lam) * beta - lr * s, in place."""
+    assert beta.dtype == torch.float32 and s.dtype == torch.float32 and beta.shape == s.shape
+    assert beta.is_contiguous() and s.is_contiguous()
+    _check(lib().twa_beta_update(_ptr(beta), _ptr(s), beta.numel(), float(lr), float(lam), _stream()),
+           "twa_beta_update")
+
+
+def weights_from_beta(P: Pmat, beta: torch.Tensor, plan: LayerPlan, wbar: torch.Tensor,
+                      w: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """twa_weights_from_beta: w = wbar + P beta, layer by layer."""
+    assert beta.dtype == torch.float32 and beta.is_contiguous() and tuple(beta.shape) == (plan.L, P.n)
+    assert wbar.dtype == torch.float32 and wbar.is_contiguous() and wbar.numel() == P.D and plan.D == P.D
+    if w is None:
+        w = torch.empty_like(wbar)
+    st = P.c_struct()
+    _check(lib().twa_weights_from_beta(C.byref(st), _ptr(beta), plan.ptr, plan.L, _ptr(wbar), _ptr(w), _stream()),
+           "twa_weights_from_beta")
+    return w
 
 
 def build_basis(W: torch.Tensor, D: int, out: Optional[torch.Tensor] = None, want_R: bool = True,

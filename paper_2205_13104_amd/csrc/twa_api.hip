@@ -305,7 +305,65 @@ int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan
   // the per-layer tiling adds up to one tile per layer: let the grid grow to two workgroups per compute unit
   const int grid = persistent_grid("TWA_EXPAND_LAYERS_GRID", 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
-  return launch_expand_update_layers(v, P->dtype, S, plan, L, w, lr, g_tilde, grid, static_cast<hipStream_t>(stream));
+  return launch_expand_update_layers(v, P->dtype, S, plan, L, w, w, lr, g_tilde, grid,
+                                     static_cast<hipStream_t>(stream));
+}
+
+int twa_weights_from_beta(const twa_pmat* P, const float* beta, const void* plan, int32_t L, const float* wbar,
+                          float* w, void* stream) {
+  PView v;
+  int rc = view_of(P, &v);
+  if (rc != TWA_OK) return rc;
+  if (!beta || !wbar || !w) return TWA_ERR_NULL;
+  rc = check_plan(plan, L);
+  if (rc != TWA_OK) return rc;
+  if (!aligned16(w) || !aligned16(wbar) || (reinterpret_cast<uintptr_t>(beta) & 3u)) return TWA_ERR_ALIGN;
+  const int grid = persistent_grid("TWA_EXPAND_LAYERS_GRID", 8);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  // w = wbar - (-1) * (P beta): the expansion kernel with the mean as the weights it reads
+  return launch_expand_update_layers(v, P->dtype, beta, plan, L, wbar, w, -1.0f, nullptr, grid,
+                                     static_cast<hipStream_t>(stream));
+}
+
+int twa_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, void* stream) {
+  if (!beta || !s) return TWA_ERR_NULL;
+  if (count <= 0 || count > (int64_t)TWA_MAX_LAYERS * TWA_MAX_N) return TWA_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(beta) & 3u) || (reinterpret_cast<uintptr_t>(s) & 3u)) return TWA_ERR_ALIGN;
+  if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_beta_update(beta, s, count, lr, lambda, static_cast<hipStream_t>(stream));
+}
+
+int twa_centre_normalise_workspace_bytes(int64_t D, int32_t n, int32_t L, size_t* bytes) {
+  if (!bytes) return TWA_ERR_NULL;
+  if (D <= 0 || n <= 0 || n > TWA_MAX_N || L <= 0 || L > TWA_MAX_LAYERS) return TWA_ERR_SHAPE;
+  *bytes = centre_workspace_bytes(D, n, L);
+  return TWA_OK;
+}
+
+int twa_centre_normalise(const float* W, int64_t D, int32_t n, int64_t ldw, const void* plan, int32_t L, float* wbar,
+                         float* E, int64_t lde, float* norms, void* ws, size_t ws_bytes, void* stream) {
+  if (!W || !wbar || !E) return TWA_ERR_NULL;
+  int rc = check_dims(D, n, ldw, TWA_F32);
+  if (rc != TWA_OK) return rc;
+  rc = check_dims(D, n, lde, TWA_F32);
+  if (rc != TWA_OK) return rc;
+  rc = check_plan(plan, L);
+  if (rc != TWA_OK) return rc;
+  if (!aligned16(W) || !aligned16(E) || !aligned16(wbar) || (norms && (reinterpret_cast<uintptr_t>(norms) & 3u)))
+    return TWA_ERR_ALIGN;
+  if (E != W) {                              // in place, or apart: no partial overlap
+    const char* a = reinterpret_cast<const char*>(W);
+    const char* b = reinterpret_cast<const char*>(E);
+    const size_t wa = (size_t)n * ldw * 4, eb = (size_t)n * lde * 4;
+    if (a < b + eb && b < a + wa) return TWA_ERR_SHAPE;
+  } else if (lde != ldw) {
+    return TWA_ERR_SHAPE;
+  }
+  if (!ws || ws_bytes < centre_workspace_bytes(D, n, L)) return TWA_ERR_WORKSPACE;
+  if (!aligned16(ws)) return TWA_ERR_ALIGN;
+  const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_centre_normalise(W, D, n, ldw, plan, L, wbar, E, lde, norms, ws, grid, static_cast<hipStream_t>(stream));
 }
 
 int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* out, void* stream) {

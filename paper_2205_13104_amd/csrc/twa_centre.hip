@@ -1,0 +1,161 @@
+// The paper's default basis (arXiv 2205.13104, Sec. 4.1, the extraction of base vectors, and
+// Sec. 4.5, its layer-wise form; Alg. 1, first steps):
+//   wbar = (1/n) sum_j w_j ,   e_j^l = (w_j^l - wbar^l) / || w_j^l - wbar^l ||_2 .
+// One-time work that is bound by a few passes over the n x D checkpoint matrix:
+//   1. mean_kernel        reads W, writes wbar (the sum is kept in fp64; besides the fp32 mean its
+//                         rounding error is kept too, so that step 2 subtracts the mean to almost
+//                         fp64 accuracy: layers that hardly move between checkpoints have
+//                         |w_j - wbar| << |wbar| and would otherwise lose most of their digits);
+//   2. centre_kernel      E = (W - wbar_hi) - wbar_lo, zero padding; may run in place;
+//   3. the per-layer squared norms of E (the layer-wise projection kernel in its squares mode);
+//   4. rinv_kernel        1/norm per (layer, vector), 0 for a zero vector; the norms if wanted;
+//   5. scale_kernel       E_ij *= 1/norm of (layer of i, j).
+#include "twa_device.h"
+#include "twa_host.h"
+
+namespace twa {
+
+constexpr int kEltThreads = 256;
+
+// 4 consecutive elements per thread; `grid` workgroups stride over the D elements.
+__global__ __launch_bounds__(kEltThreads) void mean_kernel(const float* __restrict__ W, int64_t D, int n, int64_t ldw,
+                                                           float* __restrict__ wbar, float* __restrict__ wbar_lo) {
+  const uint32_t bytes = (uint32_t)(D * 4);
+  const rsrc_t ro = make_rsrc(wbar, bytes), rl = make_rsrc(wbar_lo, bytes);
+  const int64_t nvec = (D + 3) / 4;
+  for (int64_t q = (int64_t)blockIdx.x * kEltThreads + threadIdx.x; q < nvec; q += (int64_t)gridDim.x * kEltThreads) {
+    double a[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int j = 0; j < n; ++j) {
+      const u32x4 x = ld128_stream(make_rsrc(W + (int64_t)j * ldw, bytes), (uint32_t)q * 16u);   // past D: zeros
+#pragma unroll
+      for (int r = 0; r < 4; ++r) a[r] += (double)as_f32(x[r]);
+    }
+    u32x4 hi, lo;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const double m = a[r] / (double)n;
+      const float h = (float)m;
+      hi[r] = as_u32(h);
+      lo[r] = as_u32((float)(m - (double)h));
+    }
+    // a 128-bit store is range-checked dword by dword: the ragged end is cut off
+    st128(ro, (uint32_t)q * 16u, hi);
+    st128(rl, (uint32_t)q * 16u, lo);
+  }
+}
+
+// E[j][i] = (W[j][i] - hi[i]) - lo[i] for i < D, 0 for D <= i < lde.
+__global__ __launch_bounds__(kEltThreads) void centre_kernel(const float* W, int64_t D, int n, int64_t ldw,
+                                                             const float* __restrict__ wbar,
+                                                             const float* __restrict__ wbar_lo, float* E,
+                                                             int64_t lde) {   // E may be W
+  const uint32_t bytes = (uint32_t)(D * 4);
+  const rsrc_t rh = make_rsrc(wbar, bytes), rl = make_rsrc(wbar_lo, bytes);
+  const int64_t nvec = lde / 4;
+  for (int64_t q = (int64_t)blockIdx.x * kEltThreads + threadIdx.x; q < nvec; q += (int64_t)gridDim.x * kEltThreads) {
+    const u32x4 h = ld128(rh, (uint32_t)q * 16u), l = ld128(rl, (uint32_t)q * 16u);
+    for (int j = 0; j < n; ++j) {
+      const u32x4 x = ld128_stream(make_rsrc(W + (int64_t)j * ldw, bytes), (uint32_t)q * 16u);
+      u32x4 y;
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        y[r] = 4 * q + r < D ? as_u32((as_f32(x[r]) - as_f32(h[r])) - as_f32(l[r])) : 0u;
+      *reinterpret_cast<u32x4*>(E + (int64_t)j * lde + 4 * q) = y;
+    }
+  }
+}
+
+// rinv[l][j] = 1/sqrt(Q[l][j]) (0 where Q is 0); norms[l][j] = sqrt(Q[l][j]) if wanted.
+__global__ __launch_bounds__(kEltThreads) void rinv_kernel(const float* __restrict__ Q, int64_t count,
+                                                           float* __restrict__ rinv, float* __restrict__ norms) {
+  const int64_t q = (int64_t)blockIdx.x * kEltThreads + threadIdx.x;
+  if (q >= count) return;
+  const double v = (double)Q[q];
+  const double r = sqrt(v);
+  rinv[q] = v > 0.0 ? (float)(1.0 / r) : 0.0f;
+  if (norms) norms[q] = (float)r;
+}
+
+// E[j][i] *= rinv[layer of i][j].  4 consecutive elements per thread; the layer of the first one by
+// bisection, the others follow.
+__global__ __launch_bounds__(kEltThreads) void scale_kernel(float* __restrict__ E, int64_t D, int n, int64_t lde,
+                                                            const int64_t* __restrict__ off, int L,
+                                                            const float* __restrict__ rinv) {
+  const int64_t nvec = (D + 3) / 4;
+  for (int64_t q = (int64_t)blockIdx.x * kEltThreads + threadIdx.x; q < nvec; q += (int64_t)gridDim.x * kEltThreads) {
+    const int64_t i0 = 4 * q;
+    int a = 0, b = L - 1;                       // largest l with off[l] <= i0
+    while (a < b) {
+      const int mid = (a + b + 1) >> 1;
+      if (off[mid] <= i0) a = mid; else b = mid - 1;
+    }
+    int lay[4];
+    int l = a;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      while (l < L - 1 && off[l + 1] <= i0 + r) ++l;
+      lay[r] = l;
+    }
+    for (int j = 0; j < n; ++j) {
+      float4* p = reinterpret_cast<float4*>(E + (int64_t)j * lde + i0);      // lde % 4 == 0: inside the row
+      float4 x = *p;
+      x.x *= rinv[(int64_t)lay[0] * n + j];
+      x.y *= rinv[(int64_t)lay[1] * n + j];
+      x.z *= rinv[(int64_t)lay[2] * n + j];
+      x.w *= rinv[(int64_t)lay[3] * n + j];
+      *p = x;                                                                // padding: 0 * finite = 0
+    }
+  }
+}
+
+// beta <- (1 - lr*lambda) beta - lr * s   (Alg. 1, "update variables")
+__global__ __launch_bounds__(kEltThreads) void beta_update_kernel(float* __restrict__ beta, const float* __restrict__ s,
+                                                                  int64_t count, float lr, float lambda) {
+  const int64_t q = (int64_t)blockIdx.x * kEltThreads + threadIdx.x;
+  if (q >= count) return;
+  const float keep = 1.0f - lr * lambda;
+  beta[q] = __builtin_fmaf(-lr, s[q], keep * beta[q]);
+}
+
+static int elt_grid(int64_t nvec) {
+  const int64_t want = (nvec + kEltThreads - 1) / kEltThreads;
+  const int cap = device_cus() * 8;
+  return (int)(want < cap ? (want > 0 ? want : 1) : cap);
+}
+
+// Workspace layout: wbar_lo [D rounded up to 4 floats] | Q [L*n] | rinv [L*n] | partial sums of the squares kernel.
+size_t centre_workspace_bytes(int64_t D, int n, int L) {
+  const size_t lo = (size_t)((D + 3) / 4 * 4) * sizeof(float);
+  return lo + 2 * (size_t)L * n * sizeof(float) + ((size_t)kMaxGrid + (size_t)L) * n * sizeof(float);
+}
+
+int launch_centre_normalise(const float* W, int64_t D, int n, int64_t ldw, const void* plan_dev, int L, float* wbar,
+                            float* E, int64_t lde, float* norms, void* ws, int max_grid, hipStream_t st) {
+  float* wbar_lo = static_cast<float*>(ws);
+  float* Q = wbar_lo + (D + 3) / 4 * 4;
+  float* rinv = Q + (size_t)L * n;
+  float* partial = rinv + (size_t)L * n;
+  hipLaunchKernelGGL(mean_kernel, dim3(elt_grid((D + 3) / 4)), dim3(kEltThreads), 0, st, W, D, n, ldw, wbar, wbar_lo);
+  hipLaunchKernelGGL(centre_kernel, dim3(elt_grid(lde / 4)), dim3(kEltThreads), 0, st, W, D, n, ldw, wbar, wbar_lo, E,
+                     lde);
+  int rc = hip_check(hipGetLastError());
+  if (rc != TWA_OK) return rc;
+  PView v{reinterpret_cast<const uint8_t*>(E), nullptr, D, lde, n, 0, 1.0f};
+  rc = launch_layer_squares(v, plan_dev, L, Q, partial, max_grid, st);
+  if (rc != TWA_OK) return rc;
+  const int64_t count = (int64_t)L * n;
+  hipLaunchKernelGGL(rinv_kernel, dim3((unsigned)((count + kEltThreads - 1) / kEltThreads)), dim3(kEltThreads), 0, st, Q,
+                     count, rinv, norms);
+  const LayerPlan plan = plan_view(plan_dev, L, 2048);
+  hipLaunchKernelGGL(scale_kernel, dim3(elt_grid((D + 3) / 4)), dim3(kEltThreads), 0, st, E, D, n, lde, plan.off, L,
+                     rinv);
+  return hip_check(hipGetLastError());
+}
+
+int launch_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, hipStream_t st) {
+  hipLaunchKernelGGL(beta_update_kernel, dim3((unsigned)((count + kEltThreads - 1) / kEltThreads)), dim3(kEltThreads), 0,
+                     st, beta, s, count, lr, lambda);
+  return hip_check(hipGetLastError());
+}
+
+}  // namespace twa

@@ -44,6 +44,7 @@ struct Expander {
   int gshift;
   uint32_t span_scale_bytes;
   rsrc_t rw, rgt;
+  rsrc_t rw_in;                                         // where the old weights are read (normally = rw)
   float lr;
   float* tb;                                            // this wave's LDS transpose buffer
 
@@ -127,7 +128,7 @@ struct Expander {
 #pragma unroll
     for (int v = 0; v < VPL; ++v)
 #pragma unroll
-      for (int q = 0; q < EPV / 4; ++q) wv[v][q] = ld128(rw, piece(e0, v, q) * 4u);
+      for (int q = 0; q < EPV / 4; ++q) wv[v][q] = ld128(rw_in, piece(e0, v, q) * 4u);
   }
 
   // lane's EPV sums of one wave-vector -> its padded row of an LDS buffer of kWave*ROW floats
@@ -197,7 +198,7 @@ struct Expander {
 // of its layer, and only the elements of its layer are written.
 template <int DT, int U, int VPL, int HOLD, int LH, bool LAYERED>
 __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const float* __restrict__ s,
-                                                               float* __restrict__ w, float lr,
+                                                               const float* w_in, float* w, float lr,
                                                                float* __restrict__ g_tilde, int rounds,
                                                                LayerPlan plan) {
   using X = Expander<DT, U, VPL, LAYERED>;
@@ -224,6 +225,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
             X::S::kScaled ? ((uint32_t)P.n << (kScaleSpanShift - P.block_shift)) * (uint32_t)X::S::kScaleBytes : 0u,
             make_rsrc(w, w_bytes),
             make_rsrc(g_tilde, g_tilde ? w_bytes : 0u),
+            make_rsrc(w_in, w_bytes),
             lr,
             tbuf[wave]};
 
@@ -310,8 +312,8 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
 }
 
 template <int DT, int U, int VPL, int HOLD, int LH, bool LAYERED>
-static void launch_expand_cfg(const PView& P, const float* s, float* w, float lr, float* g_tilde, int max_grid,
-                              hipStream_t st, const void* plan_dev, int L) {
+static void launch_expand_cfg(const PView& P, const float* s, const float* w_in, float* w, float lr, float* g_tilde,
+                              int max_grid, hipStream_t st, const void* plan_dev, int L) {
   constexpr int tile = kWave * VPL * Store<DT>::kEPV;
   LayerPlan plan{nullptr, nullptr, 1};
   const int64_t ntiles = (P.D + tile - 1) / tile;
@@ -321,19 +323,19 @@ static void launch_expand_cfg(const PView& P, const float* s, float* w, float lr
     plan = plan_view(plan_dev, L, tile);
     grid = max_grid;                  // the kernel divides the plan's tiles over the grid itself
   }
-  hipLaunchKernelGGL((expand_update_kernel<DT, U, VPL, HOLD, LH, LAYERED>), dim3(grid), dim3(256), 0, st, P, s, w, lr,
-                     g_tilde, (int)rounds, plan);
+  hipLaunchKernelGGL((expand_update_kernel<DT, U, VPL, HOLD, LH, LAYERED>), dim3(grid), dim3(256), 0, st, P, s, w_in, w,
+                     lr, g_tilde, (int)rounds, plan);
 }
 
 // <U, VPL, HOLD, LH> per storage type: chosen by interleaved timing on MI355X at D = 25.6 M, n = 100
 template <bool LAYERED>
-static int launch_expand_any(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde,
-                             int max_grid, hipStream_t st, const void* plan_dev, int L) {
+static int launch_expand_any(const PView& P, int dtype, const float* s, const float* w_in, float* w, float lr,
+                             float* g_tilde, int max_grid, hipStream_t st, const void* plan_dev, int L) {
   switch (dtype) {
-    case TWA_F32: launch_expand_cfg<TWA_F32, 1, 8, 6, 1, LAYERED>(P, s, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
-    case TWA_BF16: launch_expand_cfg<TWA_BF16, 2, 4, 6, 1, LAYERED>(P, s, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
-    case TWA_I8: launch_expand_cfg<TWA_I8, 4, 2, 6, 1, LAYERED>(P, s, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
-    case TWA_I4: launch_expand_cfg<TWA_I4, 8, 1, 5, 0, LAYERED>(P, s, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_F32: launch_expand_cfg<TWA_F32, 1, 8, 6, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_BF16: launch_expand_cfg<TWA_BF16, 2, 4, 6, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_I8: launch_expand_cfg<TWA_I8, 4, 2, 6, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_I4: launch_expand_cfg<TWA_I4, 8, 1, 5, 0, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
     default: return TWA_ERR_DTYPE;
   }
   return hip_check(hipGetLastError());
@@ -341,13 +343,15 @@ static int launch_expand_any(const PView& P, int dtype, const float* s, float* w
 
 int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int max_grid,
                          hipStream_t st) {
-  return launch_expand_any<false>(P, dtype, s, w, lr, g_tilde, max_grid, st, nullptr, 1);
+  return launch_expand_any<false>(P, dtype, s, w, w, lr, g_tilde, max_grid, st, nullptr, 1);
 }
 
 // Layer-wise: s is L x n, row l holds the coefficients of layer l; `plan_dev` is the device plan.
-int launch_expand_update_layers(const PView& P, int dtype, const float* s, const void* plan_dev, int L, float* w,
-                                float lr, float* g_tilde, int max_grid, hipStream_t st) {
-  return launch_expand_any<true>(P, dtype, s, w, lr, g_tilde, max_grid, st, plan_dev, L);
+// w_out = w_in - lr * g~ (w_in may be w_out: the in-place update).
+int launch_expand_update_layers(const PView& P, int dtype, const float* s, const void* plan_dev, int L,
+                                const float* w_in, float* w_out, float lr, float* g_tilde, int max_grid,
+                                hipStream_t st) {
+  return launch_expand_any<true>(P, dtype, s, w_in, w_out, lr, g_tilde, max_grid, st, plan_dev, L);
 }
 
 }  // namespace twa

@@ -37,8 +37,15 @@ LayerPlan plan_view(const void* plan_dev, int L, int tile);
 int launch_layer_plan(const int64_t* layer_off, int L, int64_t D, void* plan_dev, hipStream_t st);
 int launch_project_layers(const PView& P, int dtype, const float* g, const void* plan_dev, int L, float* S,
                           float* partial, int max_grid, hipStream_t st);
-int launch_expand_update_layers(const PView& P, int dtype, const float* s, const void* plan_dev, int L, float* w,
-                                float lr, float* g_tilde, int max_grid, hipStream_t st);
+int launch_expand_update_layers(const PView& P, int dtype, const float* s, const void* plan_dev, int L,
+                                const float* w_in, float* w_out, float lr, float* g_tilde, int max_grid,
+                                hipStream_t st);
+int launch_layer_squares(const PView& P, const void* plan_dev, int L, float* Q, float* partial, int max_grid,
+                         hipStream_t st);
+size_t centre_workspace_bytes(int64_t D, int n, int L);
+int launch_centre_normalise(const float* W, int64_t D, int n, int64_t ldw, const void* plan_dev, int L, float* wbar,
+                            float* E, int64_t lde, float* norms, void* ws, int max_grid, hipStream_t st);
+int launch_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, hipStream_t st);
 int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pmat& out, hipStream_t st);
 int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st);
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram, hipStream_t st);

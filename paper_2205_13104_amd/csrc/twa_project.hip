@@ -30,7 +30,9 @@ namespace twa {
 // walks into the next layer it reduces its running sums and writes them to partial slot
 // (workgroup + layer): along the walk both indices only grow, so the slot is unique, and the
 // reduction kernel knows from the plan which workgroups contributed to a layer.
-template <int DT, int KB, int U, int NCH, int VPL, bool LAYERED>
+// SQUARES (with LAYERED, F32): no gradient; the sums are the squares of the stored elements of the
+// layer, sum_i P_ij^2 -- the squared norms that the layer-wise basis divides by (Sec. 4.5).
+template <int DT, int KB, int U, int NCH, int VPL, bool LAYERED, bool SQUARES = false>
 __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __restrict__ g, int64_t ldg,
                                                       int kvalid, float* __restrict__ partial, int cpw,
                                                       int tiles_per_wg, LayerPlan plan) {
@@ -92,6 +94,7 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
     int64_t e0 = t * TILE;
     uint32_t g_bytes = (uint32_t)(D * 4);
     uint32_t head = 0;                  // elements of this tile in front of its layer's first element
+    uint32_t tail = TILE;               // elements of this tile up to its layer's end
     if constexpr (LAYERED) {
       if (lc.behind(plan, t)) {                                  // this tile starts the next (non-empty) layer
         flush((int)blockIdx.x + lc.cur);                         // a workgroup never holds a layer without tiles
@@ -101,6 +104,7 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
       e0 = lc.tile_start(t, TILE);
       g_bytes = (uint32_t)(hi * 4);                              // the gradient ends with the layer
       head = lc.lo > e0 ? (uint32_t)(lc.lo - e0 < TILE ? lc.lo - e0 : TILE) : 0u;
+      tail = hi - e0 < TILE ? (uint32_t)(hi > e0 ? hi - e0 : 0) : (uint32_t)TILE;
     }
 
     // ---- this lane's slice of the gradient(s); the descriptor ends at element D (at the end of
@@ -113,13 +117,19 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
 #pragma unroll
       for (int v = 0; v < VPL; ++v) {
         const uint32_t elem = (uint32_t)e0 + (uint32_t)(v * kWave + lane) * EPV;
+        if constexpr (SQUARES) {
+          const uint32_t rel = (uint32_t)(v * kWave + lane) * EPV;
 #pragma unroll
-        for (int q = 0; q < EPV / 4; ++q) {
-          const u32x4 x = ld128(rg, (elem + 4u * q) * 4u);   // shared by the 4 waves: keep it cacheable
+          for (int e = 0; e < EPV; ++e) gs[c][v][e] = (rel + e >= head && rel + e < tail) ? 1.0f : 0.0f;
+        } else {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) gs[c][v][4 * q + r] = as_f32(x[r]);
+          for (int q = 0; q < EPV / 4; ++q) {
+            const u32x4 x = ld128(rg, (elem + 4u * q) * 4u);   // shared by the 4 waves: keep it cacheable
+#pragma unroll
+            for (int r = 0; r < 4; ++r) gs[c][v][4 * q + r] = as_f32(x[r]);
+          }
         }
-        if constexpr (LAYERED) {
+        if constexpr (LAYERED && !SQUARES) {
           if (head != 0) {                                   // first tile of a layer with an unaligned start
             const uint32_t rel = (uint32_t)(v * kWave + lane) * EPV;
 #pragma unroll
@@ -196,7 +206,7 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
             } else {
               float d = acc[slot][c];
 #pragma unroll
-              for (int e = 0; e < EPV; ++e) d = __builtin_fmaf(x[e], gs[c][v][e], d);
+              for (int e = 0; e < EPV; ++e) d = __builtin_fmaf(SQUARES ? x[e] * gs[c][v][e] : x[e], SQUARES ? x[e] : gs[c][v][e], d);
               acc[slot][c] = d;
             }
           }
@@ -398,7 +408,7 @@ static void divide_tiles(int64_t D, int tile, int max_grid, int* grid, int* tile
   *grid = (int)((ntiles + per - 1) / per);
 }
 
-template <int DT, int KB, int VPL, bool LAYERED = false>
+template <int DT, int KB, int VPL, bool LAYERED = false, bool SQUARES = false>
 static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kvalid, float* partial, int max_grid,
                              int* grid_out, hipStream_t st, LayerPlan plan = LayerPlan{nullptr, nullptr, 1}) {
   const int cpw = (P.n + 3) / 4;
@@ -409,7 +419,7 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   *grid_out = grid;
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
 #define TWA_LAUNCH(U_, NCH_)                                                                         \
-  hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL, LAYERED>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
+  hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL, LAYERED, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
                      kvalid, partial, cpw, tiles_per_wg, plan)
   {
     if (cpw == 25) {
@@ -475,6 +485,18 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   int rc = launch_project_dt<DT, 1, VPL, true>(P, g, 0, 1, partial, max_grid, &grid, st, plan);
   if (rc != TWA_OK) return rc;
   hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, S);
+  return hip_check(hipGetLastError());
+}
+
+// Per-layer squared norms of the vectors of an fp32 matrix: Q[l][j] = sum over layer l of P_ij^2.
+int launch_layer_squares(const PView& P, const void* plan_dev, int L, float* Q, float* partial, int max_grid,
+                         hipStream_t st) {
+  constexpr int tile = kWave * 4 * Store<TWA_F32>::kEPV;
+  const LayerPlan plan = plan_view(plan_dev, L, tile);
+  int grid = 0;
+  int rc = launch_project_dt<TWA_F32, 1, 4, true, true>(P, nullptr, 0, 1, partial, max_grid, &grid, st, plan);
+  if (rc != TWA_OK) return rc;
+  hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, Q);
   return hip_check(hipGetLastError());
 }
 
