@@ -56,7 +56,7 @@
 #define ORC_ERR_RANK (-6)
 #define ORC_ERR_NOMEM (-8)
 
-enum { ORC_F64 = -1, ORC_F32 = 0, ORC_BF16 = 1, ORC_I8 = 2, ORC_I4 = 3 };
+enum { ORC_F64 = -1, ORC_F32 = 0, ORC_BF16 = 1, ORC_I8 = 2, ORC_I4 = 3, ORC_MM = 4 };
 
 int twa_oracle_threads(void) {
 #ifdef _OPENMP
@@ -148,6 +148,10 @@ typedef struct {
   const void* scales;   /* [n][ld/block]: float (I8) or binary16 bits (I4) */
   int32_t block;
   float gscale;         /* power-of-two multiplier of the binary16 scales (I4) */
+  /* ORC_MM only (Sec. 4.6, the paper's own format): data = one uint16 code per element,
+     scales = L pairs of floats (a_l, b_l), value = a_l * code + b_l for the elements of layer l */
+  const int64_t* layer_off;
+  int32_t L;
 } orc_pmat;
 
 /* The value of stored element (i, j), exactly, as a double. */
@@ -161,6 +165,15 @@ static double deq(const orc_pmat* P, int64_t i, int32_t j) {
       int64_t nblk = P->ld / P->block;
       double sc = (double)((const float*)P->scales)[(int64_t)j * nblk + i / P->block];
       return sc * (double)((const int8_t*)P->data)[(int64_t)j * P->ld + i];
+    }
+    case ORC_MM: {
+      int32_t l = 0, hi = P->L - 1;                              /* bisection: the last layer that starts at or before i */
+      while (l < hi) {
+        int32_t mid = (l + hi + 1) / 2;
+        if (P->layer_off[mid] <= i) l = mid; else hi = mid - 1;
+      }
+      const float* ab = (const float*)P->scales + 2 * (int64_t)l;
+      return (double)ab[0] * (double)((const uint16_t*)P->data)[(int64_t)j * P->ld + i] + (double)ab[1];
     }
     case ORC_I4: {
       int64_t nblk = P->ld / P->block;
@@ -534,7 +547,8 @@ int twa_oracle_quantize_minmax(const double* P, int64_t D, int32_t n, int64_t ld
   const double levels = (double)((1u << B) - 1u);
   for (int32_t l = 0; l < L; ++l) {
     int64_t lo = layer_off[l], hi = layer_off[l + 1];
-    if (hi <= lo) return ORC_ERR_ARG;
+    if (hi < lo) return ORC_ERR_ARG;
+    if (hi == lo) { a_out[l] = 0.0; b_out[l] = 0.0; continue; }      /* an empty layer has nothing to store */
     double mn = INFINITY, mx = -INFINITY;
     for (int32_t j = 0; j < n; ++j)
       for (int64_t i = lo; i < hi; ++i) {

@@ -22,7 +22,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "twa_oracle.c")
 _LIB = os.path.join(_HERE, "libtwa_oracle.so")
 
-F64, F32, BF16, I8, I4 = -1, 0, 1, 2, 3
+F64, F32, BF16, I8, I4, MM = -1, 0, 1, 2, 3, 4
 ERR_ARG, ERR_RANK, ERR_NOMEM = -1, -6, -8
 
 
@@ -38,7 +38,7 @@ def build(force: bool = False) -> str:
 class _PmatStruct(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("n", C.c_int32), ("D", C.c_int64), ("ld", C.c_int64),
                 ("data", C.c_void_p), ("scales", C.c_void_p), ("block", C.c_int32),
-                ("gscale", C.c_float)]
+                ("gscale", C.c_float), ("layer_off", C.c_void_p), ("L", C.c_int32)]
 
 
 _lib = None
@@ -112,7 +112,7 @@ class OracleError(RuntimeError):
         self.code = code
 
 
-_NP = {F64: np.float64, F32: np.float32, BF16: np.uint16, I8: np.int8, I4: np.uint8}
+_NP = {F64: np.float64, F32: np.float32, BF16: np.uint16, I8: np.int8, I4: np.uint8, MM: np.uint16}
 
 
 @dataclass
@@ -124,10 +124,16 @@ class Pmat:
     scales: Optional[np.ndarray] = None   # (n, ld//block): float32 (I8) / uint16 binary16 bits (I4)
     block: int = 0
     gscale: float = 1.0
+    layer_off: Optional[np.ndarray] = None   # MM (the paper's min-max format): L+1 int64 offsets; scales = (L, 2) float32 (a, b)
 
     def __post_init__(self):
         assert self.data.ndim == 2 and self.data.flags.c_contiguous
         assert self.data.dtype == _NP[self.dtype], (self.data.dtype, self.dtype)
+        if self.dtype == MM:
+            assert self.layer_off is not None and self.layer_off.dtype == np.int64 and self.layer_off.flags.c_contiguous
+            assert self.scales is not None and self.scales.dtype == np.float32 and self.scales.flags.c_contiguous
+            assert self.scales.shape == (self.layer_off.size - 1, 2)
+            assert self.layer_off[0] == 0 and self.layer_off[-1] == self.D
         if self.dtype in (I8, I4):
             assert self.scales is not None and self.scales.flags.c_contiguous and self.block > 0
             assert self.scales.dtype == (np.float32 if self.dtype == I8 else np.uint16)
@@ -145,7 +151,9 @@ class Pmat:
     def _struct(self) -> _PmatStruct:
         return _PmatStruct(self.dtype, self.n, self.D, self.ld, self.data.ctypes.data,
                            0 if self.scales is None else self.scales.ctypes.data,
-                           self.block, float(self.gscale))
+                           self.block, float(self.gscale),
+                           0 if self.layer_off is None else self.layer_off.ctypes.data,
+                           0 if self.layer_off is None else self.layer_off.size - 1)
 
     def dense(self) -> np.ndarray:
         """(n, D) float64 array of the exact stored values."""
@@ -340,6 +348,15 @@ def quantize_minmax(P: np.ndarray, B: int, layer_off):
     _check(lib().twa_oracle_quantize_minmax(_ptr(P), D, n, D, B, _ptr(off), L, _ptr(codes), D, _ptr(a), _ptr(b)),
            "quantize_minmax")
     return codes, a, b
+
+
+def pmat_minmax(codes: np.ndarray, a, b, layer_off, D: Optional[int] = None) -> Pmat:
+    """The stored matrix of the paper's min-max format (Sec. 4.6): value = a_l * code + b_l, with the two
+    factors of every layer kept as binary32 (8L bytes in the memory table of that section)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint16)
+    ab = np.ascontiguousarray(np.stack([np.asarray(a), np.asarray(b)], axis=1).astype(np.float32))
+    off = np.ascontiguousarray(layer_off, dtype=np.int64)
+    return Pmat(MM, codes.shape[1] if D is None else D, codes, ab, 0, 1.0, off)
 
 
 def f32_to_f16_bits(x: float) -> int:

@@ -473,6 +473,33 @@ def test_minmax_quantiser_properties(B):
         assert c[np.unravel_index(np.argmax(seg), seg.shape)] == 2 ** B - 1
 
 
+def test_minmax_stored_matrix_and_fused_dequantisation():
+    # value = a*code + b; hence (P~^l)^T g^l = a (Q^l)^T g^l + b sum(g^l) and P~^l beta = a Q^l beta + b sum(beta)
+    r = rng(41)
+    n, D, B = 5, 700, 4
+    off = np.array([0, 100, 100, 333, 700], dtype=np.int64)
+    P = r.normal(size=(n, D)) * 0.01
+    codes, a, b = orc.quantize_minmax(P, B, off)
+    assert a[1] == 0.0 and b[1] == 0.0                               # the empty layer
+    pm = orc.pmat_minmax(codes, a, b, off)
+    a32, b32 = a.astype(np.float32).astype(np.float64), b.astype(np.float32).astype(np.float64)
+    dense = pm.dense()
+    g = r.normal(size=D)
+    S = orc.project_layers(pm, g, off)
+    beta = r.normal(size=(4, n))
+    w = orc.weights_from_beta(pm, beta, off, np.zeros(D))
+    for l in range(4):
+        sl = slice(off[l], off[l + 1])
+        Q = codes[:, sl].astype(np.float64)
+        assert np.array_equal(dense[:, sl], a32[l] * Q + b32[l])
+        assert np.allclose(S[l], a32[l] * (Q @ g[sl]) + b32[l] * g[sl].sum(), rtol=0, atol=1e-12)
+        assert np.allclose(w[sl], a32[l] * (beta[l] @ Q) + b32[l] * beta[l].sum(), rtol=0, atol=1e-12)
+    # the stored matrix is within half a step of the original, layer by layer (a in binary32: one more ulp)
+    for l in (0, 2, 3):
+        sl = slice(off[l], off[l + 1])
+        assert np.max(np.abs(dense[:, sl] - P[:, sl])) <= 0.5 * a[l] * (1 + 1e-5)
+
+
 # --------------------------------------------------------------------------- default construction (Sec. 4.1)
 def test_centre_normalise_matches_definition():
     W = traj(3000, 9, seed=19)
