@@ -58,9 +58,16 @@ typedef enum twa_dtype {
   TWA_F32 = 0,  /* IEEE binary32 values                                                        */
   TWA_BF16 = 1, /* bfloat16 values (binary32 rounded to nearest even to 16 bits)               */
   TWA_I8 = 2,   /* int8 codes q in [-127,127] + one binary32 scale per block: value = scale*q  */
-  TWA_I4 = 3    /* 4-bit codes q in [-7,7], two per byte (element i in the LOW nibble when i is
+  TWA_I4 = 3,   /* 4-bit codes q in [-7,7], two per byte (element i in the LOW nibble when i is
                    even), stored offset-binary as q+8; one binary16 scale h per block:
                    value = (float(h) * gscale) * q                                             */
+  /* The paper's own format (Sec. 4.6): unsigned B-bit codes c in [0, 2^B - 1] and ONE pair of
+     binary32 factors (a_l, b_l) per layer, shared by all n vectors: value = a_l * c + b_l.
+     `scales` of the descriptor points to the 2L floats a_0, b_0, a_1, b_1, ...; `block` and
+     `gscale` are ignored.  Only the layer-wise calls accept these (with the plan of the same
+     layer table the matrix was quantised with).                                               */
+  TWA_U8MM = 4, /* B = 8: the byte holds c - 128 as a two's-complement int8                      */
+  TWA_U4MM = 5  /* B = 4: two codes per byte, element i in the LOW nibble when i is even         */
 } twa_dtype;
 
 /*
@@ -227,6 +234,21 @@ int twa_project_layers(const twa_pmat* P, const float* g, const void* plan, int3
  */
 int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan, int32_t L, float* w, float lr,
                              float* g_tilde, void* stream);
+
+/*
+ * Quantise an fp32 matrix into the paper's own format (Sec. 4.6): per layer l, over ALL n vectors,
+ *     a_l = (max - min) / (2^B - 1),  b_l = min,  c = round((p - b_l) / a_l)  in [0, 2^B - 1],
+ * evaluated in fp64 with ties to even (the paper names no tie rule); a_l = 0 (a constant layer)
+ * gives c = 0; the factors are stored rounded to binary32 (b_l exactly).  The stored value is
+ * within a_l/2 of p.
+ *   out  [in/out] dtype TWA_U8MM or TWA_U4MM; data and scales (2L floats) allocated by the caller
+ *                 (twa_pmat_bytes gives ld and the data size; it reports 0 scale bytes for these
+ *                 types since it does not know L).
+ *   ws, ws_bytes  device workspace of at least twa_quantize_minmax_workspace_bytes(L).
+ */
+int twa_quantize_minmax_workspace_bytes(int32_t L, size_t* bytes);
+int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const void* plan, int32_t L,
+                        twa_pmat* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * The paper's default basis and the coefficient form of the step (Sec. 4.1, extraction of base

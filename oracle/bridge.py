@@ -10,9 +10,27 @@ import torch
 from . import twa_oracle as orc
 
 
-def to_oracle(pm, cols=None) -> orc.Pmat:
-    """The oracle's view of the stored matrix `pm` (optionally only the basis vectors in `cols`)."""
+U8MM, U4MM = 4, 5      # dtype codes of the paper's min-max format in the C descriptor
+
+
+def to_oracle(pm, cols=None, layer_off=None) -> orc.Pmat:
+    """The oracle's view of the stored matrix `pm` (optionally only the basis vectors in `cols`).
+
+    The min-max formats need the layer table (`layer_off`, L+1 offsets) the matrix was quantised with;
+    their packed codes are spread out to one unsigned 16-bit code per element, as the oracle keeps them."""
     data = pm.data if cols is None else pm.data[cols]
+    if pm.dtype in (U8MM, U4MM):
+        raw = data.cpu().numpy()
+        if pm.dtype == U8MM:
+            codes = (raw.astype(np.int16) + 128).astype(np.uint16)            # the byte holds code - 128
+        else:
+            b = raw.astype(np.uint16)
+            codes = np.empty((b.shape[0], 2 * b.shape[1]), dtype=np.uint16)
+            codes[:, 0::2] = b & 0xF                                            # even element in the low nibble
+            codes[:, 1::2] = b >> 4
+        ab = np.ascontiguousarray(pm.scales.cpu().numpy(), dtype=np.float32)
+        off = np.ascontiguousarray(np.asarray(layer_off), dtype=np.int64)
+        return orc.Pmat(orc.MM, pm.D, np.ascontiguousarray(codes), ab, 0, 1.0, off)
     scales = None
     if pm.scales is not None:
         # the device keeps the scales as [span][vector][scale in span]; the oracle wants one row of

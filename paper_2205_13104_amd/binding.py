@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtwa.so")
 
-F32, BF16, I8, I4 = 0, 1, 2, 3
+F32, BF16, I8, I4, U8MM, U4MM = 0, 1, 2, 3, 4, 5
 MAX_N, MAX_K, LD_MULTIPLE, SCALE_SPAN, MAX_LAYERS = 128, 8, 128, 2048, 65536
 DEFAULT_BLOCK = {I8: 128, I4: 64}
 
@@ -66,6 +66,10 @@ def lib():
         L.twa_expand_update_layers.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, f32, vp, vp]
         L.twa_layer_plan_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
         L.twa_layer_plan.argtypes = [vp, i32, i64, vp, C.c_size_t, vp]
+        L.twa_quantize_minmax_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
+        L.twa_quantize_minmax.argtypes = [vp, i64, i32, i64, vp, i32, C.POINTER(_Pmat), vp, C.c_size_t, vp]
+        L.twa_quantize_minmax_workspace_bytes.restype = C.c_int
+        L.twa_quantize_minmax.restype = C.c_int
         L.twa_centre_normalise_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(C.c_size_t)]
         L.twa_centre_normalise.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp, i64, vp, vp, C.c_size_t, vp]
         L.twa_beta_update.argtypes = [vp, vp, i64, f32, f32, vp]
@@ -118,7 +122,8 @@ def build_basis_workspace_bytes(n: int) -> int:
     return int(b.value)
 
 
-_TORCH_OF = {F32: torch.float32, BF16: torch.bfloat16, I8: torch.int8, I4: torch.uint8}
+_TORCH_OF = {F32: torch.float32, BF16: torch.bfloat16, I8: torch.int8, I4: torch.uint8, U8MM: torch.int8,
+             U4MM: torch.uint8}
 
 
 @dataclass
@@ -146,8 +151,10 @@ class Pmat:
     @property
     def stream_bytes(self) -> int:
         """Bytes of P one pass over the matrix has to move (codes/values of the D logical elements + scales)."""
-        bits = {F32: 32, BF16: 16, I8: 8, I4: 4}[self.dtype]
+        bits = {F32: 32, BF16: 16, I8: 8, I4: 4, U8MM: 8, U4MM: 4}[self.dtype]
         b = self.n * self.D * bits // 8
+        if self.dtype in (U8MM, U4MM):
+            return b + self.scales.numel() * 4
         if self.scales is not None:
             b += self.n * ((self.D + self.block - 1) // self.block) * self.scales.element_size()
         return b
@@ -285,6 +292,25 @@ def expand_update_layers(P: Pmat, S: torch.Tensor, plan: LayerPlan, w: torch.Ten
     st = P.c_struct()
     _check(lib().twa_expand_update_layers(C.byref(st), _ptr(S), plan.ptr, L, _ptr(w), float(lr),
                                           _ptr(g_tilde), _stream()), "twa_expand_update_layers")
+
+
+def quantize_minmax(P: torch.Tensor, D: int, plan: LayerPlan, bits: int = 4) -> Pmat:
+    """twa_quantize_minmax: the paper's per-layer min-max format (Sec. 4.6), B = 4 or 8 bits."""
+    assert P.dtype == torch.float32 and P.dim() == 2 and P.is_contiguous() and plan.D == D
+    dtype = {4: U4MM, 8: U8MM}[bits]
+    n, ldp = P.shape
+    ld, _, _ = pmat_bytes(dtype, D, n)
+    cols = ld // 2 if dtype == U4MM else ld
+    data = torch.empty((n, cols), dtype=_TORCH_OF[dtype], device=P.device)
+    ab = torch.empty((plan.L, 2), dtype=torch.float32, device=P.device)
+    out = Pmat(dtype, D, n, ld, data, ab, 0, 1.0)
+    nb = C.c_size_t()
+    _check(lib().twa_quantize_minmax_workspace_bytes(plan.L, C.byref(nb)), "twa_quantize_minmax_workspace_bytes")
+    ws = Workspace(int(nb.value) + 8, device=P.device)
+    st = out.c_struct()
+    _check(lib().twa_quantize_minmax(_ptr(P), D, n, ldp, plan.ptr, plan.L, C.byref(st), ws.ptr, ws.nbytes, _stream()),
+           "twa_quantize_minmax")
+    return out
 
 
 def centre_normalise(W: torch.Tensor, D: int, plan: LayerPlan, out: Optional[torch.Tensor] = None,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtwa.so")
-SOURCES = ["twa_api.hip", "twa_project.hip", "twa_expand.hip", "twa_quantize.hip", "twa_basis.hip", "twa_layers.hip", "twa_centre.hip"]
+SOURCES = ["twa_api.hip", "twa_project.hip", "twa_expand.hip", "twa_quantize.hip", "twa_basis.hip", "twa_layers.hip", "twa_centre.hip", "twa_minmax.hip"]
 HEADERS = ["twa_device.h", "twa_host.h", os.path.join("..", "..", "include", "twa.h")]
 # -packed-fp32-ops: keep the compiler from forming packed fp32 instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -45,17 +45,20 @@ int env_int(const char* name, int fallback) {
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 static bool scaled(int dtype) { return dtype == TWA_I8 || dtype == TWA_I4; }
+static bool minmax(int dtype) { return dtype == TWA_U8MM || dtype == TWA_U4MM; }
 static int bits_of(int dtype) {
   switch (dtype) {
     case TWA_F32: return 32;
     case TWA_BF16: return 16;
     case TWA_I8: return 8;
     case TWA_I4: return 4;
+    case TWA_U8MM: return 8;
+    case TWA_U4MM: return 4;
     default: return 0;
   }
 }
 
-static int64_t ld_multiple(int dtype) { return scaled(dtype) ? TWA_SCALE_SPAN : TWA_LD_MULTIPLE; }
+static int64_t ld_multiple(int dtype) { return scaled(dtype) || minmax(dtype) ? TWA_SCALE_SPAN : TWA_LD_MULTIPLE; }
 
 static int check_dims(int64_t D, int32_t n, int64_t ld, int dtype) {
   const int bits = bits_of(dtype);
@@ -77,6 +80,10 @@ static int view_of(const twa_pmat* P, PView* v) {
   if (!aligned16(P->data)) return TWA_ERR_ALIGN;
   int shift = 0;
   float gscale = 1.0f;
+  if (minmax(P->dtype)) {
+    if (!P->scales) return TWA_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(P->scales) & 7u) return TWA_ERR_ALIGN;
+  }
   if (scaled(P->dtype)) {
     if (!P->scales) return TWA_ERR_NULL;
     if (!aligned16(P->scales)) return TWA_ERR_ALIGN;
@@ -244,7 +251,8 @@ int twa_expand_update(const twa_pmat* P, const float* s, float* w, float lr, flo
 int twa_project_layers_workspace_bytes(int32_t n, int32_t L, size_t* bytes) {
   if (!bytes) return TWA_ERR_NULL;
   if (n <= 0 || n > TWA_MAX_N || L <= 0 || L > TWA_MAX_LAYERS) return TWA_ERR_SHAPE;
-  *bytes = ((size_t)kMaxGrid + (size_t)L) * (size_t)n * sizeof(float);
+  // partial sums per (workgroup + layer) slot: n coefficients, and one more number for the min-max formats
+  *bytes = ((size_t)kMaxGrid + (size_t)L) * ((size_t)n + 1) * sizeof(float);
   return TWA_OK;
 }
 
@@ -331,6 +339,32 @@ int twa_beta_update(float* beta, const float* s, int64_t count, float lr, float 
   if ((reinterpret_cast<uintptr_t>(beta) & 3u) || (reinterpret_cast<uintptr_t>(s) & 3u)) return TWA_ERR_ALIGN;
   if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
   return launch_beta_update(beta, s, count, lr, lambda, static_cast<hipStream_t>(stream));
+}
+
+int twa_quantize_minmax_workspace_bytes(int32_t L, size_t* bytes) {
+  if (!bytes) return TWA_ERR_NULL;
+  if (L <= 0 || L > TWA_MAX_LAYERS) return TWA_ERR_SHAPE;
+  *bytes = minmax_workspace_bytes(L);
+  return TWA_OK;
+}
+
+int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const void* plan, int32_t L, twa_pmat* out,
+                        void* ws, size_t ws_bytes, void* stream) {
+  if (!P || !out || !out->data || !out->scales) return TWA_ERR_NULL;
+  if (!minmax(out->dtype)) return TWA_ERR_DTYPE;
+  if (out->D != D || out->n != n) return TWA_ERR_SHAPE;
+  int rc = check_dims(D, n, ldp, TWA_F32);
+  if (rc != TWA_OK) return rc;
+  rc = check_dims(D, n, out->ld, out->dtype);
+  if (rc != TWA_OK) return rc;
+  rc = check_plan(plan, L);
+  if (rc != TWA_OK) return rc;
+  if (!aligned16(P) || !aligned16(out->data) || (reinterpret_cast<uintptr_t>(out->scales) & 7u)) return TWA_ERR_ALIGN;
+  if (!ws || ws_bytes < minmax_workspace_bytes(L)) return TWA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 7u) return TWA_ERR_ALIGN;
+  if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_quantize_minmax(P, D, n, ldp, plan, L, out->dtype, static_cast<uint8_t*>(out->data), out->ld,
+                                static_cast<float*>(out->scales), ws, static_cast<hipStream_t>(stream));
 }
 
 int twa_centre_normalise_workspace_bytes(int64_t D, int32_t n, int32_t L, size_t* bytes) {

@@ -85,6 +85,25 @@ template <> struct Store<TWA_I4> {
   static constexpr int kScaleBytes = 2;
 };
 
+// The paper's own format: unsigned codes, one (a, b) pair per layer, no per-block scales.  The
+// stored bytes are those of I8 (c - 128) and I4 (nibbles), so they share the decoders.
+template <> struct Store<TWA_U8MM> {
+  static constexpr int kEPV = 16;
+  static constexpr int kBitsPerElem = 8;
+  static constexpr bool kScaled = false;
+  static constexpr int kScaleBytes = 0;
+};
+template <> struct Store<TWA_U4MM> {
+  static constexpr int kEPV = 32;
+  static constexpr int kBitsPerElem = 4;
+  static constexpr bool kScaled = false;
+  static constexpr int kScaleBytes = 0;
+};
+template <int DT> constexpr bool kMinMax = DT == TWA_U8MM || DT == TWA_U4MM;
+template <int DT> constexpr bool kNibbles = DT == TWA_I4 || DT == TWA_U4MM;
+// decoded code = c - kCodeBias<DT> for the min-max formats
+template <int DT> constexpr float kCodeBias = DT == TWA_U8MM ? 128.0f : 0.0f;
+
 // Decode one 128-bit vector into kEPV "raw" floats: the stored value up to the per-block
 // scale, and for I4 up to the bias and nibble position:
 //   F32, BF16 : raw = value
@@ -132,6 +151,9 @@ template <> __device__ __forceinline__ void decode<TWA_I4>(const u32x4& v, float
     raw[8 * q + 7] = (float)(hi >> 24);
   }
 }
+
+template <> __device__ __forceinline__ void decode<TWA_U8MM>(const u32x4& v, float* raw) { decode<TWA_I8>(v, raw); }
+template <> __device__ __forceinline__ void decode<TWA_U4MM>(const u32x4& v, float* raw) { decode<TWA_I4>(v, raw); }
 
 // Scale of one block as a float (binary16 scales are widened and multiplied by gscale).
 template <int DT> __device__ __forceinline__ float load_scale(rsrc_t r, uint32_t voff, float gscale) {

@@ -50,8 +50,12 @@ struct Expander {
 
   // sums of tile e0 over all basis vectors with the coefficients sv[0..n) (for I4 the bias / nibble
   // corrections are applied at the end)
-  __device__ __forceinline__ void accumulate(int64_t e0, float (&acc)[VPL][EPV], const float* __restrict__ sv) const {
+  // Min-max formats (Sec. 4.6): mm_a scales every coefficient, and mm_b * sum_j s_j is added at the end
+  // (mm_b = b_l + bias * a_l for codes stored relative to `bias`).
+  __device__ __forceinline__ void accumulate(int64_t e0, float (&acc)[VPL][EPV], const float* __restrict__ sv,
+                                             float mm_a = 1.0f, float mm_b = 0.0f) const {
     const int n = P.n;
+    float ssum = 0.0f;
     float tsum[VPL];
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
@@ -77,7 +81,11 @@ struct Expander {
         const int j = j0 + u;
         const bool valid = j < n;
         const int col = valid ? j : 0;
-        const float sj = valid ? sv[col] : 0.0f;
+        float sj = valid ? sv[col] : 0.0f;
+        if constexpr (kMinMax<DT>) {
+          ssum += sj;
+          sj *= mm_a;
+        }
         const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
@@ -116,6 +124,14 @@ struct Expander {
 #pragma unroll
         for (int e = 0; e < EPV; ++e)
           acc[v][e] = ((e & 1) ? acc[v][e] * 0.0625f : acc[v][e]) - 8.0f * tsum[v];
+    }
+    if constexpr (kMinMax<DT>) {
+      const float add = mm_b * ssum;
+#pragma unroll
+      for (int v = 0; v < VPL; ++v)
+#pragma unroll
+        for (int e = 0; e < EPV; ++e)
+          acc[v][e] = ((kNibbles<DT> && (e & 1)) ? acc[v][e] * 0.0625f : acc[v][e]) + add;   // odd nibbles: 16*code
     }
   }
 
@@ -235,6 +251,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
     int64_t e0;
     uint32_t lo, hi;
     const float* sv;
+    float mm_a, mm_b;                   // min-max formats: the layer's a_l and b_l + bias * a_l
   };
   // (the plan is read again for every tile: keeping a layer's numbers in registers across the
   //  tiles costs registers this kernel does not have, and a tile is long enough to hide the loads)
@@ -246,9 +263,15 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
       int64_t hi = plan.off[c + 1];
       hi = hi < D ? hi : D;
       const int64_t e0 = (lo & ~(int64_t)(kLayerAlign - 1)) + (t - plan.first[c]) * X::TILE;
-      return Where{e0, (uint32_t)lo, (uint32_t)hi, s + (int64_t)c * P.n};
+      float ma = 1.0f, mb = 0.0f;
+      if constexpr (kMinMax<DT>) {
+        const float* ab = reinterpret_cast<const float*>(P.scales) + 2 * (int64_t)c;
+        ma = ab[0];
+        mb = ab[1] + kCodeBias<DT> * ma;
+      }
+      return Where{e0, (uint32_t)lo, (uint32_t)hi, s + (int64_t)c * P.n, ma, mb};
     } else {
-      return Where{t * X::TILE, 0u, (uint32_t)D, s};
+      return Where{t * X::TILE, 0u, (uint32_t)D, s, 1.0f, 0.0f};
     }
   };
   int cur = cur0;                       // cursor of the reading phases
@@ -262,7 +285,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
     u32x4 wv[VPL][EPV / 4];
     x.load_w(at.e0, wv);                  // issued before the stream of P, consumed after it
     float acc[VPL][EPV];
-    x.accumulate(at.e0, acc, at.sv);
+    x.accumulate(at.e0, acc, at.sv, at.mm_a, at.mm_b);
     x.update_store(at.e0, acc, wv, at.lo, at.hi);
   }
 
@@ -272,7 +295,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   if (lds_tile) {
     const Where at = locate(t_lds, cur);
     float acc[VPL][EPV];
-    x.accumulate(at.e0, acc, at.sv);
+    x.accumulate(at.e0, acc, at.sv, at.mm_a, at.mm_b);
 #pragma unroll
     for (int v = 0; v < VPL; ++v) x.rows_to_lds(acc[v], lhold[wave][v]);
   }
@@ -285,7 +308,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
     const int64_t t = first + 4 * (int64_t)(reg0 + i);
     if (reg0 + i < rounds && t < ntiles) {
       const Where at = locate(t, cur);
-      x.accumulate(at.e0, held[i], at.sv);
+      x.accumulate(at.e0, held[i], at.sv, at.mm_a, at.mm_b);
     }
   }
   // ---- ... and everything is written in one burst once this wave has finished reading (the same
@@ -336,6 +359,18 @@ static int launch_expand_any(const PView& P, int dtype, const float* s, const fl
     case TWA_BF16: launch_expand_cfg<TWA_BF16, 2, 4, 6, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
     case TWA_I8: launch_expand_cfg<TWA_I8, 4, 2, 6, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
     case TWA_I4: launch_expand_cfg<TWA_I4, 8, 1, 5, 0, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_U8MM:
+      if constexpr (LAYERED) {
+        launch_expand_cfg<TWA_U8MM, 4, 2, 6, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        break;
+      }
+      return TWA_ERR_DTYPE;
+    case TWA_U4MM:
+      if constexpr (LAYERED) {
+        launch_expand_cfg<TWA_U4MM, 8, 1, 5, 0, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        break;
+      }
+      return TWA_ERR_DTYPE;
     default: return TWA_ERR_DTYPE;
   }
   return hip_check(hipGetLastError());

@@ -1,0 +1,173 @@
+// The paper's own quantiser of the projection matrix (arXiv 2205.13104, Sec. 4.6): uniform min-max
+// codes with ONE scaling and zero factor per layer, shared by all n basis vectors:
+//     a_l = (max - min)/(2^B - 1),  b_l = min,  c = round((p - b_l)/a_l) in [0, 2^B - 1].
+// One-time work in three small steps, each bound by one pass over the fp32 matrix or less:
+//   1. layer_minmax_kernel   minimum and maximum of every layer over all vectors.  Workgroups walk
+//      the per-layer tiles of the plan; a wave reduces what it saw of a layer and merges it with
+//      integer atomics on an order-preserving key of the float (min and max do not depend on the
+//      order, so the result is deterministic);
+//   2. layer_factors_kernel  (a_l, b_l): binary32 for the stored matrix, a_l also in fp64 for step 3;
+//   3. minmax_codes_kernel   the codes, in fp64 with ties to even like the definition's oracle
+//      (a constant layer, a_l = 0, gets c = 0), packed into dwords.
+#include <math.h>
+
+#include "twa_device.h"
+#include "twa_host.h"
+
+namespace twa {
+
+// order-preserving map float -> uint32 (larger float <=> larger key)
+__device__ __forceinline__ uint32_t key_of(float f) {
+  const uint32_t u = as_u32(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float float_of(uint32_t k) {
+  return as_f32((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+__global__ __launch_bounds__(256) void minmax_init_kernel(uint32_t* __restrict__ keys, int L) {
+  const int l = blockIdx.x * 256 + threadIdx.x;
+  if (l < L) {
+    keys[2 * l] = 0xffffffffu;        // running minimum
+    keys[2 * l + 1] = 0u;             // running maximum
+  }
+}
+
+// Tiles of 2048 elements: a thread owns 8 consecutive elements of the tile, for every vector.
+__global__ __launch_bounds__(256) void layer_minmax_kernel(const float* __restrict__ P, int64_t D, int n, int64_t ldp,
+                                                           LayerPlan plan, uint32_t* __restrict__ keys) {
+  constexpr int TILE = 2048;
+  const int ntiles = plan.first[plan.L];
+  const int per = (ntiles + gridDim.x - 1) / gridDim.x;
+  const int t0 = blockIdx.x * per;
+  const int t1 = t0 + per < ntiles ? t0 + per : ntiles;
+  if (t0 >= t1) return;
+  const uint32_t bytes = (uint32_t)(D * 4);
+  LayerCursor lc{0, 0, 0, 0, 0};
+  lc.load(plan, layer_of_tile(plan, t0));
+  float mn = INFINITY, mx = -INFINITY;
+  auto merge = [&](int layer) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      mn = fminf(mn, __shfl_xor(mn, m, kWave));
+      mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0 && mn <= mx) {
+      atomicMin(&keys[2 * layer], key_of(mn));
+      atomicMax(&keys[2 * layer + 1], key_of(mx));
+    }
+    mn = INFINITY;
+    mx = -INFINITY;
+  };
+  for (int t = t0; t < t1; ++t) {
+    if (lc.behind(plan, t)) {
+      merge(lc.cur);
+      lc.seek(plan, t);
+    }
+    const int64_t hi = lc.hi < D ? lc.hi : D;
+    const int64_t i0 = lc.tile_start(t, TILE) + 8 * (int64_t)threadIdx.x;
+    for (int j = 0; j < n; ++j) {
+      const rsrc_t rc = make_rsrc(P + (int64_t)j * ldp, bytes);
+      const u32x4 x0 = ld128_stream(rc, (uint32_t)i0 * 4u), x1 = ld128_stream(rc, (uint32_t)i0 * 4u + 16u);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const float v = as_f32(r < 4 ? x0[r] : x1[r - 4]);
+        if (i0 + r >= lc.lo && i0 + r < hi) {
+          mn = fminf(mn, v);
+          mx = fmaxf(mx, v);
+        }
+      }
+    }
+  }
+  merge(lc.cur);
+}
+
+// ab[2l] = (float)a_l, ab[2l+1] = b_l; a64[l] = a_l in fp64.  An empty layer gets (0, 0).
+__global__ __launch_bounds__(256) void layer_factors_kernel(const uint32_t* __restrict__ keys, int L, double levels,
+                                                            float* __restrict__ ab, double* __restrict__ a64) {
+  const int l = blockIdx.x * 256 + threadIdx.x;
+  if (l >= L) return;
+  const uint32_t kmin = keys[2 * l], kmax = keys[2 * l + 1];
+  double a = 0.0;
+  float b = 0.0f;
+  if (kmin <= kmax) {                       // the layer has elements
+    const float mn = float_of(kmin), mx = float_of(kmax);
+    a = ((double)mx - (double)mn) / levels;
+    b = mn;
+  }
+  ab[2 * l] = (float)a;
+  ab[2 * l + 1] = b;
+  a64[l] = a;
+}
+
+// A thread packs EL consecutive elements of one vector into one dword: 4 bytes (c - 128) or 8 nibbles.
+template <int DT>
+__global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restrict__ P, int64_t D, int64_t ldp,
+                                                           uint8_t* __restrict__ codes, int64_t ld,
+                                                           const int64_t* __restrict__ off, int L,
+                                                           const float* __restrict__ ab,
+                                                           const double* __restrict__ a64, double levels) {
+  constexpr int EL = (DT == TWA_U8MM) ? 4 : 8;
+  const int j = blockIdx.y;
+  const int64_t nvec = ld / EL;
+  const float* p = P + (int64_t)j * ldp;
+  uint32_t* out = reinterpret_cast<uint32_t*>(codes + (((int64_t)j * ld * Store<DT>::kBitsPerElem) >> 3));
+  for (int64_t vec = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; vec < nvec;
+       vec += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i0 = vec * EL;
+    uint32_t word = 0;
+    if (i0 < D) {
+      int a_ = 0, b_ = L - 1;                   // largest l with off[l] <= i0
+      while (a_ < b_) {
+        const int mid = (a_ + b_ + 1) >> 1;
+        if (off[mid] <= i0) a_ = mid; else b_ = mid - 1;
+      }
+      int l = a_;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) {
+        const int64_t i = i0 + e;
+        uint32_t c = 0;
+        if (i < D) {
+          while (l < L - 1 && off[l + 1] <= i) ++l;
+          const double a = a64[l], b = (double)ab[2 * l + 1];
+          double q = a > 0.0 ? rint(((double)p[i] - b) / a) : 0.0;
+          q = q < 0.0 ? 0.0 : (q > levels ? levels : q);
+          c = (uint32_t)q;
+        }
+        if constexpr (DT == TWA_U8MM) word |= ((c ^ 0x80u) & 0xffu) << (8 * e);      // c - 128 as int8
+        else word |= (c & 0xfu) << (4 * e);                                          // even element in the low nibble
+      }
+    } else if constexpr (DT == TWA_U8MM) {
+      word = 0x80808080u;                       // padding: code 0
+    }
+    out[vec] = word;
+  }
+}
+
+size_t minmax_workspace_bytes(int L) { return (size_t)L * (2 * sizeof(uint32_t) + sizeof(double)); }
+
+int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const void* plan_dev, int L, int dtype,
+                           uint8_t* codes, int64_t ld, float* ab, void* ws, hipStream_t st) {
+  double* a64 = static_cast<double*>(ws);                         // 8-byte aligned first
+  uint32_t* keys = reinterpret_cast<uint32_t*>(a64 + L);
+  const LayerPlan plan = plan_view(plan_dev, L, 2048);
+  const double levels = dtype == TWA_U8MM ? 255.0 : 15.0;
+  const int lgrid = (L + 255) / 256;
+  hipLaunchKernelGGL(minmax_init_kernel, dim3(lgrid), dim3(256), 0, st, keys, L);
+  const int cus = device_cus();
+  hipLaunchKernelGGL(layer_minmax_kernel, dim3(cus * 4), dim3(256), 0, st, P, D, n, ldp, plan, keys);
+  hipLaunchKernelGGL(layer_factors_kernel, dim3(lgrid), dim3(256), 0, st, keys, L, levels, ab, a64);
+  const int el = dtype == TWA_U8MM ? 4 : 8;
+  const int64_t nvec = ld / el;
+  int gx = (int)((nvec + 255) / 256);
+  if (gx > cus * 8) gx = cus * 8;
+  if (dtype == TWA_U8MM)
+    hipLaunchKernelGGL(minmax_codes_kernel<TWA_U8MM>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L,
+                       ab, a64, levels);
+  else
+    hipLaunchKernelGGL(minmax_codes_kernel<TWA_U4MM>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L,
+                       ab, a64, levels);
+  return hip_check(hipGetLastError());
+}
+
+}  // namespace twa

@@ -35,7 +35,8 @@ namespace twa {
 template <int DT, int KB, int U, int NCH, int VPL, bool LAYERED, bool SQUARES = false>
 __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __restrict__ g, int64_t ldg,
                                                       int kvalid, float* __restrict__ partial, int cpw,
-                                                      int tiles_per_wg, LayerPlan plan) {
+                                                      int tiles_per_wg, LayerPlan plan,
+                                                      float* __restrict__ partial_g) {
   using S = Store<DT>;
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
@@ -71,8 +72,15 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
 #pragma unroll
     for (int c = 0; c < KB; ++c) acc[sl][c] = 0.0f;
 
+  // min-max formats: the layer's sum of the gradient itself (the zero point b_l multiplies it)
+  float gsum = 0.0f;
   // one reduction over the wave's lanes, then the partial sums of row `slot_row`
   auto flush = [&](int slot_row) {
+    if constexpr (kMinMax<DT>) {
+      const float tot = wave_sum_to_last_lane(gsum);
+      if (wave == 0 && lane == kSumLane) partial_g[slot_row] = tot;
+      gsum = 0.0f;
+    }
 #pragma unroll
     for (int sl = 0; sl < SLOTS; ++sl) {
 #pragma unroll
@@ -136,13 +144,16 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
             for (int e = 0; e < EPV; ++e) gs[c][v][e] = rel + e >= head ? gs[c][v][e] : 0.0f;
           }
         }
-        if constexpr (DT == TWA_I4) {
+        if constexpr (kNibbles<DT> || kMinMax<DT>) {
           float sum = 0.0f;
 #pragma unroll
           for (int e = 0; e < EPV; ++e) sum += gs[c][v][e];
-          gcorr[c][v] = -8.0f * sum;                       // codes are stored as q+8
+          if constexpr (kMinMax<DT>) gsum += sum;
+          gcorr[c][v] = kNibbles<DT> ? -8.0f * sum : 0.0f;     // nibble codes are taken relative to 8
+          if constexpr (kNibbles<DT>) {
 #pragma unroll
-          for (int e = 1; e < EPV; e += 2) gs[c][v][e] *= 0.0625f;   // odd nibbles decode as 16*(q+8)
+            for (int e = 1; e < EPV; e += 2) gs[c][v][e] *= 0.0625f;   // odd nibbles decode as 16*code
+          }
         } else {
           gcorr[c][v] = 0.0f;
         }
@@ -204,7 +215,7 @@ __global__ __launch_bounds__(256) void project_kernel(PView P, const float* __re
               for (int e = 0; e < EPV; ++e) d = __builtin_fmaf(x[e], gs[c][v][e], d);
               acc[slot][c] = __builtin_fmaf(d, sc[u][v], acc[slot][c]);
             } else {
-              float d = acc[slot][c];
+              float d = acc[slot][c] + (kNibbles<DT> ? gcorr[c][v] : 0.0f);
 #pragma unroll
               for (int e = 0; e < EPV; ++e) d = __builtin_fmaf(SQUARES ? x[e] * gs[c][v][e] : x[e], SQUARES ? x[e] : gs[c][v][e], d);
               acc[slot][c] = d;
@@ -410,7 +421,8 @@ static void divide_tiles(int64_t D, int tile, int max_grid, int* grid, int* tile
 
 template <int DT, int KB, int VPL, bool LAYERED = false, bool SQUARES = false>
 static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kvalid, float* partial, int max_grid,
-                             int* grid_out, hipStream_t st, LayerPlan plan = LayerPlan{nullptr, nullptr, 1}) {
+                             int* grid_out, hipStream_t st, LayerPlan plan = LayerPlan{nullptr, nullptr, 1},
+                             float* partial_g = nullptr) {
   const int cpw = (P.n + 3) / 4;
   constexpr int tile = kWave * VPL * Store<DT>::kEPV;
   int grid, tiles_per_wg;
@@ -420,7 +432,7 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
 #define TWA_LAUNCH(U_, NCH_)                                                                         \
   hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL, LAYERED, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
-                     kvalid, partial, cpw, tiles_per_wg, plan)
+                     kvalid, partial, cpw, tiles_per_wg, plan, partial_g)
   {
     if (cpw == 25) {
       TWA_LAUNCH(5, 5);
@@ -476,15 +488,44 @@ __global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_kernel(const 
   S[(int64_t)l * n + j] = (float)a;
 }
 
+// The min-max formats (Sec. 4.6): (P~^l)^T g^l = a_l * (C^l)^T g^l + (b_l + bias * a_l) * sum(g^l), where C holds
+// the decoded codes (code - bias).  Same summation order as above.
+__global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_minmax_kernel(
+    const float* __restrict__ partial, const float* __restrict__ partial_g, int n, LayerPlan plan, int grid,
+    const float* __restrict__ ab, float bias, float* __restrict__ S) {
+  const int l = blockIdx.x;
+  const int j = threadIdx.x;
+  if (j >= n) return;
+  const int ntiles = plan.first[plan.L];
+  const int tiles_per_wg = ntiles > 0 ? (ntiles + grid - 1) / grid : 1;      // as in project_kernel
+  const int32_t ta = plan.first[l], tb = plan.first[l + 1];
+  double a = 0.0, gs = 0.0;
+  if (tb > ta) {
+    const int b0 = ta / tiles_per_wg, b1 = (tb - 1) / tiles_per_wg;
+    for (int b = b0; b <= b1; ++b) {
+      a += (double)partial[(int64_t)(b + l) * n + j];
+      gs += (double)partial_g[b + l];
+    }
+  }
+  const double al = (double)ab[2 * l], bl = (double)ab[2 * l + 1];
+  S[(int64_t)l * n + j] = (float)(al * a + (bl + (double)bias * al) * gs);
+}
+
 template <int DT, int VPL>
 static int launch_project_layers_dt(const PView& P, const float* g, const void* plan_dev, int L, float* S,
                                     float* partial, int max_grid, hipStream_t st) {
   constexpr int tile = kWave * VPL * Store<DT>::kEPV;
   const LayerPlan plan = plan_view(plan_dev, L, tile);
   int grid = 0;
-  int rc = launch_project_dt<DT, 1, VPL, true>(P, g, 0, 1, partial, max_grid, &grid, st, plan);
+  float* partial_g = partial + ((size_t)kMaxGrid + (size_t)L) * P.n;        // min-max formats only
+  int rc = launch_project_dt<DT, 1, VPL, true>(P, g, 0, 1, partial, max_grid, &grid, st, plan, partial_g);
   if (rc != TWA_OK) return rc;
-  hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, S);
+  if constexpr (kMinMax<DT>) {
+    hipLaunchKernelGGL(project_layers_reduce_minmax_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, partial_g, P.n,
+                       plan, grid, reinterpret_cast<const float*>(P.scales), kNibbles<DT> ? 8.0f : 128.0f, S);
+  } else {
+    hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, S);
+  }
   return hip_check(hipGetLastError());
 }
 
@@ -508,6 +549,8 @@ int launch_project_layers(const PView& P, int dtype, const float* g, const void*
     case TWA_BF16: return launch_project_layers_dt<TWA_BF16, 2>(P, g, plan_dev, L, S, partial, max_grid, st);
     case TWA_I8: return launch_project_layers_dt<TWA_I8, 2>(P, g, plan_dev, L, S, partial, max_grid, st);
     case TWA_I4: return launch_project_layers_dt<TWA_I4, 1>(P, g, plan_dev, L, S, partial, max_grid, st);
+    case TWA_U8MM: return launch_project_layers_dt<TWA_U8MM, 2>(P, g, plan_dev, L, S, partial, max_grid, st);
+    case TWA_U4MM: return launch_project_layers_dt<TWA_U4MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st);
     default: return TWA_ERR_DTYPE;
   }
 }

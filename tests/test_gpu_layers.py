@@ -128,6 +128,59 @@ def test_layer_rows_add_up_to_the_whole_model_projection():
     assert torch.equal(S, twa.project_layers(pm, g, off))
 
 
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("D,n", [(70001, 7), (300_017, 100), (1_234_567, 33)])
+def test_minmax_format_matches_oracle(bits, D, n):
+    """The paper's own quantiser (Sec. 4.6): codes and factors bit-exact against the fp64 oracle, then the
+    layer-wise step on the stored matrix within the bar."""
+    for name, sizes in layer_tables(D):
+        off_cpu = synth.layer_offsets(sizes)
+        L = len(sizes)
+        plan = twa.LayerPlan(off_cpu, D)
+        P32 = random_basis_like(D, n, seed=D % 1000 + n + bits)
+        P32[0, :64] = 3.0 * P32[0, :64]                         # an outlier decides a layer's range
+        say("minmax", bits, "D", D, "n", n, name, "L", L)
+        pm = twa.quantize_minmax(P32, D, plan, bits=bits)
+        torch.cuda.synchronize()
+        codes_o, a_o, b_o = orc.quantize_minmax(P32[:, :D].cpu().numpy().astype(np.float64), bits, off_cpu.numpy())
+        po = to_oracle(pm, layer_off=off_cpu.numpy())
+        assert np.array_equal(po.data[:, :D], codes_o)
+        ab = pm.scales.cpu().numpy()
+        assert np.array_equal(ab[:, 0], a_o.astype(np.float32)) and np.array_equal(ab[:, 1], b_o.astype(np.float32))
+        # the stored values stay within half a step of the original
+        g = synth.gradient(D, 1e-2, seed=3, device="cuda")
+        S = twa.project_layers(pm, g, plan)
+        S_ref = orc.project_layers(po, g.cpu().numpy().astype(np.float64), off_cpu.numpy())
+        assert rel_l2(S.cpu().numpy(), S_ref) <= REL_L2_TOL
+        scale = np.abs(S_ref).max()
+        Sg = S.cpu().numpy()
+        for l in range(L):
+            assert np.linalg.norm(Sg[l] - S_ref[l]) <= REL_L2_TOL * max(np.linalg.norm(S_ref[l]), scale), (l, sizes[l])
+        gen = torch.Generator().manual_seed(D + bits)
+        S2 = torch.randn((L, n), generator=gen, dtype=torch.float32).cuda()
+        w0 = synth.gradient(D, 0.05, seed=9, device="cuda")
+        w = w0.clone()
+        gt = torch.full((D,), float("nan"), device="cuda")
+        twa.expand_update_layers(pm, S2, plan, w, 0.1, gt)
+        torch.cuda.synchronize()
+        w_ref = w0.cpu().numpy().astype(np.float64)
+        gt_ref = orc.expand_update_layers(po, S2.cpu().numpy().astype(np.float64), off_cpu.numpy(), w_ref,
+                                          float(np.float32(0.1)), want_gt=True)
+        assert rel_l2(gt.cpu().numpy(), gt_ref) <= REL_L2_TOL
+        assert rel_l2(w.cpu().numpy(), w_ref) <= REL_L2_TOL
+        gg = gt.cpu().numpy()
+        rms = float(np.sqrt(np.mean(gt_ref ** 2)))
+        for l in range(L):
+            a, b = int(off_cpu[l]), int(off_cpu[l + 1])
+            if b > a:
+                bound = max(np.linalg.norm(gt_ref[a:b]), rms * (b - a) ** 0.5)
+                assert np.linalg.norm(gg[a:b] - gt_ref[a:b]) <= 2 * REL_L2_TOL * bound, (l, a, b)
+    # the whole-model calls do not take this format
+    with pytest.raises(twa.TwaError) as e:
+        twa.project(pm, g)
+    assert e.value.code == twa.ERR_DTYPE
+
+
 def test_plan_tables():
     D = 10_000
     plan = twa.LayerPlan([0, 5, 5, 40, 2100, 2100, 9000, D], D)
