@@ -284,6 +284,16 @@ int twa_centre_normalise(const float* W, int64_t D, int32_t n, int64_t ldw, cons
 int twa_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, void* stream);
 
 /*
+ * Both "update variables" steps of Alg. 1 in one call: s = (P^l)^T g^l for every layer, then
+ * beta <- (1 - lr*lambda) * beta - lr * s, the second inside the reduction kernel of the first (one
+ * launch less than twa_project_layers + twa_beta_update).
+ *   beta [in/out] L*n floats.   S [out, optional] L*n floats receiving s (NULL: not stored).
+ *   ws, ws_bytes  as for twa_project_layers.
+ */
+int twa_beta_step(const twa_pmat* P, const float* g, const void* plan, int32_t L, float* beta, float lr, float lambda,
+                  float* S, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * w^l = wbar^l + P^l beta^l   (Alg. 1, "update weights"; Sec. 4.3).  The same pass over P as
  * twa_expand_update_layers.
  *   beta [in] L*n floats.   wbar [in] D floats.   w [out] D floats (may be wbar's buffer).

@@ -73,6 +73,8 @@ def lib():
         L.twa_centre_normalise_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(C.c_size_t)]
         L.twa_centre_normalise.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp, i64, vp, vp, C.c_size_t, vp]
         L.twa_beta_update.argtypes = [vp, vp, i64, f32, f32, vp]
+        L.twa_beta_step.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, f32, f32, vp, vp, C.c_size_t, vp]
+        L.twa_beta_step.restype = C.c_int
         L.twa_weights_from_beta.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, vp, vp]
         for f in (L.twa_project_layers_workspace_bytes, L.twa_project_layers, L.twa_expand_update_layers,
                   L.twa_layer_plan_bytes, L.twa_layer_plan, L.twa_centre_normalise_workspace_bytes,
@@ -337,6 +339,18 @@ def beta_update(beta: torch.Tensor, s: torch.Tensor, lr: float, lam: float = 0.0
     assert beta.is_contiguous() and s.is_contiguous()
     _check(lib().twa_beta_update(_ptr(beta), _ptr(s), beta.numel(), float(lr), float(lam), _stream()),
            "twa_beta_update")
+
+
+def beta_step(P: Pmat, g: torch.Tensor, plan: LayerPlan, beta: torch.Tensor, lr: float, lam: float = 0.0,
+              S: Optional[torch.Tensor] = None, ws: Optional[Workspace] = None) -> None:
+    """twa_beta_step: s = (P^l)^T g^l and beta <- (1 - lr*lam) * beta - lr * s in one call (s stored in S if given)."""
+    assert g.dtype == torch.float32 and g.is_contiguous() and g.dim() == 1 and plan.D == P.D
+    assert beta.dtype == torch.float32 and beta.is_contiguous() and tuple(beta.shape) == (plan.L, P.n)
+    if ws is None:
+        ws = Workspace(project_layers_workspace_bytes(P.n, plan.L), device=g.device)
+    st = P.c_struct()
+    _check(lib().twa_beta_step(C.byref(st), _ptr(g), plan.ptr, plan.L, _ptr(beta), float(lr), float(lam), _ptr(S),
+                               ws.ptr, ws.nbytes, _stream()), "twa_beta_step")
 
 
 def weights_from_beta(P: Pmat, beta: torch.Tensor, plan: LayerPlan, wbar: torch.Tensor,

@@ -281,23 +281,36 @@ static int check_plan(const void* plan, int32_t L) {
   return TWA_OK;
 }
 
-int twa_project_layers(const twa_pmat* P, const float* g, const void* plan, int32_t L, float* S, void* ws,
-                       size_t ws_bytes, void* stream) {
+static int project_layers_common(const twa_pmat* P, const float* g, const void* plan, int32_t L, float* S, float* beta,
+                                 float lr, float lambda, void* ws, size_t ws_bytes, void* stream) {
   PView v;
   int rc = view_of(P, &v);
   if (rc != TWA_OK) return rc;
-  if (!g || !S) return TWA_ERR_NULL;
+  if (!g || (!S && !beta)) return TWA_ERR_NULL;
   rc = check_plan(plan, L);
   if (rc != TWA_OK) return rc;
-  if (!aligned16(g) || (reinterpret_cast<uintptr_t>(S) & 3u)) return TWA_ERR_ALIGN;
+  if (!aligned16(g) || (reinterpret_cast<uintptr_t>(S) & 3u) || (reinterpret_cast<uintptr_t>(beta) & 3u))
+    return TWA_ERR_ALIGN;
   size_t need = 0;
   twa_project_layers_workspace_bytes(v.n, L, &need);
   if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
   if (!aligned16(ws)) return TWA_ERR_ALIGN;
   const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
-  return launch_project_layers(v, P->dtype, g, plan, L, S, static_cast<float*>(ws), grid,
+  return launch_project_layers(v, P->dtype, g, plan, L, S, beta, lr, lambda, static_cast<float*>(ws), grid,
                                static_cast<hipStream_t>(stream));
+}
+
+int twa_project_layers(const twa_pmat* P, const float* g, const void* plan, int32_t L, float* S, void* ws,
+                       size_t ws_bytes, void* stream) {
+  if (!S) return TWA_ERR_NULL;
+  return project_layers_common(P, g, plan, L, S, nullptr, 0.0f, 0.0f, ws, ws_bytes, stream);
+}
+
+int twa_beta_step(const twa_pmat* P, const float* g, const void* plan, int32_t L, float* beta, float lr, float lambda,
+                  float* S, void* ws, size_t ws_bytes, void* stream) {
+  if (!beta) return TWA_ERR_NULL;
+  return project_layers_common(P, g, plan, L, S, beta, lr, lambda, ws, ws_bytes, stream);
 }
 
 int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan, int32_t L, float* w, float lr,

@@ -36,7 +36,7 @@ size_t layer_plan_bytes(int L);
 LayerPlan plan_view(const void* plan_dev, int L, int tile);
 int launch_layer_plan(const int64_t* layer_off, int L, int64_t D, void* plan_dev, hipStream_t st);
 int launch_project_layers(const PView& P, int dtype, const float* g, const void* plan_dev, int L, float* S,
-                          float* partial, int max_grid, hipStream_t st);
+                          float* beta, float lr, float lambda, float* partial, int max_grid, hipStream_t st);
 int launch_expand_update_layers(const PView& P, int dtype, const float* s, const void* plan_dev, int L,
                                 const float* w_in, float* w_out, float lr, float* g_tilde, int max_grid,
                                 hipStream_t st);

@@ -33,7 +33,8 @@ namespace twa {
 // SQUARES (with LAYERED, F32): no gradient; the sums are the squares of the stored elements of the
 // layer, sum_i P_ij^2 -- the squared norms that the layer-wise basis divides by (Sec. 4.5).
 template <int DT, int KB, int U, int NCH, int VPL, bool LAYERED, bool SQUARES = false>
-__global__ __launch_bounds__(256) void project_kernel(PView P, const float* __restrict__ g, int64_t ldg,
+// (launch bounds: two workgroups per compute unit, i.e. at most 256 registers per lane)
+__global__ __launch_bounds__(256, 2) void project_kernel(PView P, const float* __restrict__ g, int64_t ldg,
                                                       int kvalid, float* __restrict__ partial, int cpw,
                                                       int tiles_per_wg, LayerPlan plan,
                                                       float* __restrict__ partial_g) {
@@ -469,11 +470,22 @@ int launch_project(const PView& P, int dtype, const float* g, float* s, float* p
   return hip_check(hipGetLastError());
 }
 
+// What the layer-wise reduction does with a finished sum s: store it, and/or take the coefficient
+// step of Alg. 1 with it, beta <- (1 - lr*lambda) beta - lr s ("update variables").
+struct BetaStep {
+  float* beta;          // NULL: no step
+  float lr, lambda;
+  __device__ __forceinline__ void finish(float* __restrict__ S, int64_t at, float s) const {
+    if (S) S[at] = s;
+    if (beta) beta[at] = __builtin_fmaf(-lr, s, (1.0f - lr * lambda) * beta[at]);
+  }
+};
+
 // S[l][j] = sum of the partial slots (b + l) of the workgroups b that own tiles of layer l, in
 // workgroup order, accumulated in fp64.  One block per layer, one thread per basis vector.
 __global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_kernel(const float* __restrict__ partial, int n,
                                                                          LayerPlan plan, int grid,
-                                                                         float* __restrict__ S) {
+                                                                         float* __restrict__ S, BetaStep bs) {
   const int l = blockIdx.x;
   const int j = threadIdx.x;
   if (j >= n) return;
@@ -485,14 +497,14 @@ __global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_kernel(const 
     const int b0 = ta / tiles_per_wg, b1 = (tb - 1) / tiles_per_wg;
     for (int b = b0; b <= b1; ++b) a += (double)partial[(int64_t)(b + l) * n + j];
   }
-  S[(int64_t)l * n + j] = (float)a;
+  bs.finish(S, (int64_t)l * n + j, (float)a);
 }
 
 // The min-max formats (Sec. 4.6): (P~^l)^T g^l = a_l * (C^l)^T g^l + (b_l + bias * a_l) * sum(g^l), where C holds
 // the decoded codes (code - bias).  Same summation order as above.
 __global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_minmax_kernel(
     const float* __restrict__ partial, const float* __restrict__ partial_g, int n, LayerPlan plan, int grid,
-    const float* __restrict__ ab, float bias, float* __restrict__ S) {
+    const float* __restrict__ ab, float bias, float* __restrict__ S, BetaStep bs) {
   const int l = blockIdx.x;
   const int j = threadIdx.x;
   if (j >= n) return;
@@ -508,12 +520,12 @@ __global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_minmax_kernel
     }
   }
   const double al = (double)ab[2 * l], bl = (double)ab[2 * l + 1];
-  S[(int64_t)l * n + j] = (float)(al * a + (bl + (double)bias * al) * gs);
+  bs.finish(S, (int64_t)l * n + j, (float)(al * a + (bl + (double)bias * al) * gs));
 }
 
 template <int DT, int VPL>
 static int launch_project_layers_dt(const PView& P, const float* g, const void* plan_dev, int L, float* S,
-                                    float* partial, int max_grid, hipStream_t st) {
+                                    float* partial, int max_grid, hipStream_t st, BetaStep bs) {
   constexpr int tile = kWave * VPL * Store<DT>::kEPV;
   const LayerPlan plan = plan_view(plan_dev, L, tile);
   int grid = 0;
@@ -522,9 +534,9 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   if (rc != TWA_OK) return rc;
   if constexpr (kMinMax<DT>) {
     hipLaunchKernelGGL(project_layers_reduce_minmax_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, partial_g, P.n,
-                       plan, grid, reinterpret_cast<const float*>(P.scales), kNibbles<DT> ? 8.0f : 128.0f, S);
+                       plan, grid, reinterpret_cast<const float*>(P.scales), kNibbles<DT> ? 8.0f : 128.0f, S, bs);
   } else {
-    hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, S);
+    hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, S, bs);
   }
   return hip_check(hipGetLastError());
 }
@@ -537,20 +549,23 @@ int launch_layer_squares(const PView& P, const void* plan_dev, int L, float* Q, 
   int grid = 0;
   int rc = launch_project_dt<TWA_F32, 1, 4, true, true>(P, nullptr, 0, 1, partial, max_grid, &grid, st, plan);
   if (rc != TWA_OK) return rc;
-  hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, Q);
+  hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, Q,
+                     BetaStep{nullptr, 0.0f, 0.0f});
   return hip_check(hipGetLastError());
 }
 
-// Layer-wise projection.  `partial` holds (max_grid + L) * n floats.
+// Layer-wise projection.  `partial` holds (max_grid + L) * (n + 1) floats.  S and/or beta (the fused
+// coefficient step, beta <- (1 - lr*lambda) beta - lr s) receive the result.
 int launch_project_layers(const PView& P, int dtype, const float* g, const void* plan_dev, int L, float* S,
-                          float* partial, int max_grid, hipStream_t st) {
+                          float* beta, float lr, float lambda, float* partial, int max_grid, hipStream_t st) {
+  const BetaStep bs{beta, lr, lambda};
   switch (dtype) {
-    case TWA_F32: return launch_project_layers_dt<TWA_F32, 4>(P, g, plan_dev, L, S, partial, max_grid, st);
-    case TWA_BF16: return launch_project_layers_dt<TWA_BF16, 2>(P, g, plan_dev, L, S, partial, max_grid, st);
-    case TWA_I8: return launch_project_layers_dt<TWA_I8, 2>(P, g, plan_dev, L, S, partial, max_grid, st);
-    case TWA_I4: return launch_project_layers_dt<TWA_I4, 1>(P, g, plan_dev, L, S, partial, max_grid, st);
-    case TWA_U8MM: return launch_project_layers_dt<TWA_U8MM, 2>(P, g, plan_dev, L, S, partial, max_grid, st);
-    case TWA_U4MM: return launch_project_layers_dt<TWA_U4MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st);
+    case TWA_F32: return launch_project_layers_dt<TWA_F32, 4>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_BF16: return launch_project_layers_dt<TWA_BF16, 2>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_I8: return launch_project_layers_dt<TWA_I8, 2>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_I4: return launch_project_layers_dt<TWA_I4, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_U8MM: return launch_project_layers_dt<TWA_U8MM, 2>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_U4MM: return launch_project_layers_dt<TWA_U4MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     default: return TWA_ERR_DTYPE;
   }
 }

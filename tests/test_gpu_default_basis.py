@@ -90,6 +90,18 @@ def test_coefficient_form_of_the_step(dtype, lam):
         if lam == 0.0:
             twa.expand_update_layers(pm, S, plan, w_direct, lr)
             assert rel_l2(w_direct.cpu().numpy(), wo) <= REL_L2_TOL
+    # the fused call takes the same coefficient step
+    b1 = beta.clone()
+    b2 = beta.clone()
+    g = synth.gradient(D, 1e-2, seed=5, step=T, device="cuda")
+    S1 = twa.project_layers(pm, g, plan)
+    twa.beta_update(b1, S1, lr, lam)
+    S2 = torch.empty_like(S1)
+    twa.beta_step(pm, g, plan, b2, lr, lam, S=S2)
+    assert torch.equal(S1, S2) and torch.equal(b1, b2)
+    b3 = beta.clone()
+    twa.beta_step(pm, g, plan, b3, lr, lam)
+    assert torch.equal(b1, b3)
     # w may be written over wbar's buffer
     wb2 = wbar.clone()
     w2 = twa.weights_from_beta(pm, beta, plan, wb2, w=wb2)
