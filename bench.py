@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 METRIC = "projected steps/s and P-stream HBM GB/s (% of peak), D=25.6M n=100 int8"
+METRIC_LAYERWISE = "layer-wise coefficient-form steps/s (Alg. 1) and P-stream HBM GB/s (% of peak)"
 
 
 def log(*a):
@@ -52,7 +53,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=1000,
                     help="untimed steps; the device needs ~0.5 s of this load before the step time settles")
     ap.add_argument("--workload", default="imagenet_resnet50", help="name in synth.WORKLOADS")
-    ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4"])
+    ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4", "mm8", "mm4"],
+                    help="mm8 / mm4: the paper's per-layer min-max codes (layer-wise mode only)")
+    ap.add_argument("--mode", default="whole", choices=["whole", "layerwise"],
+                    help="whole: the headline step (orthonormal basis, s = P^T g, w -= lr P s).  layerwise: Alg. 1 as "
+                         "written -- per-layer centre+normalise basis, coefficient step with weight decay, w = wbar + P beta")
     ap.add_argument("--D", type=int, default=0, help="override the parameter count (smoke runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -78,7 +83,10 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     D = args.D or wl.D
     n = wl.n
-    dtype = {"f32": twa.F32, "bf16": twa.BF16, "i8": twa.I8, "i4": twa.I4}[args.storage]
+    dtype = {"f32": twa.F32, "bf16": twa.BF16, "i8": twa.I8, "i4": twa.I4, "mm8": twa.U8MM, "mm4": twa.U4MM}[args.storage]
+    layerwise = args.mode == "layerwise"
+    if dtype in (twa.U8MM, twa.U4MM) and not layerwise:
+        sys.exit("bench.py: the min-max formats exist for the layer-wise calls only (use --mode layerwise)")
 
     # ---- inputs: checkpoints -> orthonormal basis (in place) -> stored P ------------------------
     t0 = time.time()
@@ -86,10 +94,22 @@ def main():
     w = W[:, :D].mean(dim=0).contiguous()                  # the plain average: starting point of TWA
     torch.cuda.synchronize()
     t1 = time.time()
-    P32, _ = twa.build_basis(W, D, out=W, want_R=False)
+    plan = None
+    if layerwise:
+        sizes = synth.workload_layers(wl.name) if D == wl.D else synth.layer_offsets(synth.random_layer_sizes(D, 12, 11))
+        plan = twa.LayerPlan(sizes, D)
+        P32, w, _ = twa.centre_normalise(W, D, plan, out=W, want_norms=False)     # w = wbar: Alg. 1 starts at the mean
+        wbar = w.clone()
+    else:
+        P32, _ = twa.build_basis(W, D, out=W, want_R=False)
     torch.cuda.synchronize()
     t2 = time.time()
-    pm = twa.wrap_f32(P32, D) if dtype == twa.F32 else twa.quantize(P32, D, dtype)
+    if dtype == twa.F32:
+        pm = twa.wrap_f32(P32, D)
+    elif dtype in (twa.U8MM, twa.U4MM):
+        pm = twa.quantize_minmax(P32, D, plan, bits=8 if dtype == twa.U8MM else 4)
+    else:
+        pm = twa.quantize(P32, D, dtype)
     torch.cuda.synchronize()
     t3 = time.time()
     if dtype != twa.F32:
@@ -106,13 +126,23 @@ def main():
         del a, b
         torch.cuda.empty_cache()
     ring = [synth.gradient(D, wl.sigma_g, seed=args.seed, step=i, device=dev) for i in range(4)]
-    s = torch.empty(n, dtype=torch.float32, device=dev)
-    ws = twa.Workspace(twa.project_workspace_bytes(n), device=dev)
     lr = wl.lr
+    lam = 1e-4                                  # weight decay of the coefficient form (layer-wise mode)
+    if layerwise:
+        L = plan.L
+        beta = torch.zeros((L, n), dtype=torch.float32, device=dev)
+        ws = twa.Workspace(twa.project_layers_workspace_bytes(n, L), device=dev)
 
-    def step(i):
-        twa.project(pm, ring[i & 3], s, ws)
-        twa.expand_update(pm, s, w, lr)
+        def step(i):
+            twa.beta_step(pm, ring[i & 3], plan, beta, lr, lam, None, ws)
+            twa.weights_from_beta(pm, beta, plan, wbar, w)
+    else:
+        s = torch.empty(n, dtype=torch.float32, device=dev)
+        ws = twa.Workspace(twa.project_workspace_bytes(n), device=dev)
+
+        def step(i):
+            twa.project(pm, ring[i & 3], s, ws)
+            twa.expand_update(pm, s, w, lr)
 
     # ---- the timed region: exactly K steps --------------------------------------------------------
     for i in range(args.warmup):
@@ -145,13 +175,22 @@ def main():
         torch.cuda.synchronize()
         return sum(a.elapsed_time(b) for a, b in evs) / K2
 
-    ms_project = timed_each(lambda i: twa.project(pm, ring[i & 3], s, ws))
-    ms_expand = timed_each(lambda i: twa.expand_update(pm, s, w, lr))
-    alg = {
-        "twa_project": p_bytes + 4 * D + 4 * n,                 # P once + g + s
-        "twa_expand_update": p_bytes + 8 * D + 4 * n,           # P once + w read + w write + s
-    }
-    dur = {"twa_project": ms_project, "twa_expand_update": ms_expand}
+    if layerwise:
+        ms_project = timed_each(lambda i: twa.beta_step(pm, ring[i & 3], plan, beta, lr, lam, None, ws))
+        ms_expand = timed_each(lambda i: twa.weights_from_beta(pm, beta, plan, wbar, w))
+        alg = {
+            "twa_beta_step": p_bytes + 4 * D + 8 * n * L,           # P once + g + beta read and written
+            "twa_weights_from_beta": p_bytes + 8 * D + 4 * n * L,   # P once + wbar read + w written + beta
+        }
+        dur = {"twa_beta_step": ms_project, "twa_weights_from_beta": ms_expand}
+    else:
+        ms_project = timed_each(lambda i: twa.project(pm, ring[i & 3], s, ws))
+        ms_expand = timed_each(lambda i: twa.expand_update(pm, s, w, lr))
+        alg = {
+            "twa_project": p_bytes + 4 * D + 4 * n,                 # P once + g + s
+            "twa_expand_update": p_bytes + 8 * D + 4 * n,           # P once + w read + w write + s
+        }
+        dur = {"twa_project": ms_project, "twa_expand_update": ms_expand}
     dom = max(dur, key=dur.get)
     achieved = alg[dom] / (dur[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -168,12 +207,19 @@ def main():
 
         g_h = ring[0].cpu().numpy().astype(np.float64)
         w_h = w.cpu().numpy().astype(np.float64)
+        off_h = plan.layer_off.cpu().numpy() if layerwise else None
 
         def oracle_step(cols):
-            po = to_oracle(pm, cols=cols)
+            po = to_oracle(pm, cols=cols, layer_off=off_h)
             t = time.perf_counter()
-            so = orc.project(po, g_h)
-            orc.expand_update(po, so, w_h.copy(), lr)
+            if layerwise:
+                so = orc.project_layers(po, g_h, off_h)
+                bo = np.zeros_like(so)
+                orc.beta_step(bo, so, lr, lam)
+                orc.weights_from_beta(po, bo, off_h, w_h)
+            else:
+                so = orc.project(po, g_h)
+                orc.expand_update(po, so, w_h.copy(), lr)
             return time.perf_counter() - t
 
         t_one = oracle_step([0])
@@ -184,16 +230,18 @@ def main():
             reps += 1
         t_m = t_sum / reps
         cpu = {"value": round(1.0 / (t_m * n / m), 5), "unit": "steps/s", "cores": orc.threads(), "kind": "oracle",
-               "sample": f"{reps} full step(s) (project + expand_update, fp64, on-the-fly dequantisation) over the "
+               "sample": f"{reps} full step(s) ({'coefficient step + weights from coefficients, layer-wise' if layerwise else 'project + expand_update'}, fp64, on-the-fly dequantisation) over the "
                          f"first {m} of {n} basis vectors at full D={D}: {t_m:.2f} s per step-sample, scaled by {n}/{m}"}
 
     out = {
-        "metric": METRIC, "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "metric": METRIC if not layerwise else METRIC_LAYERWISE, "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: D={D}, n={n}, P stored as {args.storage}"
                                + (f" (block {pm.block}, {'fp32' if dtype == twa.I8 else 'fp16'} scales)"
-                                  if dtype in (twa.I8, twa.I4) else ""),
+                                  if dtype in (twa.I8, twa.I4) else "")
+                               + (f"; layer-wise, L={plan.L}, centre+normalise basis, coefficient form, lambda={lam}"
+                                  if layerwise else ""),
                    "lr": lr, "sigma_g": wl.sigma_g, "gradient_ring": 4, "seed": args.seed},
         "p_stream_GBps": round(p_stream_gbps, 1), "p_stream_pct_of_peak": round(100 * p_stream_gbps / HBM_PEAK_GBPS, 2),
         "p_bytes_per_pass": p_bytes, "roofline": roofline, "cpu_baseline": cpu,
