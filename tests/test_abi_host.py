@@ -107,6 +107,46 @@ def test_other_entry_points_argument_errors():
     assert L.twa_build_basis(0x6000, 1000, 4, 1024, 0x6000, 2048, None, 0x8000, wsb, None) == twa.ERR_SHAPE  # alias
 
 
+def test_layerwise_entry_points_argument_errors():
+    L = twa.lib()
+    nb = C.c_size_t()
+    assert L.twa_layer_plan_bytes(161, C.byref(nb)) == twa.OK and nb.value == 162 * 16
+    assert L.twa_layer_plan_bytes(0, C.byref(nb)) == twa.ERR_SHAPE
+    assert L.twa_layer_plan_bytes(twa.MAX_LAYERS + 1, C.byref(nb)) == twa.ERR_SHAPE
+    assert L.twa_layer_plan(None, 3, 1000, 0x9000, 1 << 20, None) == twa.ERR_NULL
+    assert L.twa_layer_plan(0x8000, 3, 1000, 0x9000, 8, None) == twa.ERR_WORKSPACE
+    assert L.twa_layer_plan(0x8004, 3, 1000, 0x9000, 1 << 20, None) == twa.ERR_ALIGN
+    assert L.twa_layer_plan(0x8000, 3, 0, 0x9000, 1 << 20, None) == twa.ERR_SHAPE
+    assert L.twa_project_layers_workspace_bytes(100, 161, C.byref(nb)) == twa.OK
+    assert nb.value == (2048 + 161) * 101 * 4            # partial sums per (workgroup + layer) slot, n + 1 numbers each
+    pm = _pm()
+    wsb = nb.value
+    assert L.twa_project_layers(C.byref(pm), 0x2000, None, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_NULL
+    assert L.twa_project_layers(C.byref(pm), 0x2000, 0x9000, 2, None, 0x4000, wsb, None) == twa.ERR_NULL
+    assert L.twa_project_layers(C.byref(pm), 0x2000, 0x9000, 0, 0x3000, 0x4000, wsb, None) == twa.ERR_SHAPE
+    assert L.twa_project_layers(C.byref(pm), 0x2000, 0x9004, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_ALIGN
+    assert L.twa_project_layers(C.byref(pm), 0x2000, 0x9000, 2, 0x3000, 0x4000, 64, None) == twa.ERR_WORKSPACE
+    assert L.twa_beta_step(C.byref(pm), 0x2000, 0x9000, 2, None, 0.1, 0.0, None, 0x4000, wsb, None) == twa.ERR_NULL
+    assert L.twa_expand_update_layers(C.byref(pm), None, 0x9000, 2, 0x3000, 0.1, None, None) == twa.ERR_NULL
+    assert L.twa_expand_update_layers(C.byref(pm), 0x2000, 0x9000, 2, 0x3004, 0.1, None, None) == twa.ERR_ALIGN
+    assert L.twa_weights_from_beta(C.byref(pm), 0x2000, 0x9000, 2, None, 0x3000, None) == twa.ERR_NULL
+    assert L.twa_beta_update(0x2000, 0x3000, -1, 0.1, 0.0, None) == twa.ERR_SHAPE
+    # the paper's min-max format: layer-wise calls only, factors required
+    mm = _pm(dtype=twa.U4MM, ld=2048, scales=0)
+    assert L.twa_project_layers(C.byref(mm), 0x2000, 0x9000, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_NULL
+    mm = _pm(dtype=twa.U4MM, ld=1024, scales=0x5000)
+    assert L.twa_project_layers(C.byref(mm), 0x2000, 0x9000, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_ALIGN
+    out = _pm(dtype=twa.I8, block=128, scales=0x5000, ld=2048)
+    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_DTYPE
+    out = _pm(dtype=twa.U8MM, scales=0x5000, ld=2048)
+    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, C.byref(out), 0x4000, 8, None) == twa.ERR_WORKSPACE
+    assert L.twa_quantize_minmax(0x6000, 1000, 5, 1024, 0x9000, 2, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
+    assert L.twa_centre_normalise(0x6000, 1000, 4, 1024, 0x9000, 2, None, 0x7000, 1024, None, 0x4000, 1 << 30,
+                                  None) == twa.ERR_NULL
+    assert L.twa_centre_normalise(0x6000, 1000, 4, 1000, 0x9000, 2, 0xa000, 0x7000, 1024, None, 0x4000, 1 << 30,
+                                  None) == twa.ERR_ALIGN
+
+
 def test_valid_call_without_a_gpu_fails_loudly():
     import torch
     if torch.cuda.is_available():
