@@ -481,46 +481,48 @@ struct BetaStep {
   }
 };
 
-// S[l][j] = sum of the partial slots (b + l) of the workgroups b that own tiles of layer l, in
-// workgroup order, accumulated in fp64.  One block per layer, one thread per basis vector.
-__global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_kernel(const float* __restrict__ partial, int n,
-                                                                         LayerPlan plan, int grid,
-                                                                         float* __restrict__ S, BetaStep bs) {
-  const int l = blockIdx.x;
-  const int j = threadIdx.x;
-  if (j >= n) return;
-  const int ntiles = plan.first[plan.L];
-  const int tiles_per_wg = ntiles > 0 ? (ntiles + grid - 1) / grid : 1;      // as in project_kernel
-  const int32_t ta = plan.first[l], tb = plan.first[l + 1];          // tiles [ta, tb)
-  double a = 0.0;
-  if (tb > ta) {
-    const int b0 = ta / tiles_per_wg, b1 = (tb - 1) / tiles_per_wg;
-    for (int b = b0; b <= b1; ++b) a += (double)partial[(int64_t)(b + l) * n + j];
-  }
-  bs.finish(S, (int64_t)l * n + j, (float)a);
-}
-
-// The min-max formats (Sec. 4.6): (P~^l)^T g^l = a_l * (C^l)^T g^l + (b_l + bias * a_l) * sum(g^l), where C holds
-// the decoded codes (code - bias).  Same summation order as above.
-__global__ __launch_bounds__(TWA_MAX_N) void project_layers_reduce_minmax_kernel(
+// S[l][j] = sum of the partial slots (b + l) of the workgroups b that own tiles of layer l, accumulated
+// in fp64 in a fixed order.  One block per layer; thread (q, j) adds the slots of every kRedWays-th
+// workgroup for basis vector j (a long layer spans ~50 workgroups: one thread per vector alone would
+// walk them one dependent load after the other), then the kRedWays sums are added in the order of q.
+// The min-max formats (Sec. 4.6) finish with (P~^l)^T g^l = a_l * (C^l)^T g^l + (b_l + bias * a_l) * sum(g^l),
+// where C holds the decoded codes (code - bias).
+constexpr int kRedWays = 8;
+template <bool MINMAX>
+__global__ __launch_bounds__(TWA_MAX_N* kRedWays) void project_layers_reduce_kernel(
     const float* __restrict__ partial, const float* __restrict__ partial_g, int n, LayerPlan plan, int grid,
     const float* __restrict__ ab, float bias, float* __restrict__ S, BetaStep bs) {
+  __shared__ double red[kRedWays][TWA_MAX_N];
+  __shared__ double redg[kRedWays];
   const int l = blockIdx.x;
-  const int j = threadIdx.x;
-  if (j >= n) return;
+  const int j = threadIdx.x % TWA_MAX_N;
+  const int q = threadIdx.x / TWA_MAX_N;
   const int ntiles = plan.first[plan.L];
   const int tiles_per_wg = ntiles > 0 ? (ntiles + grid - 1) / grid : 1;      // as in project_kernel
-  const int32_t ta = plan.first[l], tb = plan.first[l + 1];
+  const int32_t ta = plan.first[l], tb = plan.first[l + 1];                  // tiles [ta, tb)
   double a = 0.0, gs = 0.0;
-  if (tb > ta) {
+  if (tb > ta && j < n) {
     const int b0 = ta / tiles_per_wg, b1 = (tb - 1) / tiles_per_wg;
-    for (int b = b0; b <= b1; ++b) {
+    for (int b = b0 + q; b <= b1; b += kRedWays) {
       a += (double)partial[(int64_t)(b + l) * n + j];
-      gs += (double)partial_g[b + l];
+      if (MINMAX && j == 0) gs += (double)partial_g[b + l];
     }
   }
-  const double al = (double)ab[2 * l], bl = (double)ab[2 * l + 1];
-  bs.finish(S, (int64_t)l * n + j, (float)(al * a + (bl + (double)bias * al) * gs));
+  red[q][j] = a;
+  if (MINMAX && j == 0) redg[q] = gs;
+  __syncthreads();
+  if (q != 0 || j >= n) return;
+  double tot = 0.0, totg = 0.0;
+#pragma unroll
+  for (int r = 0; r < kRedWays; ++r) {
+    tot += red[r][j];
+    if (MINMAX) totg += redg[r];
+  }
+  if constexpr (MINMAX) {
+    const double al = (double)ab[2 * l], bl = (double)ab[2 * l + 1];
+    tot = al * tot + (bl + (double)bias * al) * totg;
+  }
+  bs.finish(S, (int64_t)l * n + j, (float)tot);
 }
 
 template <int DT, int VPL>
@@ -532,12 +534,9 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   float* partial_g = partial + ((size_t)kMaxGrid + (size_t)L) * P.n;        // min-max formats only
   int rc = launch_project_dt<DT, 1, VPL, true>(P, g, 0, 1, partial, max_grid, &grid, st, plan, partial_g);
   if (rc != TWA_OK) return rc;
-  if constexpr (kMinMax<DT>) {
-    hipLaunchKernelGGL(project_layers_reduce_minmax_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, partial_g, P.n,
-                       plan, grid, reinterpret_cast<const float*>(P.scales), kNibbles<DT> ? 8.0f : 128.0f, S, bs);
-  } else {
-    hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, S, bs);
-  }
+  hipLaunchKernelGGL(project_layers_reduce_kernel<kMinMax<DT>>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial,
+                     partial_g, P.n, plan, grid, reinterpret_cast<const float*>(P.scales), kNibbles<DT> ? 8.0f : 128.0f,
+                     S, bs);
   return hip_check(hipGetLastError());
 }
 
@@ -549,8 +548,8 @@ int launch_layer_squares(const PView& P, const void* plan_dev, int L, float* Q, 
   int grid = 0;
   int rc = launch_project_dt<TWA_F32, 1, 4, true, true>(P, nullptr, 0, 1, partial, max_grid, &grid, st, plan);
   if (rc != TWA_OK) return rc;
-  hipLaunchKernelGGL(project_layers_reduce_kernel, dim3(L), dim3(TWA_MAX_N), 0, st, partial, P.n, plan, grid, Q,
-                     BetaStep{nullptr, 0.0f, 0.0f});
+  hipLaunchKernelGGL(project_layers_reduce_kernel<false>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial, nullptr,
+                     P.n, plan, grid, nullptr, 0.0f, Q, BetaStep{nullptr, 0.0f, 0.0f});
   return hip_check(hipGetLastError());
 }
 
