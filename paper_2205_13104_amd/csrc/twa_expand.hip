@@ -45,6 +45,7 @@ struct Expander {
   uint32_t span_scale_bytes;
   rsrc_t rw, rgt;
   rsrc_t rw_in;                                         // where the old weights are read (normally = rw)
+  bool out_of_place;                                    // ... and whether that is another buffer
   float lr;
   float* tb;                                            // this wave's LDS transpose buffer
 
@@ -167,7 +168,8 @@ struct Expander {
     nw[2] = as_u32(__builtin_fmaf(-lr, gt.z, as_f32(wq[2])));
     nw[3] = as_u32(__builtin_fmaf(-lr, gt.w, as_f32(wq[3])));
     if (el >= lo && el + 4 <= hi) {
-      st128_through(rw, off, nw);
+      if (out_of_place) st128_through_nt(rw, off, nw);
+      else st128_through(rw, off, nw);
       st128(rgt, off, gv);          // empty descriptor when g~ is not wanted: dropped
     } else {
 #pragma unroll
@@ -242,6 +244,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
             make_rsrc(w, w_bytes),
             make_rsrc(g_tilde, g_tilde ? w_bytes : 0u),
             make_rsrc(w_in, w_bytes),
+            w_in != w,
             lr,
             tbuf[wave]};
 
