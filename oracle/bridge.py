@@ -2,7 +2,8 @@
 
 Test infrastructure (see twa_oracle.py).  The argument is duck-typed -- any object with the
 fields of the C descriptor (dtype code, D, block, gscale) whose `data` / `scales` are torch
-tensors -- so that nothing of the HIP path is imported here.  Only bytes are moved; no arithmetic.
+tensors -- so that nothing of the HIP path is imported here.  Only stored bytes are moved and re-encoded
+(scales permuted into the oracle's order, packed integer codes spread out); none of the method's arithmetic.
 """
 import numpy as np
 import torch

@@ -135,8 +135,9 @@ class Pmat:
     D: int
     n: int
     ld: int
-    data: torch.Tensor                      # (n, ld) values/codes; I4: (n, ld // 2) bytes
-    scales: Optional[torch.Tensor] = None   # (ld // 2048, n, 2048 // block): float32 (I8) / float16 (I4)
+    data: torch.Tensor                      # (n, ld) values/codes; I4, U4MM: (n, ld // 2) bytes
+    scales: Optional[torch.Tensor] = None   # (ld // 2048, n, 2048 // block): float32 (I8) / float16 (I4);
+                                            # U8MM, U4MM: (L, 2) float32 = (a_l, b_l) per layer
     block: int = 0
     gscale: float = 1.0
 

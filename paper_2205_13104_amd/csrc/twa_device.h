@@ -174,14 +174,8 @@ template <int DT> __device__ __forceinline__ float load_scale(rsrc_t r, uint32_t
   }
 }
 
-// Sum over the 64 lanes of a wave, same order on every call; result valid in every lane.
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, kWave);
-  return x;
-}
-// The same sum with data-parallel-primitive adds instead of cross-lane shuffles (no LDS traffic, a
-// few cycles per step): an inclusive scan inside each row of 16 lanes (row_shr 1, 2, 4, 8; lanes
+// Sum over the 64 lanes of a wave with data-parallel-primitive adds instead of cross-lane shuffles
+// (no LDS traffic, a few cycles per step): an inclusive scan inside each row of 16 lanes (row_shr 1, 2, 4, 8; lanes
 // without a source add 0), then row_bcast:15 hands each row total to the next row (rows 1 and 3)
 // and row_bcast:31 hands the total of the first half to the second.  LANE 63 ends with the sum of
 // all 64 lanes; the other lanes hold partial sums.  Fixed order: identical bits on every call.
@@ -198,6 +192,7 @@ __device__ __forceinline__ float wave_sum_to_last_lane(float x) {
 #undef TWA_DPP_ADD
   return x;
 }
+// Sum of a double over the 64 lanes, same order on every call; result valid in every lane.
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, kWave);
