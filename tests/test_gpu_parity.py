@@ -302,3 +302,46 @@ def test_projector_identities_on_gpu_basis():
         twa.expand_update(Pi, si, torch.zeros(D, device="cuda"), 1.0, gi)
         acc += gi
     assert rel_l2(acc.cpu().numpy(), gt.cpu().numpy()) <= 1e-5
+
+
+# ------------------------------------------------------------------------------------------------ HIP graph
+def test_step_captured_in_a_graph_replays_bit_for_bit():
+    """The step calls neither allocate nor synchronise, so a caller may capture them in a HIP graph.  Every
+    replay (with eager work and synchronisations of the program's own in between) must reproduce the eager
+    result bit for bit."""
+    D, n = 1_500_007, 100
+    pm = store_as(random_basis_like(D, n, seed=31), D, twa.I8)
+    gs = [synth.gradient(D, 1e-2, seed=31, step=i, device="cuda") for i in range(3)]
+    plan = twa.LayerPlan(synth.layer_offsets(synth.random_layer_sizes(D, 20, seed=3)), D)
+    s = torch.empty(n, device="cuda")
+    S = torch.empty((plan.L, n), device="cuda")
+    ws = twa.Workspace(max(twa.project_workspace_bytes(n), twa.project_layers_workspace_bytes(n, plan.L)))
+    w0 = synth.gradient(D, 0.05, seed=32, device="cuda")
+
+    def steps(w):
+        for g in gs:
+            twa.project(pm, g, s, ws)
+            twa.expand_update(pm, s, w, 0.1)
+            twa.project_layers(pm, g, plan, S, ws)
+            twa.expand_update_layers(pm, S, plan, w, 0.05)
+
+    w_eager = w0.clone()
+    steps(w_eager)
+    torch.cuda.synchronize()
+    w_graph = w0.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        steps(w_graph)                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        steps(w_graph)
+    for rep in range(4):
+        w_graph.copy_(w0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(w_graph, w_eager), rep
+        # eager work of the program's own between the replays
+        twa.project(pm, gs[rep % 3], s, ws)
+        torch.cuda.synchronize()
