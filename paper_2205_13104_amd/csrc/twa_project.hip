@@ -33,11 +33,9 @@ namespace twa {
 // SQUARES (with LAYERED, F32): no gradient; the sums are the squares of the stored elements of the
 // layer, sum_i P_ij^2 -- the squared norms that the layer-wise basis divides by (Sec. 4.5).
 template <int DT, int KB, int U, int NCH, int VPL, bool LAYERED, bool SQUARES = false>
-// (launch bounds: two workgroups per compute unit, i.e. at most 256 registers per lane)
-__global__ __launch_bounds__(256, 2) void project_kernel(PView P, const float* __restrict__ g, int64_t ldg,
-                                                      int kvalid, float* __restrict__ partial, int cpw,
-                                                      int tiles_per_wg, LayerPlan plan,
-                                                      float* __restrict__ partial_g) {
+__device__ __forceinline__ void project_body(PView P, const float* __restrict__ g, int64_t ldg, int kvalid,
+                                             float* __restrict__ partial, int cpw, int tiles_per_wg, LayerPlan plan,
+                                             float* __restrict__ partial_g) {
   using S = Store<DT>;
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
@@ -245,6 +243,35 @@ __global__ __launch_bounds__(256, 2) void project_kernel(PView P, const float* _
   }
 }
 
+// The kernels around the body differ in their register budget only, which decides how the compiler
+// schedules the loads (measured at D = 25.6 M over n = 10 .. 128 and all storage types):
+//   * whole model, many basis vectors per wave (5 or more chunks, n > 64): the compiler's default.  Told to
+//     fit two waves per SIMD it schedules the int4 variants for far fewer registers than it may use
+//     and they lose 40 %;
+//   * whole model, few basis vectors per wave: exactly two waves per SIMD.  By default several of these
+//     variants use the accumulation registers as well and run at ONE wave per SIMD (int8, n = 10: 0.129 ms
+//     instead of 0.078 ms);
+//   * layer-wise: two workgroups per compute unit (256 registers per lane), for the same reason.
+template <int DT, int KB, int U, int NCH, int VPL>
+__global__ __launch_bounds__(256) void project_kernel(PView P, const float* __restrict__ g, int64_t ldg, int kvalid,
+                                                      float* __restrict__ partial, int cpw, int tiles_per_wg) {
+  project_body<DT, KB, U, NCH, VPL, false, false>(P, g, ldg, kvalid, partial, cpw, tiles_per_wg,
+                                                  LayerPlan{nullptr, nullptr, 1}, nullptr);
+}
+template <int DT, int KB, int U, int NCH, int VPL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void project_kernel_two_waves(
+    PView P, const float* __restrict__ g, int64_t ldg, int kvalid, float* __restrict__ partial, int cpw,
+    int tiles_per_wg) {
+  project_body<DT, KB, U, NCH, VPL, false, false>(P, g, ldg, kvalid, partial, cpw, tiles_per_wg,
+                                                  LayerPlan{nullptr, nullptr, 1}, nullptr);
+}
+template <int DT, int U, int NCH, int VPL, bool SQUARES>
+__global__ __launch_bounds__(256, 2) void project_layers_kernel(PView P, const float* __restrict__ g,
+                                                                float* __restrict__ partial, int cpw, LayerPlan plan,
+                                                                float* __restrict__ partial_g) {
+  project_body<DT, 1, U, NCH, VPL, true, SQUARES>(P, g, 0, 1, partial, cpw, 0, plan, partial_g);
+}
+
 // S = P^T G for up to TWA_MAX_K gradients in ONE pass over P (n <= 32 basis vectors; not int4).
 // The gradients are 44 % of the bytes at k = 8, n = 20, so they must not be fetched once per wave:
 // the workgroup loads each tile of G once, coalesced, into a double-buffered LDS tile (the loads of
@@ -431,9 +458,18 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   if (LAYERED) grid = max_grid;      // the kernel divides the plan's tiles over the grid itself
   *grid_out = grid;
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
-#define TWA_LAUNCH(U_, NCH_)                                                                         \
-  hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL, LAYERED, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
-                     kvalid, partial, cpw, tiles_per_wg, plan, partial_g)
+#define TWA_LAUNCH(U_, NCH_)                                                                                  \
+  do {                                                                                                        \
+    if constexpr (LAYERED)                                                                                    \
+      hipLaunchKernelGGL((project_layers_kernel<DT, U_, NCH_, VPL, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, \
+                         partial, cpw, plan, partial_g);                                                      \
+    else if constexpr (NCH_ <= 4)                                                                             \
+      hipLaunchKernelGGL((project_kernel_two_waves<DT, KB, U_, NCH_, VPL>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
+                         kvalid, partial, cpw, tiles_per_wg);                                                 \
+    else                                                                                                      \
+      hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL>), dim3(grid), dim3(256), 0, st, P, g, ldg, kvalid, \
+                         partial, cpw, tiles_per_wg);                                                         \
+  } while (0)
   {
     if (cpw == 25) {
       TWA_LAUNCH(5, 5);
