@@ -345,3 +345,32 @@ def test_step_captured_in_a_graph_replays_bit_for_bit():
         # eager work of the program's own between the replays
         twa.project(pm, gs[rep % 3], s, ws)
         torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------------ many rounds per wave
+@pytest.mark.parametrize("dtype", [twa.F32, twa.I8, twa.I4], ids=["f32", "i8", "i4"])
+def test_expand_with_more_rounds_than_a_wave_can_hold(dtype):
+    """A vector so long that a wave owns more tiles than it keeps on chip: the early tiles are written as they
+    finish, the last ones in the final burst -- same results as the oracle, whole-model and layer-wise."""
+    D, n = 33_000_001, 4
+    pm = store_as(random_basis_like(D, n, seed=41), D, dtype)
+    po = to_oracle(pm)
+    s = torch.tensor([0.7, -1.3, 0.2, 2.1], device="cuda")
+    w0 = synth.gradient(D, 0.05, seed=42, device="cuda")
+    w = w0.clone()
+    gt = torch.empty(D, device="cuda")
+    twa.expand_update(pm, s, w, 0.1, gt)
+    torch.cuda.synchronize()
+    wo = w0.cpu().numpy().astype(np.float64)
+    gto = orc.expand_update(po, s.cpu().numpy().astype(np.float64), wo, float(np.float32(0.1)), want_gt=True)
+    assert rel_l2(gt.cpu().numpy(), gto) <= REL_L2_TOL and rel_l2(w.cpu().numpy(), wo) <= REL_L2_TOL
+    off = synth.layer_offsets(synth.random_layer_sizes(D, 25, seed=6))
+    plan = twa.LayerPlan(off, D)
+    S = torch.randn((plan.L, n), generator=torch.Generator().manual_seed(3)).cuda()
+    w = w0.clone()
+    twa.expand_update_layers(pm, S, plan, w, 0.1, gt)
+    torch.cuda.synchronize()
+    wo = w0.cpu().numpy().astype(np.float64)
+    gto = orc.expand_update_layers(po, S.cpu().numpy().astype(np.float64), off.numpy(), wo, float(np.float32(0.1)),
+                                   want_gt=True)
+    assert rel_l2(gt.cpu().numpy(), gto) <= REL_L2_TOL and rel_l2(w.cpu().numpy(), wo) <= REL_L2_TOL
