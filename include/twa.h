@@ -241,6 +241,10 @@ int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan
  * evaluated in fp64 with ties to even (the paper names no tie rule); a_l = 0 (a constant layer)
  * gives c = 0; the factors are stored rounded to binary32 (b_l exactly).  The stored value is
  * within a_l/2 of p.
+ *   bits [in]     B: 1..4 with out->dtype TWA_U4MM, 1..8 with TWA_U8MM.  The paper studies B in
+ *                 {1, 2, 3, 4, 8, 16}: codes of fewer bits than the container holds are stored in the
+ *                 container (same values and factors as B-bit storage would give, without the extra
+ *                 saving of memory); B = 16 is not provided.
  *   out  [in/out] dtype TWA_U8MM or TWA_U4MM; data and scales (2L floats) allocated by the caller
  *                 (twa_pmat_bytes gives ld and the data size; it reports 0 scale bytes for these
  *                 types since it does not know L).
@@ -248,7 +252,7 @@ int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan
  */
 int twa_quantize_minmax_workspace_bytes(int32_t L, size_t* bytes);
 int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const void* plan, int32_t L,
-                        twa_pmat* out, void* ws, size_t ws_bytes, void* stream);
+                        int32_t bits, twa_pmat* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * The paper's default basis and the coefficient form of the step (Sec. 4.1, extraction of base

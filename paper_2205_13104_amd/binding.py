@@ -67,7 +67,7 @@ def lib():
         L.twa_layer_plan_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
         L.twa_layer_plan.argtypes = [vp, i32, i64, vp, C.c_size_t, vp]
         L.twa_quantize_minmax_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
-        L.twa_quantize_minmax.argtypes = [vp, i64, i32, i64, vp, i32, C.POINTER(_Pmat), vp, C.c_size_t, vp]
+        L.twa_quantize_minmax.argtypes = [vp, i64, i32, i64, vp, i32, i32, C.POINTER(_Pmat), vp, C.c_size_t, vp]
         L.twa_quantize_minmax_workspace_bytes.restype = C.c_int
         L.twa_quantize_minmax.restype = C.c_int
         L.twa_centre_normalise_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(C.c_size_t)]
@@ -298,9 +298,11 @@ def expand_update_layers(P: Pmat, S: torch.Tensor, plan: LayerPlan, w: torch.Ten
 
 
 def quantize_minmax(P: torch.Tensor, D: int, plan: LayerPlan, bits: int = 4) -> Pmat:
-    """twa_quantize_minmax: the paper's per-layer min-max format (Sec. 4.6), B = 4 or 8 bits."""
+    """twa_quantize_minmax: the paper's per-layer min-max format (Sec. 4.6), B = 1..8 bits (codes of up to 4
+    bits travel in nibbles, wider ones in bytes)."""
     assert P.dtype == torch.float32 and P.dim() == 2 and P.is_contiguous() and plan.D == D
-    dtype = {4: U4MM, 8: U8MM}[bits]
+    assert 1 <= bits <= 8
+    dtype = U4MM if bits <= 4 else U8MM
     n, ldp = P.shape
     ld, _, _ = pmat_bytes(dtype, D, n)
     cols = ld // 2 if dtype == U4MM else ld
@@ -311,8 +313,8 @@ def quantize_minmax(P: torch.Tensor, D: int, plan: LayerPlan, bits: int = 4) -> 
     _check(lib().twa_quantize_minmax_workspace_bytes(plan.L, C.byref(nb)), "twa_quantize_minmax_workspace_bytes")
     ws = Workspace(int(nb.value) + 8, device=P.device)
     st = out.c_struct()
-    _check(lib().twa_quantize_minmax(_ptr(P), D, n, ldp, plan.ptr, plan.L, C.byref(st), ws.ptr, ws.nbytes, _stream()),
-           "twa_quantize_minmax")
+    _check(lib().twa_quantize_minmax(_ptr(P), D, n, ldp, plan.ptr, plan.L, bits, C.byref(st), ws.ptr, ws.nbytes,
+                                     _stream()), "twa_quantize_minmax")
     return out
 
 

@@ -361,10 +361,11 @@ int twa_quantize_minmax_workspace_bytes(int32_t L, size_t* bytes) {
   return TWA_OK;
 }
 
-int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const void* plan, int32_t L, twa_pmat* out,
-                        void* ws, size_t ws_bytes, void* stream) {
+int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const void* plan, int32_t L, int32_t bits,
+                        twa_pmat* out, void* ws, size_t ws_bytes, void* stream) {
   if (!P || !out || !out->data || !out->scales) return TWA_ERR_NULL;
   if (!minmax(out->dtype)) return TWA_ERR_DTYPE;
+  if (bits < 1 || bits > bits_of(out->dtype)) return TWA_ERR_SHAPE;
   if (out->D != D || out->n != n) return TWA_ERR_SHAPE;
   int rc = check_dims(D, n, ldp, TWA_F32);
   if (rc != TWA_OK) return rc;
@@ -376,7 +377,7 @@ int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const
   if (!ws || ws_bytes < minmax_workspace_bytes(L)) return TWA_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 7u) return TWA_ERR_ALIGN;
   if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
-  return launch_quantize_minmax(P, D, n, ldp, plan, L, out->dtype, static_cast<uint8_t*>(out->data), out->ld,
+  return launch_quantize_minmax(P, D, n, ldp, plan, L, out->dtype, bits, static_cast<uint8_t*>(out->data), out->ld,
                                 static_cast<float*>(out->scales), ws, static_cast<hipStream_t>(stream));
 }
 

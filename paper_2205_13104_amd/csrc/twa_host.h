@@ -47,7 +47,7 @@ int launch_centre_normalise(const float* W, int64_t D, int n, int64_t ldw, const
                             float* E, int64_t lde, float* norms, void* ws, int max_grid, hipStream_t st);
 size_t minmax_workspace_bytes(int L);
 int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const void* plan_dev, int L, int dtype,
-                           uint8_t* codes, int64_t ld, float* ab, void* ws, hipStream_t st);
+                           int bits, uint8_t* codes, int64_t ld, float* ab, void* ws, hipStream_t st);
 int launch_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, hipStream_t st);
 int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pmat& out, hipStream_t st);
 int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st);

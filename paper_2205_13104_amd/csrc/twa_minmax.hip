@@ -147,11 +147,11 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
 size_t minmax_workspace_bytes(int L) { return (size_t)L * (2 * sizeof(uint32_t) + sizeof(double)); }
 
 int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const void* plan_dev, int L, int dtype,
-                           uint8_t* codes, int64_t ld, float* ab, void* ws, hipStream_t st) {
+                           int bits, uint8_t* codes, int64_t ld, float* ab, void* ws, hipStream_t st) {
   double* a64 = static_cast<double*>(ws);                         // 8-byte aligned first
   uint32_t* keys = reinterpret_cast<uint32_t*>(a64 + L);
   const LayerPlan plan = plan_view(plan_dev, L, 2048);
-  const double levels = dtype == TWA_U8MM ? 255.0 : 15.0;
+  const double levels = (double)((1 << bits) - 1);              // codes 0 .. 2^B - 1, whatever the container
   const int lgrid = (L + 255) / 256;
   hipLaunchKernelGGL(minmax_init_kernel, dim3(lgrid), dim3(256), 0, st, keys, L);
   const int cus = device_cus();

@@ -137,10 +137,13 @@ def test_layerwise_entry_points_argument_errors():
     mm = _pm(dtype=twa.U4MM, ld=1024, scales=0x5000)
     assert L.twa_project_layers(C.byref(mm), 0x2000, 0x9000, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_ALIGN
     out = _pm(dtype=twa.I8, block=128, scales=0x5000, ld=2048)
-    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_DTYPE
+    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 8, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_DTYPE
     out = _pm(dtype=twa.U8MM, scales=0x5000, ld=2048)
-    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, C.byref(out), 0x4000, 8, None) == twa.ERR_WORKSPACE
-    assert L.twa_quantize_minmax(0x6000, 1000, 5, 1024, 0x9000, 2, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
+    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 8, C.byref(out), 0x4000, 8, None) == twa.ERR_WORKSPACE
+    assert L.twa_quantize_minmax(0x6000, 1000, 5, 1024, 0x9000, 2, 8, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
+    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 9, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
+    out = _pm(dtype=twa.U4MM, scales=0x5000, ld=2048)
+    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 5, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
     assert L.twa_centre_normalise(0x6000, 1000, 4, 1024, 0x9000, 2, None, 0x7000, 1024, None, 0x4000, 1 << 30,
                                   None) == twa.ERR_NULL
     assert L.twa_centre_normalise(0x6000, 1000, 4, 1000, 0x9000, 2, 0xa000, 0x7000, 1024, None, 0x4000, 1 << 30,
