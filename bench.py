@@ -68,7 +68,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a single-GPU library (no collectives, no sharding); run with --gpus 1. "
-                 "How the path would shard over GPUs is described in DESIGN.md.")
+                 "How the path would shard over GPUs is described in the repository's design notes.")
 
     import numpy as np
     import torch

@@ -35,11 +35,11 @@ struct Expander {
   static constexpr int ROW = EPV + 4;                   // padded LDS row of one lane (conflict free)
   static constexpr int SPANS = TILE > kScaleSpan ? TILE / kScaleSpan : 1;
   static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
+  static_assert(kLayerAlign % kScaleSpan == 0, "per-layer tiles keep the alignment of the scale spans");
 
   const PView& P;
   int lane;
   uint32_t col_bytes;
-  uint32_t total_spans;
   int64_t ld_bytes;
   int gshift;
   uint32_t span_scale_bytes;
@@ -65,13 +65,8 @@ struct Expander {
       for (int e = 0; e < EPV; ++e) acc[v][e] = 0.0f;
     }
     rsrc_t rs = rw;
-    if constexpr (S::kScaled) {
-      // a layer-wise tile need not start on a span boundary: one more span, but never past the array
-      const uint32_t span0 = (uint32_t)(e0 >> kScaleSpanShift);
-      uint32_t spans = SPANS + (LAYERED ? 1 : 0);
-      if constexpr (LAYERED) spans = span0 + spans <= total_spans ? spans : total_spans - span0;
-      rs = make_rsrc(P.scales + (int64_t)span0 * span_scale_bytes, spans * span_scale_bytes);
-    }
+    if constexpr (S::kScaled)      // (per-layer tiles start on the same grid as the scale spans)
+      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, SPANS * span_scale_bytes);
     const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);   // tile offset inside its first span
 
     for (int j0 = 0; j0 < n; j0 += U) {
@@ -237,7 +232,6 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   const X x{P,
             lane,
             (uint32_t)((((D * X::S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3),
-            (uint32_t)(P.ld >> kScaleSpanShift),
             (P.ld * X::S::kBitsPerElem) >> 3,
             kScaleSpanShift - P.block_shift,
             X::S::kScaled ? ((uint32_t)P.n << (kScaleSpanShift - P.block_shift)) * (uint32_t)X::S::kScaleBytes : 0u,

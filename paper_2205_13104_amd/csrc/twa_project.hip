@@ -63,7 +63,6 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
   const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
   const int gshift = kScaleSpanShift - P.block_shift;            // log2(scales per span and vector)
   const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes : 0u;
-  const uint32_t total_spans = (uint32_t)(P.ld >> kScaleSpanShift);
 
   float acc[SLOTS][KB];
 #pragma unroll
@@ -161,14 +160,11 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
 
     // ---- stream this wave's basis vectors over the tile ----------------------------------
     rsrc_t rs = make_rsrc(g, 0u);
-    // scale spans one tile touches (a layer-wise tile need not start on a span boundary)
-    constexpr int SPANS = (TILE > kScaleSpan ? TILE / kScaleSpan : 1) + (LAYERED ? 1 : 0);
-    if constexpr (S::kScaled) {
-      const uint32_t span0 = (uint32_t)(e0 >> kScaleSpanShift);
-      uint32_t spans = SPANS;
-      if constexpr (LAYERED) spans = span0 + spans <= total_spans ? spans : total_spans - span0;   // stay inside the array
-      rs = make_rsrc(P.scales + (int64_t)span0 * span_scale_bytes, spans * span_scale_bytes);
-    }
+    // scale spans one tile touches (per-layer tiles start on the same grid: kLayerAlign is a multiple of the span)
+    constexpr int SPANS = TILE > kScaleSpan ? TILE / kScaleSpan : 1;
+    static_assert(kLayerAlign % kScaleSpan == 0, "per-layer tiles keep the alignment of the scale spans");
+    if constexpr (S::kScaled)
+      rs = make_rsrc(P.scales + (e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, SPANS * span_scale_bytes);
     const uint32_t in_span = (uint32_t)e0 & (uint32_t)(kScaleSpan - 1);   // tile offset inside its first span
     // chunk ch = column slots [ch*U, (ch+1)*U): fetch (128-bit codes/values + block scales) ...
     auto load_chunk = [&](int ch, u32x4 (&raw)[U][VPL], float (&sc)[U][VPL]) {
