@@ -243,7 +243,7 @@ int twa_expand_update(const twa_pmat* P, const float* s, float* w, float lr, flo
   if (!aligned16(w) || (g_tilde && !aligned16(g_tilde)) || (reinterpret_cast<uintptr_t>(s) & 3u))
     return TWA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int grid = persistent_grid("TWA_EXPAND_GRID", 7);
+  const int grid = persistent_grid("TWA_EXPAND_GRID", 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   return launch_expand_update(v, P->dtype, s, w, lr, g_tilde, grid, st);
 }
@@ -323,8 +323,7 @@ int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan
   if (rc != TWA_OK) return rc;
   if (!aligned16(w) || (g_tilde && !aligned16(g_tilde)) || (reinterpret_cast<uintptr_t>(S) & 3u))
     return TWA_ERR_ALIGN;
-  // the per-layer tiling adds up to one tile per layer: let the grid grow to two workgroups per compute unit
-  const int grid = persistent_grid("TWA_EXPAND_LAYERS_GRID", 8);
+  const int grid = persistent_grid("TWA_EXPAND_GRID", 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   return launch_expand_update_layers(v, P->dtype, S, plan, L, w, w, lr, g_tilde, grid,
                                      static_cast<hipStream_t>(stream));
@@ -339,7 +338,7 @@ int twa_weights_from_beta(const twa_pmat* P, const float* beta, const void* plan
   rc = check_plan(plan, L);
   if (rc != TWA_OK) return rc;
   if (!aligned16(w) || !aligned16(wbar) || (reinterpret_cast<uintptr_t>(beta) & 3u)) return TWA_ERR_ALIGN;
-  const int grid = persistent_grid("TWA_EXPAND_LAYERS_GRID", 8);
+  const int grid = persistent_grid("TWA_EXPAND_GRID", 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   // w = wbar - (-1) * (P beta): the expansion kernel with the mean as the weights it reads
   return launch_expand_update_layers(v, P->dtype, beta, plan, L, wbar, w, -1.0f, nullptr, grid,
