@@ -45,16 +45,10 @@ __device__ __forceinline__ uint32_t ld16(rsrc_t r, uint32_t voff) {
 __device__ __forceinline__ void st128(rsrc_t r, uint32_t voff, u32x4 v) {
   __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, 0, 0);
 }
-// Store that is written through to memory (sc0 sc1) instead of lingering dirty in L2: the burst of
-// w written at the end of the expand kernel then does not trickle out during the next kernel's
-// reads (measured: 0.6 % of the step).
-__device__ __forceinline__ void st128_through(rsrc_t r, uint32_t voff, u32x4 v) {
-  __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, 0, /*sc0*/ 1 | /*sc1*/ 16);
-}
-// The same, marked non-temporal as well: for a burst that goes to OTHER memory than what the kernel
-// read (w = wbar + P beta into its own buffer).  Without the hint the freshly allocated lines slowed
-// the NEXT kernel down (the following projection took 0.47 ms instead of 0.41 ms); for the
-// in-place update the hint costs 0.5 %, so each case keeps its own policy.
+// Store of the burst of w at the end of the expand kernel: written through to memory (sc0 sc1) instead
+// of lingering dirty in L2, and marked non-temporal.  Measured with the step (projection + expansion)
+// repeated at D = 25.6 M .. 350 M: lines left behind by plain or merely written-through stores slow the
+// NEXT kernel down, by 1.5 % of the step at D = 25.6 M and by 10 % at D = 100 M.
 __device__ __forceinline__ void st128_through_nt(rsrc_t r, uint32_t voff, u32x4 v) {
   __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, 0, /*sc0*/ 1 | /*nt*/ 2 | /*sc1*/ 16);
 }

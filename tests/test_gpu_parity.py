@@ -347,12 +347,14 @@ def test_step_captured_in_a_graph_replays_bit_for_bit():
         torch.cuda.synchronize()
 
 
-# ------------------------------------------------------------------------------------------------ many rounds per wave
-@pytest.mark.parametrize("dtype", [twa.F32, twa.I8, twa.I4], ids=["f32", "i8", "i4"])
-def test_expand_with_more_rounds_than_a_wave_can_hold(dtype):
-    """A vector so long that a wave owns more tiles than it keeps on chip: the early tiles are written as they
-    finish, the last ones in the final burst -- same results as the oracle, whole-model and layer-wise."""
-    D, n = 33_000_001, 4
+# ------------------------------------------------------------------------------------------------ several launches
+@pytest.mark.parametrize("D", [33_000_001, 61_000_001], ids=["two", "three"])
+@pytest.mark.parametrize("dtype", [twa.F32, twa.BF16, twa.I8, twa.I4], ids=["f32", "bf16", "i8", "i4"])
+def test_expand_in_several_launches(dtype, D):
+    """A vector so long that a wave cannot keep the sums of all its tiles on chip is expanded by several
+    launches, one run of tiles each (runs that do not divide evenly; two and three launches) -- same results
+    as the oracle, whole-model and layer-wise, in place and into another buffer."""
+    n = 4
     pm = store_as(random_basis_like(D, n, seed=41), D, dtype)
     po = to_oracle(pm)
     s = torch.tensor([0.7, -1.3, 0.2, 2.1], device="cuda")
@@ -374,3 +376,9 @@ def test_expand_with_more_rounds_than_a_wave_can_hold(dtype):
     gto = orc.expand_update_layers(po, S.cpu().numpy().astype(np.float64), off.numpy(), wo, float(np.float32(0.1)),
                                    want_gt=True)
     assert rel_l2(gt.cpu().numpy(), gto) <= REL_L2_TOL and rel_l2(w.cpu().numpy(), wo) <= REL_L2_TOL
+    # into another buffer: w = wbar + P beta (the coefficient form), the old weights left untouched
+    wbar = w0.clone()
+    w2 = twa.weights_from_beta(pm, S, plan, wbar)
+    torch.cuda.synchronize()
+    w2o = orc.weights_from_beta(po, S.cpu().numpy().astype(np.float64), off.numpy(), w0.cpu().numpy().astype(np.float64))
+    assert rel_l2(w2.cpu().numpy(), w2o) <= REL_L2_TOL and torch.equal(wbar, w0)
