@@ -384,6 +384,39 @@ int twa_oracle_beta_step(double* beta, const double* s, int64_t count, double et
   return ORC_OK;
 }
 
+/* The coefficient step with the base optimiser in place of plain gradient descent (Sec. 5.1: the base
+ * optimiser of the run is applied to the coefficients; the paper's runs use SGD with momentum, Adam and
+ * AdamW).  The optimisers are the published ones, written out on the count = L*n coefficients:
+ *   kind 0, heavy-ball momentum:   d = s + lambda beta;  m <- mu m + d;  beta <- beta - eta m
+ *                                  (mu = 0 is Alg. 1's own step)
+ *   kind 1, Adam, decay as an L2 term:   d = s + lambda beta
+ *   kind 2, AdamW, decoupled decay:      beta <- (1 - eta lambda) beta first;  d = s
+ *     then for both:  m <- b1 m + (1 - b1) d;  v <- b2 v + (1 - b2) d^2;
+ *                     beta <- beta - eta (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps),   t = 1, 2, ...
+ * m (and v) are the caller's state, zero before the first step. */
+int twa_oracle_beta_optim(int32_t kind, double* beta, const double* s, double* m, double* v, int64_t count,
+                          double eta, double lambda, double mu_or_b1, double b2, double eps, int32_t t) {
+  if (!beta || !s || !m || count < 0 || kind < 0 || kind > 2) return ORC_ERR_ARG;
+  if (kind != 0 && (!v || t < 1)) return ORC_ERR_ARG;
+  for (int64_t q = 0; q < count; ++q) {
+    if (kind == 0) {
+      const double d = s[q] + lambda * beta[q];
+      m[q] = mu_or_b1 * m[q] + d;
+      beta[q] -= eta * m[q];
+    } else {
+      double d = s[q];
+      if (kind == 1) d += lambda * beta[q];
+      else beta[q] *= 1.0 - eta * lambda;
+      m[q] = mu_or_b1 * m[q] + (1.0 - mu_or_b1) * d;
+      v[q] = b2 * v[q] + (1.0 - b2) * d * d;
+      const double mhat = m[q] / (1.0 - pow(mu_or_b1, (double)t));
+      const double vhat = v[q] / (1.0 - pow(b2, (double)t));
+      beta[q] -= eta * mhat / (sqrt(vhat) + eps);
+    }
+  }
+  return ORC_OK;
+}
+
 /* Alg. 1, "update weights":  w^l = wbar^l + P^l beta^l */
 int twa_oracle_weights_from_beta(const orc_pmat* P, const double* beta, const int64_t* off, int32_t L,
                                  const double* wbar, double* w) {

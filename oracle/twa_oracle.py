@@ -81,6 +81,8 @@ def lib():
         L.twa_oracle_expand_update_layers.argtypes = [P, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                                       C.c_double, C.c_void_p]
         L.twa_oracle_beta_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_double]
+        L.twa_oracle_beta_optim.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                            C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int32]
         L.twa_oracle_weights_from_beta.argtypes = [P, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.twa_oracle_centre_normalise_layers.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int64,
                                                          C.c_void_p, C.c_int32, C.c_void_p, C.c_int64,
@@ -262,6 +264,21 @@ def beta_step(beta: np.ndarray, s: np.ndarray, eta: float, lam: float) -> None:
     s = np.ascontiguousarray(s, dtype=np.float64)
     assert beta.dtype == np.float64 and beta.flags.c_contiguous and beta.shape == s.shape
     _check(lib().twa_oracle_beta_step(_ptr(beta), _ptr(s), beta.size, float(eta), float(lam)), "beta_step")
+
+
+MOMENTUM, ADAM, ADAMW = 0, 1, 2
+
+
+def beta_optim(kind: int, beta: np.ndarray, s: np.ndarray, m: np.ndarray, v, eta: float, lam: float,
+               mu_or_b1: float, b2: float = 0.0, eps: float = 0.0, t: int = 1) -> None:
+    """One coefficient step with the base optimiser (Sec. 5.1) in place: heavy-ball momentum, Adam (decay as an
+    L2 term) or AdamW (decoupled decay) on beta, state m (and v) updated in place.  t counts from 1."""
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    for a in (beta, m) + (() if v is None else (v,)):
+        assert a.dtype == np.float64 and a.flags.c_contiguous and a.shape == s.shape
+    _check(lib().twa_oracle_beta_optim(int(kind), _ptr(beta), _ptr(s), _ptr(m), None if v is None else _ptr(v),
+                                       beta.size, float(eta), float(lam), float(mu_or_b1), float(b2), float(eps),
+                                       int(t)), "beta_optim")
 
 
 def weights_from_beta(P: Pmat, beta: np.ndarray, layer_off, wbar: np.ndarray) -> np.ndarray:

@@ -191,3 +191,82 @@ def test_centre_normalise_one_layer_is_the_whole_model_construction():
     E1, wbar1 = orc.centre_normalise(W)
     E2, wbar2, _ = orc.centre_normalise_layers(W, [0, 900])
     assert np.array_equal(E1, E2) and np.array_equal(wbar1, wbar2)
+
+
+# ---------------------------------------------------------------- base optimiser on the coefficients (Sec. 5.1)
+def test_momentum_without_momentum_is_algorithm_1():
+    r = rng(40)
+    s = r.normal(size=(3, 5))
+    b1, b2, m = r.normal(size=(3, 5)), None, np.zeros((3, 5))
+    b2 = b1.copy()
+    for _ in range(4):
+        orc.beta_step(b1, s, 0.1, 0.3)
+        orc.beta_optim(orc.MOMENTUM, b2, s, m, None, 0.1, 0.3, 0.0)
+        assert np.allclose(b1, b2, rtol=0, atol=1e-15)
+
+
+def test_momentum_closed_form_under_a_constant_gradient():
+    r = rng(41)
+    s = r.normal(size=(2, 4))
+    eta, mu, T = 0.05, 0.9, 9
+    beta, m = np.zeros_like(s), np.zeros_like(s)
+    for _ in range(T):
+        orc.beta_optim(orc.MOMENTUM, beta, s, m, None, eta, 0.0, mu)
+    # m_k = s (1 - mu^k) / (1 - mu);  beta_T = -eta sum_k m_k
+    tot = sum((1 - mu ** k) / (1 - mu) for k in range(1, T + 1))
+    assert np.allclose(beta, -eta * tot * s, rtol=1e-13, atol=0)
+    assert np.allclose(m, s * (1 - mu ** T) / (1 - mu), rtol=1e-13, atol=0)
+    # one hand-computed step with decay: d = 3 + 0.5*2 = 4; m = 0.5*1 + 4 = 4.5; beta = 2 - 0.25*4.5
+    one, mm = np.array([[2.0]]), np.array([[1.0]])
+    orc.beta_optim(orc.MOMENTUM, one, np.array([[3.0]]), mm, None, 0.25, 0.5, 0.5)
+    assert mm[0, 0] == 4.5 and one[0, 0] == 0.875
+
+
+@pytest.mark.parametrize("kind", ["adam", "adamw"])
+def test_adam_closed_forms(kind):
+    r = rng(42)
+    s = r.normal(size=(2, 5))
+    eta, b1, b2, eps, T = 0.01, 0.9, 0.999, 1e-8, 7
+    K = orc.ADAM if kind == "adam" else orc.ADAMW
+    # constant gradient, no decay: the bias corrections make m^ = s and v^ = s^2 at every step,
+    # so every step moves by eta * s / (|s| + eps)
+    beta, m, v = np.zeros_like(s), np.zeros_like(s), np.zeros_like(s)
+    for t in range(1, T + 1):
+        orc.beta_optim(K, beta, s, m, v, eta, 0.0, b1, b2, eps, t)
+        assert np.allclose(beta, -t * eta * s / (np.abs(s) + eps), rtol=1e-12, atol=0)
+    # b1 = b2 = 0: no memory, a normalised step on the current gradient alone
+    beta, m, v = np.ones_like(s), np.zeros_like(s), np.zeros_like(s)
+    s2 = r.normal(size=s.shape)
+    orc.beta_optim(K, beta, s, m, v, eta, 0.0, 0.0, 0.0, eps, 1)
+    orc.beta_optim(K, beta, s2, m, v, eta, 0.0, 0.0, 0.0, eps, 2)
+    assert np.allclose(beta, 1 - eta * s / (np.abs(s) + eps) - eta * s2 / (np.abs(s2) + eps), rtol=1e-13, atol=0)
+    # where the two differ: the decay.  AdamW shrinks beta by (1 - eta*lam) and leaves the gradient alone:
+    # constant gradient => beta_t = q beta_{t-1} - c, a geometric series.  Adam adds lam*beta to the gradient.
+    lam = 0.5
+    beta, m, v = np.full_like(s, 2.0), np.zeros_like(s), np.zeros_like(s)
+    for t in range(1, T + 1):
+        orc.beta_optim(K, beta, s, m, v, eta, lam, b1, b2, eps, t)
+    if kind == "adamw":
+        q, c = 1 - eta * lam, eta * s / (np.abs(s) + eps)
+        assert np.allclose(beta, q ** T * 2.0 - c * (1 - q ** T) / (1 - q), rtol=1e-12, atol=0)
+    else:
+        # first step by hand: d = s + lam*2, step = eta * d / (|d| + eps)
+        beta1, m1, v1 = np.full_like(s, 2.0), np.zeros_like(s), np.zeros_like(s)
+        orc.beta_optim(K, beta1, s, m1, v1, eta, lam, b1, b2, eps, 1)
+        d = s + lam * 2.0
+        assert np.allclose(beta1, 2.0 - eta * d / (np.abs(d) + eps), rtol=1e-13, atol=0)
+        assert np.allclose(m1, (1 - b1) * d, rtol=1e-13, atol=0) and np.allclose(v1, (1 - b2) * d * d, rtol=1e-13, atol=0)
+
+
+def test_adam_is_invariant_to_the_scale_of_the_gradient():
+    """Adam's step depends on the gradient's direction per coordinate, not its scale (eps = 0):
+    a property a wrong power or a missing square root would break."""
+    r = rng(43)
+    G = r.normal(size=(6, 3, 4))
+    out = []
+    for scale in (1.0, 1000.0):
+        beta, m, v = np.zeros((3, 4)), np.zeros((3, 4)), np.zeros((3, 4))
+        for t in range(1, 7):
+            orc.beta_optim(orc.ADAM, beta, scale * G[t - 1], m, v, 0.01, 0.0, 0.9, 0.99, 0.0, t)
+        out.append(beta)
+    assert np.allclose(out[0], out[1], rtol=1e-12, atol=0)
