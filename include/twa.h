@@ -288,6 +288,35 @@ int twa_centre_normalise(const float* W, int64_t D, int32_t n, int64_t ldw, cons
 int twa_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, void* stream);
 
 /*
+ * The coefficient step with the run's base optimiser in place of plain gradient descent (Sec. 5.1: the
+ * base optimiser is applied to the coefficients; the paper's runs use SGD with momentum, Adam and AdamW).
+ * On the `count` = L*n coefficients, with s from twa_project_layers:
+ *   TWA_OPT_MOMENTUM  d = s + lambda*beta;  m <- mu*m + d;  beta <- beta - lr*m      (mu = 0: Alg. 1's own step)
+ *   TWA_OPT_ADAM      d = s + lambda*beta                      (decay as an L2 term)
+ *   TWA_OPT_ADAMW     beta <- (1 - lr*lambda)*beta first;  d = s   (decoupled decay)
+ *     then for both   m <- mu*m + (1-mu)*d;  v <- beta2*v + (1-beta2)*d*d;
+ *                     beta <- beta - lr * (m / (1 - mu^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+ *   m, v [in/out] device, `count` floats each: the optimiser's state, zero before the first step
+ *                 (v is not used by TWA_OPT_MOMENTUM and may be NULL there).
+ *   t             Adam / AdamW: number of this step, counted from 1.
+ * Errors: TWA_ERR_NULL; TWA_ERR_DTYPE (unknown kind); TWA_ERR_SHAPE (count out of range, t < 1, mu or
+ * beta2 outside [0, 1), eps < 0).  Asynchronous on `stream`; fp32 arithmetic.
+ */
+#define TWA_OPT_MOMENTUM 0
+#define TWA_OPT_ADAM 1
+#define TWA_OPT_ADAMW 2
+typedef struct {
+  int32_t kind;  /* TWA_OPT_* */
+  float lr;      /* eta */
+  float lambda;  /* weight decay */
+  float mu;      /* heavy-ball factor (momentum), beta_1 (Adam, AdamW) */
+  float beta2;   /* Adam, AdamW */
+  float eps;     /* Adam, AdamW */
+  int32_t t;     /* Adam, AdamW: step number from 1 */
+} twa_optim;
+int twa_beta_optim(const twa_optim* opt, float* beta, const float* s, float* m, float* v, int64_t count, void* stream);
+
+/*
  * Both "update variables" steps of Alg. 1 in one call: s = (P^l)^T g^l for every layer, then
  * beta <- (1 - lr*lambda) * beta - lr * s, the second inside the reduction kernel of the first (one
  * launch less than twa_project_layers + twa_beta_update).

@@ -33,6 +33,15 @@ class TwaError(RuntimeError):
         super().__init__(msg + (f" {detail}" if detail else ""))
 
 
+OPT_MOMENTUM, OPT_ADAM, OPT_ADAMW = 0, 1, 2
+
+
+class OptimStruct(C.Structure):
+    """twa_optim of include/twa.h."""
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("lam", C.c_float), ("mu", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("t", C.c_int32)]
+
+
 class _Pmat(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("n", C.c_int32), ("D", C.c_int64), ("ld", C.c_int64),
                 ("data", C.c_void_p), ("scales", C.c_void_p), ("block", C.c_int32), ("gscale", C.c_float)]
@@ -73,12 +82,13 @@ def lib():
         L.twa_centre_normalise_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(C.c_size_t)]
         L.twa_centre_normalise.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp, i64, vp, vp, C.c_size_t, vp]
         L.twa_beta_update.argtypes = [vp, vp, i64, f32, f32, vp]
+        L.twa_beta_optim.argtypes = [C.POINTER(OptimStruct), vp, vp, vp, vp, i64, vp]
         L.twa_beta_step.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, f32, f32, vp, vp, C.c_size_t, vp]
         L.twa_beta_step.restype = C.c_int
         L.twa_weights_from_beta.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, vp, vp]
         for f in (L.twa_project_layers_workspace_bytes, L.twa_project_layers, L.twa_expand_update_layers,
                   L.twa_layer_plan_bytes, L.twa_layer_plan, L.twa_centre_normalise_workspace_bytes,
-                  L.twa_centre_normalise, L.twa_beta_update, L.twa_weights_from_beta):
+                  L.twa_centre_normalise, L.twa_beta_update, L.twa_beta_optim, L.twa_weights_from_beta):
             f.restype = C.c_int
         for f in (L.twa_pmat_bytes, L.twa_project_workspace_bytes, L.twa_build_basis_workspace_bytes,
                   L.twa_build_basis, L.twa_quantize, L.twa_project, L.twa_expand_update):
@@ -342,6 +352,16 @@ def beta_update(beta: torch.Tensor, s: torch.Tensor, lr: float, lam: float = 0.0
     assert beta.is_contiguous() and s.is_contiguous()
     _check(lib().twa_beta_update(_ptr(beta), _ptr(s), beta.numel(), float(lr), float(lam), _stream()),
            "twa_beta_update")
+
+
+def beta_optim(kind: int, beta: torch.Tensor, s: torch.Tensor, m: torch.Tensor, v: Optional[torch.Tensor], lr: float,
+               lam: float = 0.0, mu: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, t: int = 1) -> None:
+    """twa_beta_optim: one coefficient step with momentum (OPT_MOMENTUM), Adam or AdamW, in place on beta, m, v."""
+    for a in (beta, s, m) + (() if v is None else (v,)):
+        assert a.dtype == torch.float32 and a.is_contiguous() and a.shape == beta.shape
+    o = OptimStruct(int(kind), float(lr), float(lam), float(mu), float(beta2), float(eps), int(t))
+    _check(lib().twa_beta_optim(C.byref(o), _ptr(beta), _ptr(s), _ptr(m), _ptr(v), beta.numel(), _stream()),
+           "twa_beta_optim")
 
 
 def beta_step(P: Pmat, g: torch.Tensor, plan: LayerPlan, beta: torch.Tensor, lr: float, lam: float = 0.0,

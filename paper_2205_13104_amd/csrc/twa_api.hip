@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <initializer_list>
 #include <mutex>
 #include <vector>
 
@@ -351,6 +352,26 @@ int twa_beta_update(float* beta, const float* s, int64_t count, float lr, float 
   if ((reinterpret_cast<uintptr_t>(beta) & 3u) || (reinterpret_cast<uintptr_t>(s) & 3u)) return TWA_ERR_ALIGN;
   if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
   return launch_beta_update(beta, s, count, lr, lambda, static_cast<hipStream_t>(stream));
+}
+
+int twa_beta_optim(const twa_optim* opt, float* beta, const float* s, float* m, float* v, int64_t count, void* stream) {
+  if (!opt || !beta || !s || !m) return TWA_ERR_NULL;
+  if (opt->kind != TWA_OPT_MOMENTUM && opt->kind != TWA_OPT_ADAM && opt->kind != TWA_OPT_ADAMW) return TWA_ERR_DTYPE;
+  const bool adam = opt->kind != TWA_OPT_MOMENTUM;
+  if (adam && !v) return TWA_ERR_NULL;
+  if (count <= 0 || count > (int64_t)TWA_MAX_LAYERS * TWA_MAX_N) return TWA_ERR_SHAPE;
+  if (!(opt->mu >= 0.0f && opt->mu < 1.0f)) return TWA_ERR_SHAPE;
+  if (adam && (opt->t < 1 || !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) || !(opt->eps >= 0.0f))) return TWA_ERR_SHAPE;
+  for (const void* p : {(const void*)beta, (const void*)s, (const void*)m, (const void*)v})
+    if (reinterpret_cast<uintptr_t>(p) & 3u) return TWA_ERR_ALIGN;
+  if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  float bias1 = 1.0f, bias2 = 1.0f;
+  if (adam) {
+    bias1 = (float)(1.0 - pow((double)opt->mu, (double)opt->t));
+    bias2 = (float)(1.0 - pow((double)opt->beta2, (double)opt->t));
+  }
+  return launch_beta_optim(opt->kind, beta, s, m, v, count, opt->lr, opt->lambda, opt->mu, opt->beta2, opt->eps, bias1,
+                           bias2, static_cast<hipStream_t>(stream));
 }
 
 int twa_quantize_minmax_workspace_bytes(int32_t L, size_t* bytes) {

@@ -117,6 +117,36 @@ __global__ __launch_bounds__(kEltThreads) void beta_update_kernel(float* __restr
   beta[q] = __builtin_fmaf(-lr, s[q], keep * beta[q]);
 }
 
+// The coefficient step with the base optimiser (Sec. 5.1), one coefficient per thread.
+//   KIND 0  heavy-ball momentum:  d = s + lambda beta;  m <- mu m + d;  beta <- beta - lr m
+//   KIND 1  Adam (decay as an L2 term), KIND 2 AdamW (decoupled decay):
+//           m <- mu m + (1 - mu) d;  v <- beta2 v + (1 - beta2) d^2;
+//           beta <- beta - lr (m / bias1) / (sqrt(v / bias2) + eps),  bias1 = 1 - mu^t, bias2 = 1 - beta2^t
+template <int KIND>
+__global__ __launch_bounds__(kEltThreads) void beta_optim_kernel(float* __restrict__ beta, const float* __restrict__ s,
+                                                                 float* __restrict__ m, float* __restrict__ v,
+                                                                 int64_t count, float lr, float lambda, float mu,
+                                                                 float beta2, float eps, float bias1, float bias2) {
+  const int64_t q = (int64_t)blockIdx.x * kEltThreads + threadIdx.x;
+  if (q >= count) return;
+  float b = beta[q];
+  if constexpr (KIND == 0) {
+    const float d = __builtin_fmaf(lambda, b, s[q]);
+    const float mq = __builtin_fmaf(mu, m[q], d);
+    m[q] = mq;
+    beta[q] = __builtin_fmaf(-lr, mq, b);
+  } else {
+    float d = s[q];
+    if constexpr (KIND == 1) d = __builtin_fmaf(lambda, b, d);
+    else b *= 1.0f - lr * lambda;
+    const float mq = __builtin_fmaf(mu, m[q], (1.0f - mu) * d);
+    const float vq = __builtin_fmaf(beta2, v[q], (1.0f - beta2) * d * d);
+    m[q] = mq;
+    v[q] = vq;
+    beta[q] = b - lr * (mq / bias1) / (__builtin_sqrtf(vq / bias2) + eps);
+  }
+}
+
 static int elt_grid(int64_t nvec) {
   const int64_t want = (nvec + kEltThreads - 1) / kEltThreads;
   const int cap = device_cus() * 8;
@@ -155,6 +185,18 @@ int launch_centre_normalise(const float* W, int64_t D, int n, int64_t ldw, const
 int launch_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, hipStream_t st) {
   hipLaunchKernelGGL(beta_update_kernel, dim3((unsigned)((count + kEltThreads - 1) / kEltThreads)), dim3(kEltThreads), 0,
                      st, beta, s, count, lr, lambda);
+  return hip_check(hipGetLastError());
+}
+
+int launch_beta_optim(int kind, float* beta, const float* s, float* m, float* v, int64_t count, float lr, float lambda,
+                      float mu, float beta2, float eps, float bias1, float bias2, hipStream_t st) {
+  const dim3 grid((unsigned)((count + kEltThreads - 1) / kEltThreads)), block(kEltThreads);
+  if (kind == TWA_OPT_MOMENTUM)
+    hipLaunchKernelGGL(beta_optim_kernel<0>, grid, block, 0, st, beta, s, m, v, count, lr, lambda, mu, beta2, eps, bias1, bias2);
+  else if (kind == TWA_OPT_ADAM)
+    hipLaunchKernelGGL(beta_optim_kernel<1>, grid, block, 0, st, beta, s, m, v, count, lr, lambda, mu, beta2, eps, bias1, bias2);
+  else
+    hipLaunchKernelGGL(beta_optim_kernel<2>, grid, block, 0, st, beta, s, m, v, count, lr, lambda, mu, beta2, eps, bias1, bias2);
   return hip_check(hipGetLastError());
 }
 

@@ -49,6 +49,9 @@ size_t minmax_workspace_bytes(int L);
 int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const void* plan_dev, int L, int dtype,
                            int bits, uint8_t* codes, int64_t ld, float* ab, void* ws, hipStream_t st);
 int launch_beta_update(float* beta, const float* s, int64_t count, float lr, float lambda, hipStream_t st);
+// bias1 = 1 - mu^t, bias2 = 1 - beta2^t (formed on the host in double)
+int launch_beta_optim(int kind, float* beta, const float* s, float* m, float* v, int64_t count, float lr, float lambda,
+                      float mu, float beta2, float eps, float bias1, float bias2, hipStream_t st);
 int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pmat& out, hipStream_t st);
 int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st);
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram, hipStream_t st);

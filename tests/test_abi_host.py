@@ -131,6 +131,17 @@ def test_layerwise_entry_points_argument_errors():
     assert L.twa_expand_update_layers(C.byref(pm), 0x2000, 0x9000, 2, 0x3004, 0.1, None, None) == twa.ERR_ALIGN
     assert L.twa_weights_from_beta(C.byref(pm), 0x2000, 0x9000, 2, None, 0x3000, None) == twa.ERR_NULL
     assert L.twa_beta_update(0x2000, 0x3000, -1, 0.1, 0.0, None) == twa.ERR_SHAPE
+    # the coefficient step with the base optimiser
+    opt = lambda **k: C.byref(twa.OptimStruct(k.get("kind", twa.OPT_ADAM), 0.1, 0.0, k.get("mu", 0.9), k.get("beta2", 0.99),
+                                              k.get("eps", 1e-8), k.get("t", 1)))
+    assert L.twa_beta_optim(None, 0x2000, 0x3000, 0x4000, 0x5000, 8, None) == twa.ERR_NULL
+    assert L.twa_beta_optim(opt(), 0x2000, 0x3000, None, 0x5000, 8, None) == twa.ERR_NULL
+    assert L.twa_beta_optim(opt(), 0x2000, 0x3000, 0x4000, None, 8, None) == twa.ERR_NULL
+    assert L.twa_beta_optim(opt(kind=9), 0x2000, 0x3000, 0x4000, 0x5000, 8, None) == twa.ERR_DTYPE
+    assert L.twa_beta_optim(opt(t=0), 0x2000, 0x3000, 0x4000, 0x5000, 8, None) == twa.ERR_SHAPE
+    assert L.twa_beta_optim(opt(mu=1.5), 0x2000, 0x3000, 0x4000, 0x5000, 8, None) == twa.ERR_SHAPE
+    assert L.twa_beta_optim(opt(eps=-1.0), 0x2000, 0x3000, 0x4000, 0x5000, 8, None) == twa.ERR_SHAPE
+    assert L.twa_beta_optim(opt(), 0x2000, 0x3002, 0x4000, 0x5000, 8, None) == twa.ERR_ALIGN
     # the paper's min-max format: layer-wise calls only, factors required
     mm = _pm(dtype=twa.U4MM, ld=2048, scales=0)
     assert L.twa_project_layers(C.byref(mm), 0x2000, 0x9000, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_NULL

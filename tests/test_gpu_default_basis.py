@@ -129,3 +129,63 @@ def test_default_basis_argument_errors():
     b = torch.zeros(8, device="cuda")
     assert L.twa_beta_update(None, b.data_ptr(), 8, 0.1, 0.0, None) == twa.ERR_NULL
     assert L.twa_beta_update(b.data_ptr(), b.data_ptr(), 0, 0.1, 0.0, None) == twa.ERR_SHAPE
+
+
+@pytest.mark.parametrize("kind,lam", [("momentum", 0.0), ("momentum", 0.05), ("adam", 0.0), ("adam", 0.05), ("adamw", 0.05)])
+def test_coefficient_step_with_the_base_optimiser(kind, lam):
+    """Layer-wise training of the coefficients with momentum / Adam / AdamW (Sec. 5.1) over several steps: the
+    library and the oracle each follow their own trajectory from the same gradients."""
+    D, n, T, lr = 300_007, 16, 6, 0.02
+    off = synth.layer_offsets(synth.random_layer_sizes(D, 20, seed=9))
+    plan = twa.LayerPlan(off, D)
+    L = plan.L
+    W = synth.trajectory(D, n, 0.95, 0.4, seed=23, device="cuda")
+    E, wbar, _ = twa.centre_normalise(W, D, plan)
+    pm = store_as(E, D, twa.I8)
+    po = to_oracle(pm)
+    K = {"momentum": twa.OPT_MOMENTUM, "adam": twa.OPT_ADAM, "adamw": twa.OPT_ADAMW}[kind]
+    Ko = {"momentum": orc.MOMENTUM, "adam": orc.ADAM, "adamw": orc.ADAMW}[kind]
+    mu, b2, eps = 0.9, 0.99, 1e-8
+    beta, m, v = (torch.zeros((L, n), device="cuda") for _ in range(3))
+    beta_o, m_o, v_o = (np.zeros((L, n)) for _ in range(3))
+    wbar_o = wbar.cpu().numpy().astype(np.float64)
+    f = lambda x: float(np.float32(x))
+    say("base optimiser", kind, "lambda", lam)
+    for t in range(1, T + 1):
+        g = synth.gradient(D, 1e-2, seed=6, step=t, device="cuda")
+        S = twa.project_layers(pm, g, plan)
+        twa.beta_optim(K, beta, S, m, None if kind == "momentum" else v, lr, lam, mu, b2, eps, t)
+        w = twa.weights_from_beta(pm, beta, plan, wbar)
+        torch.cuda.synchronize()
+        So = orc.project_layers(po, g.cpu().numpy().astype(np.float64), off.numpy())
+        orc.beta_optim(Ko, beta_o, So, m_o, None if kind == "momentum" else v_o, f(lr), f(lam), f(mu), f(b2), f(eps), t)
+        wo = orc.weights_from_beta(po, beta_o, off.numpy(), wbar_o)
+        assert rel_l2(beta.cpu().numpy(), beta_o) <= REL_L2_TOL, t
+        assert rel_l2(m.cpu().numpy(), m_o) <= REL_L2_TOL, t
+        if kind != "momentum":
+            assert rel_l2(v.cpu().numpy(), v_o) <= REL_L2_TOL, t
+        assert rel_l2(w.cpu().numpy(), wo) <= REL_L2_TOL, t
+    if kind == "momentum":
+        # without momentum it is Alg. 1's own step, bit for bit
+        b1, b2_, m0 = beta.clone(), beta.clone(), torch.zeros_like(beta)
+        twa.beta_update(b1, S, lr, lam)
+        twa.beta_optim(twa.OPT_MOMENTUM, b2_, S, m0, None, lr, lam, 0.0)
+        assert rel_l2(b1.cpu().numpy(), b2_.double().cpu().numpy()) <= 1e-7
+
+
+def test_base_optimiser_argument_errors():
+    import ctypes as C
+    L = twa.lib()
+    b = torch.zeros(8, device="cuda")
+    mk = lambda **k: twa.OptimStruct(k.get("kind", 1), 0.1, 0.0, k.get("mu", 0.9), k.get("beta2", 0.99), k.get("eps", 1e-8),
+                                     k.get("t", 1))
+    p = b.data_ptr()
+    assert L.twa_beta_optim(None, p, p, p, p, 8, None) == twa.ERR_NULL
+    assert L.twa_beta_optim(C.byref(mk()), p, p, p, None, 8, None) == twa.ERR_NULL          # Adam needs v
+    assert L.twa_beta_optim(C.byref(mk(kind=0)), p, p, p, None, 8, None) == twa.OK           # momentum does not
+    assert L.twa_beta_optim(C.byref(mk(kind=7)), p, p, p, p, 8, None) == twa.ERR_DTYPE
+    assert L.twa_beta_optim(C.byref(mk(t=0)), p, p, p, p, 8, None) == twa.ERR_SHAPE
+    assert L.twa_beta_optim(C.byref(mk(mu=1.0)), p, p, p, p, 8, None) == twa.ERR_SHAPE
+    assert L.twa_beta_optim(C.byref(mk(beta2=-0.1)), p, p, p, p, 8, None) == twa.ERR_SHAPE
+    assert L.twa_beta_optim(C.byref(mk()), p, p, p, p, 0, None) == twa.ERR_SHAPE
+    torch.cuda.synchronize()
