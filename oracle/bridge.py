@@ -11,7 +11,7 @@ import torch
 from . import twa_oracle as orc
 
 
-U8MM, U4MM = 4, 5      # dtype codes of the paper's min-max format in the C descriptor
+U8MM, U4MM, U16MM = 4, 5, 6      # dtype codes of the paper's min-max format in the C descriptor
 
 
 def to_oracle(pm, cols=None, layer_off=None) -> orc.Pmat:
@@ -20,9 +20,11 @@ def to_oracle(pm, cols=None, layer_off=None) -> orc.Pmat:
     The min-max formats need the layer table (`layer_off`, L+1 offsets) the matrix was quantised with;
     their packed codes are spread out to one unsigned 16-bit code per element, as the oracle keeps them."""
     data = pm.data if cols is None else pm.data[cols]
-    if pm.dtype in (U8MM, U4MM):
+    if pm.dtype in (U8MM, U4MM, U16MM):
         raw = data.cpu().numpy()
-        if pm.dtype == U8MM:
+        if pm.dtype == U16MM:
+            codes = (raw.astype(np.int32) + 32768).astype(np.uint16)          # the word holds code - 32768
+        elif pm.dtype == U8MM:
             codes = (raw.astype(np.int16) + 128).astype(np.uint16)            # the byte holds code - 128
         else:
             b = raw.astype(np.uint16)

@@ -46,7 +46,7 @@ int env_int(const char* name, int fallback) {
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 static bool scaled(int dtype) { return dtype == TWA_I8 || dtype == TWA_I4; }
-static bool minmax(int dtype) { return dtype == TWA_U8MM || dtype == TWA_U4MM; }
+static bool minmax(int dtype) { return dtype == TWA_U8MM || dtype == TWA_U4MM || dtype == TWA_U16MM; }
 static int bits_of(int dtype) {
   switch (dtype) {
     case TWA_F32: return 32;
@@ -55,6 +55,7 @@ static int bits_of(int dtype) {
     case TWA_I4: return 4;
     case TWA_U8MM: return 8;
     case TWA_U4MM: return 4;
+    case TWA_U16MM: return 16;
     default: return 0;
   }
 }
@@ -386,6 +387,8 @@ int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const
   if (!P || !out || !out->data || !out->scales) return TWA_ERR_NULL;
   if (!minmax(out->dtype)) return TWA_ERR_DTYPE;
   if (bits < 1 || bits > bits_of(out->dtype)) return TWA_ERR_SHAPE;
+  // (a 16-bit word holds c - 32768: centred only when the codes use the whole word)
+  if (out->dtype == TWA_U16MM && bits != 16) return TWA_ERR_SHAPE;
   if (out->D != D || out->n != n) return TWA_ERR_SHAPE;
   int rc = check_dims(D, n, ldp, TWA_F32);
   if (rc != TWA_OK) return rc;

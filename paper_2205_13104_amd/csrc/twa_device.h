@@ -100,10 +100,18 @@ template <> struct Store<TWA_U4MM> {
   static constexpr bool kScaled = false;
   static constexpr int kScaleBytes = 0;
 };
-template <int DT> constexpr bool kMinMax = DT == TWA_U8MM || DT == TWA_U4MM;
+template <> struct Store<TWA_U16MM> {
+  static constexpr int kEPV = 8;
+  static constexpr int kBitsPerElem = 16;
+  static constexpr bool kScaled = false;
+  static constexpr int kScaleBytes = 0;
+};
+template <int DT> constexpr bool kMinMax = DT == TWA_U8MM || DT == TWA_U4MM || DT == TWA_U16MM;
 template <int DT> constexpr bool kNibbles = DT == TWA_I4 || DT == TWA_U4MM;
 // decoded code = c - kCodeBias<DT> for the min-max formats
-template <int DT> constexpr float kCodeBias = DT == TWA_U8MM ? 128.0f : 0.0f;
+template <int DT> constexpr float kCodeBias = DT == TWA_U8MM ? 128.0f : DT == TWA_U16MM ? 32768.0f : 0.0f;
+// what the stored integer lacks of the code: the above, and 8 for nibbles (which the kernels decode as code + 8 - 8)
+template <int DT> constexpr float kStoredBias = kNibbles<DT> ? 8.0f : kCodeBias<DT>;
 
 // Decode one 128-bit vector into kEPV "raw" floats: the stored value up to the per-block
 // scale, and for I4 up to the bias and nibble position:
@@ -155,6 +163,13 @@ template <> __device__ __forceinline__ void decode<TWA_I4>(const u32x4& v, float
 
 template <> __device__ __forceinline__ void decode<TWA_U8MM>(const u32x4& v, float* raw) { decode<TWA_I8>(v, raw); }
 template <> __device__ __forceinline__ void decode<TWA_U4MM>(const u32x4& v, float* raw) { decode<TWA_I4>(v, raw); }
+template <> __device__ __forceinline__ void decode<TWA_U16MM>(const u32x4& v, float* raw) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    raw[2 * q] = (float)(int16_t)(v[q] & 0xffffu);          // sign-extending converts of the two halves
+    raw[2 * q + 1] = (float)((int32_t)v[q] >> 16);
+  }
+}
 
 // Scale of one block as a float (binary16 scales are widened and multiplied by gscale).
 template <int DT> __device__ __forceinline__ float load_scale(rsrc_t r, uint32_t voff, float gscale) {

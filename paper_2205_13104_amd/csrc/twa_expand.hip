@@ -447,6 +447,12 @@ static int launch_expand_any(const PView& P, int dtype, const float* s, const fl
         break;
       }
       return TWA_ERR_DTYPE;
+    case TWA_U16MM:
+      if constexpr (LAYERED) {
+        launch_expand_cfg<TWA_U16MM, 2, 4, 6, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        break;
+      }
+      return TWA_ERR_DTYPE;
     case TWA_U4MM:
       if constexpr (LAYERED) {
         launch_expand_cfg<TWA_U4MM, 8, 1, 5, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);

@@ -100,14 +100,15 @@ __global__ __launch_bounds__(256) void layer_factors_kernel(const uint32_t* __re
   a64[l] = a;
 }
 
-// A thread packs EL consecutive elements of one vector into one dword: 4 bytes (c - 128) or 8 nibbles.
+// A thread packs EL consecutive elements of one vector into one dword: 2 words (c - 32768), 4 bytes
+// (c - 128) or 8 nibbles.
 template <int DT>
 __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restrict__ P, int64_t D, int64_t ldp,
                                                            uint8_t* __restrict__ codes, int64_t ld,
                                                            const int64_t* __restrict__ off, int L,
                                                            const float* __restrict__ ab,
                                                            const double* __restrict__ a64, double levels) {
-  constexpr int EL = (DT == TWA_U8MM) ? 4 : 8;
+  constexpr int EL = 32 / Store<DT>::kBitsPerElem;
   const int j = blockIdx.y;
   const int64_t nvec = ld / EL;
   const float* p = P + (int64_t)j * ldp;
@@ -134,11 +135,14 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
           q = q < 0.0 ? 0.0 : (q > levels ? levels : q);
           c = (uint32_t)q;
         }
-        if constexpr (DT == TWA_U8MM) word |= ((c ^ 0x80u) & 0xffu) << (8 * e);      // c - 128 as int8
+        if constexpr (DT == TWA_U16MM) word |= ((c ^ 0x8000u) & 0xffffu) << (16 * e);   // c - 32768 as int16
+        else if constexpr (DT == TWA_U8MM) word |= ((c ^ 0x80u) & 0xffu) << (8 * e);      // c - 128 as int8
         else word |= (c & 0xfu) << (4 * e);                                          // even element in the low nibble
       }
     } else if constexpr (DT == TWA_U8MM) {
       word = 0x80808080u;                       // padding: code 0
+    } else if constexpr (DT == TWA_U16MM) {
+      word = 0x80008000u;
     }
     out[vec] = word;
   }
@@ -157,11 +161,14 @@ int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const 
   const int cus = device_cus();
   hipLaunchKernelGGL(layer_minmax_kernel, dim3(cus * 4), dim3(256), 0, st, P, D, n, ldp, plan, keys);
   hipLaunchKernelGGL(layer_factors_kernel, dim3(lgrid), dim3(256), 0, st, keys, L, levels, ab, a64);
-  const int el = dtype == TWA_U8MM ? 4 : 8;
+  const int el = dtype == TWA_U16MM ? 2 : dtype == TWA_U8MM ? 4 : 8;
   const int64_t nvec = ld / el;
   int gx = (int)((nvec + 255) / 256);
   if (gx > cus * 8) gx = cus * 8;
-  if (dtype == TWA_U8MM)
+  if (dtype == TWA_U16MM)
+    hipLaunchKernelGGL(minmax_codes_kernel<TWA_U16MM>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L,
+                       ab, a64, levels);
+  else if (dtype == TWA_U8MM)
     hipLaunchKernelGGL(minmax_codes_kernel<TWA_U8MM>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L,
                        ab, a64, levels);
   else

@@ -567,7 +567,7 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   int rc = launch_project_dt<DT, 1, VPL, true>(P, g, 0, 1, partial, max_grid, &grid, st, plan, partial_g);
   if (rc != TWA_OK) return rc;
   hipLaunchKernelGGL(project_layers_reduce_kernel<kMinMax<DT>>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial,
-                     partial_g, P.n, plan, grid, reinterpret_cast<const float*>(P.scales), kNibbles<DT> ? 8.0f : 128.0f,
+                     partial_g, P.n, plan, grid, reinterpret_cast<const float*>(P.scales), kStoredBias<DT>,
                      S, bs);
   return hip_check(hipGetLastError());
 }
@@ -597,6 +597,7 @@ int launch_project_layers(const PView& P, int dtype, const float* g, const void*
     case TWA_I4: return launch_project_layers_dt<TWA_I4, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     case TWA_U8MM: return launch_project_layers_dt<TWA_U8MM, 2>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     case TWA_U4MM: return launch_project_layers_dt<TWA_U4MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_U16MM: return launch_project_layers_dt<TWA_U16MM, 2>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     default: return TWA_ERR_DTYPE;
   }
 }

@@ -155,6 +155,9 @@ def test_layerwise_entry_points_argument_errors():
     assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 9, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
     out = _pm(dtype=twa.U4MM, scales=0x5000, ld=2048)
     assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 5, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
+    out = _pm(dtype=twa.U16MM, scales=0x5000, ld=2048)
+    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 17, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
+    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 12, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
     assert L.twa_centre_normalise(0x6000, 1000, 4, 1024, 0x9000, 2, None, 0x7000, 1024, None, 0x4000, 1 << 30,
                                   None) == twa.ERR_NULL
     assert L.twa_centre_normalise(0x6000, 1000, 4, 1000, 0x9000, 2, 0xa000, 0x7000, 1024, None, 0x4000, 1 << 30,
