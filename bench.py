@@ -53,8 +53,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1000,
                     help="untimed steps; the device needs ~0.5 s of this load before the step time settles")
     ap.add_argument("--workload", default="imagenet_resnet50", help="name in synth.WORKLOADS")
-    ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4", "mm16", "mm8", "mm4"],
-                    help="mm16 / mm8 / mm4: the paper's per-layer min-max codes (layer-wise mode only)")
+    ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4", "mm16", "mm8", "mm4", "mm2", "mm1"],
+                    help="mm16 .. mm1: the paper's per-layer min-max codes of that many bits (layer-wise mode only)")
     ap.add_argument("--mode", default="whole", choices=["whole", "layerwise"],
                     help="whole: the headline step (orthonormal basis, s = P^T g, w -= lr P s).  layerwise: Alg. 1 as "
                          "written -- per-layer centre+normalise basis, coefficient step with weight decay, w = wbar + P beta")
@@ -84,9 +84,9 @@ def main():
     D = args.D or wl.D
     n = wl.n
     dtype = {"f32": twa.F32, "bf16": twa.BF16, "i8": twa.I8, "i4": twa.I4, "mm8": twa.U8MM, "mm4": twa.U4MM,
-             "mm16": twa.U16MM}[args.storage]
+             "mm16": twa.U16MM, "mm2": twa.U2MM, "mm1": twa.U1MM}[args.storage]
     layerwise = args.mode == "layerwise"
-    if dtype in (twa.U8MM, twa.U4MM, twa.U16MM) and not layerwise:
+    if dtype in twa.MINMAX_TYPES and not layerwise:
         sys.exit("bench.py: the min-max formats exist for the layer-wise calls only (use --mode layerwise)")
 
     # ---- inputs: checkpoints -> orthonormal basis (in place) -> stored P ------------------------
@@ -107,8 +107,8 @@ def main():
     t2 = time.time()
     if dtype == twa.F32:
         pm = twa.wrap_f32(P32, D)
-    elif dtype in (twa.U8MM, twa.U4MM, twa.U16MM):
-        pm = twa.quantize_minmax(P32, D, plan, bits={twa.U8MM: 8, twa.U4MM: 4, twa.U16MM: 16}[dtype])
+    elif dtype in twa.MINMAX_TYPES:
+        pm = twa.quantize_minmax(P32, D, plan, bits=twa.BITS_OF[dtype])
     else:
         pm = twa.quantize(P32, D, dtype)
     torch.cuda.synchronize()

@@ -68,7 +68,9 @@ typedef enum twa_dtype {
      layer table the matrix was quantised with).                                               */
   TWA_U8MM = 4, /* B = 8: the byte holds c - 128 as a two's-complement int8                      */
   TWA_U4MM = 5, /* B = 4: two codes per byte, element i in the LOW nibble when i is even         */
-  TWA_U16MM = 6 /* B = 16: the 16-bit word holds c - 32768 as a two's-complement int16           */
+  TWA_U16MM = 6, /* B = 16: the 16-bit word holds c - 32768 as a two's-complement int16          */
+  TWA_U2MM = 7,  /* B = 2: four codes per byte, element i in bits 2*(i mod 4) .. 2*(i mod 4)+1    */
+  TWA_U1MM = 8   /* B = 1: eight codes per byte, element i in bit i mod 8                         */
 } twa_dtype;
 
 /*
@@ -242,13 +244,15 @@ int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan
  * evaluated in fp64 with ties to even (the paper names no tie rule); a_l = 0 (a constant layer)
  * gives c = 0; the factors are stored rounded to binary32 (b_l exactly).  The stored value is
  * within a_l/2 of p.
- *   bits [in]     B: 1..4 with out->dtype TWA_U4MM, 1..8 with TWA_U8MM, 16 with TWA_U16MM.  The paper
- *                 studies B in {1, 2, 3, 4, 8, 16}: codes of fewer bits than a nibble or a byte holds are
- *                 stored in it (same values and factors as B-bit storage would give, without the extra
- *                 saving of memory).  B = 9..15 is not provided: the stored word c - 32768 is centred
- *                 only when the codes fill it, and the fused dequantisation relies on that.
- *   out  [in/out] dtype TWA_U4MM, TWA_U8MM or TWA_U16MM; data and scales (2L floats) allocated by the
- *                 caller (twa_pmat_bytes gives ld and the data size; it reports 0 scale bytes for these
+ *   bits [in]     B: 1 with out->dtype TWA_U1MM, 1..2 with TWA_U2MM, 1..4 with TWA_U4MM, 1..8 with
+ *                 TWA_U8MM, 16 with TWA_U16MM.  The paper studies B in {1, 2, 3, 4, 8, 16}: each has a
+ *                 container of its own except B = 3, which travels in nibbles.  Codes of fewer bits than
+ *                 the container holds are stored in it (same values and factors as B-bit storage would
+ *                 give, without the extra saving of memory).  B = 9..15 is not provided: the stored word
+ *                 c - 32768 is centred only when the codes fill it, and the fused dequantisation relies
+ *                 on that.
+ *   out  [in/out] one of the TWA_U*MM types; data and scales (2L floats) allocated by the caller
+ *                 (twa_pmat_bytes gives ld and the data size; it reports 0 scale bytes for these
  *                 types since it does not know L).
  *   ws, ws_bytes  device workspace of at least twa_quantize_minmax_workspace_bytes(L).
  */

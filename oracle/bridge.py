@@ -11,7 +11,7 @@ import torch
 from . import twa_oracle as orc
 
 
-U8MM, U4MM, U16MM = 4, 5, 6      # dtype codes of the paper's min-max format in the C descriptor
+U8MM, U4MM, U16MM, U2MM, U1MM = 4, 5, 6, 7, 8      # dtype codes of the paper's min-max format in the C descriptor
 
 
 def to_oracle(pm, cols=None, layer_off=None) -> orc.Pmat:
@@ -20,9 +20,16 @@ def to_oracle(pm, cols=None, layer_off=None) -> orc.Pmat:
     The min-max formats need the layer table (`layer_off`, L+1 offsets) the matrix was quantised with;
     their packed codes are spread out to one unsigned 16-bit code per element, as the oracle keeps them."""
     data = pm.data if cols is None else pm.data[cols]
-    if pm.dtype in (U8MM, U4MM, U16MM):
+    if pm.dtype in (U8MM, U4MM, U16MM, U2MM, U1MM):
         raw = data.cpu().numpy()
-        if pm.dtype == U16MM:
+        if pm.dtype in (U2MM, U1MM):
+            bits = 2 if pm.dtype == U2MM else 1
+            per = 8 // bits                                                     # codes per byte, low bits first
+            b = raw.astype(np.uint16)
+            codes = np.empty((b.shape[0], per * b.shape[1]), dtype=np.uint16)
+            for k in range(per):
+                codes[:, k::per] = (b >> (bits * k)) & ((1 << bits) - 1)
+        elif pm.dtype == U16MM:
             codes = (raw.astype(np.int32) + 32768).astype(np.uint16)          # the word holds code - 32768
         elif pm.dtype == U8MM:
             codes = (raw.astype(np.int16) + 128).astype(np.uint16)            # the byte holds code - 128

@@ -16,7 +16,9 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtwa.so")
 
-F32, BF16, I8, I4, U8MM, U4MM, U16MM = 0, 1, 2, 3, 4, 5, 6
+F32, BF16, I8, I4, U8MM, U4MM, U16MM, U2MM, U1MM = 0, 1, 2, 3, 4, 5, 6, 7, 8
+MINMAX_TYPES = (U8MM, U4MM, U16MM, U2MM, U1MM)
+BITS_OF = {F32: 32, BF16: 16, I8: 8, I4: 4, U8MM: 8, U4MM: 4, U16MM: 16, U2MM: 2, U1MM: 1}
 MAX_N, MAX_K, LD_MULTIPLE, SCALE_SPAN, MAX_LAYERS = 128, 8, 128, 2048, 65536
 DEFAULT_BLOCK = {I8: 128, I4: 64}
 
@@ -135,7 +137,7 @@ def build_basis_workspace_bytes(n: int) -> int:
 
 
 _TORCH_OF = {F32: torch.float32, BF16: torch.bfloat16, I8: torch.int8, I4: torch.uint8, U8MM: torch.int8,
-             U4MM: torch.uint8, U16MM: torch.int16}
+             U4MM: torch.uint8, U16MM: torch.int16, U2MM: torch.uint8, U1MM: torch.uint8}
 
 
 @dataclass
@@ -145,9 +147,9 @@ class Pmat:
     D: int
     n: int
     ld: int
-    data: torch.Tensor                      # (n, ld) values/codes; I4, U4MM: (n, ld // 2) bytes
+    data: torch.Tensor                      # (n, ld) values/codes; sub-byte codes: (n, ld * bits // 8) bytes
     scales: Optional[torch.Tensor] = None   # (ld // 2048, n, 2048 // block): float32 (I8) / float16 (I4);
-                                            # U8MM, U4MM, U16MM: (L, 2) float32 = (a_l, b_l) per layer
+                                            # min-max types: (L, 2) float32 = (a_l, b_l) per layer
     block: int = 0
     gscale: float = 1.0
 
@@ -164,9 +166,9 @@ class Pmat:
     @property
     def stream_bytes(self) -> int:
         """Bytes of P one pass over the matrix has to move (codes/values of the D logical elements + scales)."""
-        bits = {F32: 32, BF16: 16, I8: 8, I4: 4, U8MM: 8, U4MM: 4, U16MM: 16}[self.dtype]
+        bits = BITS_OF[self.dtype]
         b = self.n * self.D * bits // 8
-        if self.dtype in (U8MM, U4MM, U16MM):
+        if self.dtype in MINMAX_TYPES:
             return b + self.scales.numel() * 4
         if self.scales is not None:
             b += self.n * ((self.D + self.block - 1) // self.block) * self.scales.element_size()
@@ -308,14 +310,14 @@ def expand_update_layers(P: Pmat, S: torch.Tensor, plan: LayerPlan, w: torch.Ten
 
 
 def quantize_minmax(P: torch.Tensor, D: int, plan: LayerPlan, bits: int = 4) -> Pmat:
-    """twa_quantize_minmax: the paper's per-layer min-max format (Sec. 4.6), B = 1..8 or 16 bits (codes of up
-    to 4 bits travel in nibbles, up to 8 in bytes, 16-bit codes in words)."""
+    """twa_quantize_minmax: the paper's per-layer min-max format (Sec. 4.6), B = 1..8 or 16 bits, in the
+    smallest container that holds them (1 and 2 bits packed, up to 4 in nibbles, up to 8 in bytes, 16 in words)."""
     assert P.dtype == torch.float32 and P.dim() == 2 and P.is_contiguous() and plan.D == D
     assert 1 <= bits <= 8 or bits == 16
-    dtype = U4MM if bits <= 4 else U8MM if bits <= 8 else U16MM
+    dtype = U1MM if bits == 1 else U2MM if bits == 2 else U4MM if bits <= 4 else U8MM if bits <= 8 else U16MM
     n, ldp = P.shape
     ld, _, _ = pmat_bytes(dtype, D, n)
-    cols = ld // 2 if dtype == U4MM else ld
+    cols = ld * BITS_OF[dtype] // 8 if BITS_OF[dtype] < 8 else ld
     data = torch.empty((n, cols), dtype=_TORCH_OF[dtype], device=P.device)
     ab = torch.empty((plan.L, 2), dtype=torch.float32, device=P.device)
     out = Pmat(dtype, D, n, ld, data, ab, 0, 1.0)

@@ -46,7 +46,9 @@ int env_int(const char* name, int fallback) {
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 static bool scaled(int dtype) { return dtype == TWA_I8 || dtype == TWA_I4; }
-static bool minmax(int dtype) { return dtype == TWA_U8MM || dtype == TWA_U4MM || dtype == TWA_U16MM; }
+static bool minmax(int dtype) {
+  return dtype == TWA_U8MM || dtype == TWA_U4MM || dtype == TWA_U16MM || dtype == TWA_U2MM || dtype == TWA_U1MM;
+}
 static int bits_of(int dtype) {
   switch (dtype) {
     case TWA_F32: return 32;
@@ -56,6 +58,8 @@ static int bits_of(int dtype) {
     case TWA_U8MM: return 8;
     case TWA_U4MM: return 4;
     case TWA_U16MM: return 16;
+    case TWA_U2MM: return 2;
+    case TWA_U1MM: return 1;
     default: return 0;
   }
 }

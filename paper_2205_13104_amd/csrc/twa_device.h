@@ -106,7 +106,22 @@ template <> struct Store<TWA_U16MM> {
   static constexpr bool kScaled = false;
   static constexpr int kScaleBytes = 0;
 };
-template <int DT> constexpr bool kMinMax = DT == TWA_U8MM || DT == TWA_U4MM || DT == TWA_U16MM;
+// Two and one bit per code: a lane still owns 32 consecutive elements (as with nibbles), which are 8 or 4
+// bytes, fetched with a 64- or 32-bit load.
+template <> struct Store<TWA_U2MM> {
+  static constexpr int kEPV = 32;
+  static constexpr int kBitsPerElem = 2;
+  static constexpr bool kScaled = false;
+  static constexpr int kScaleBytes = 0;
+};
+template <> struct Store<TWA_U1MM> {
+  static constexpr int kEPV = 32;
+  static constexpr int kBitsPerElem = 1;
+  static constexpr bool kScaled = false;
+  static constexpr int kScaleBytes = 0;
+};
+template <int DT>
+constexpr bool kMinMax = DT == TWA_U8MM || DT == TWA_U4MM || DT == TWA_U16MM || DT == TWA_U2MM || DT == TWA_U1MM;
 template <int DT> constexpr bool kNibbles = DT == TWA_I4 || DT == TWA_U4MM;
 // decoded code = c - kCodeBias<DT> for the min-max formats
 template <int DT> constexpr float kCodeBias = DT == TWA_U8MM ? 128.0f : DT == TWA_U16MM ? 32768.0f : 0.0f;
@@ -168,6 +183,49 @@ template <> __device__ __forceinline__ void decode<TWA_U16MM>(const u32x4& v, fl
   for (int q = 0; q < 4; ++q) {
     raw[2 * q] = (float)(int16_t)(v[q] & 0xffffu);          // sign-extending converts of the two halves
     raw[2 * q + 1] = (float)((int32_t)v[q] >> 16);
+  }
+}
+
+// B = 2: byte k of (w >> 2m) & 0x03030303 is element 4k + m of the 16 a dword holds.
+template <> __device__ __forceinline__ void decode<TWA_U2MM>(const u32x4& v, float* raw) {
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      uint32_t t = (v[q] >> (2 * m)) & 0x03030303u;
+      asm volatile("" : "+v"(t));                          // keep the masked word: one byte convert per element
+      raw[16 * q + 0 + m] = (float)(t & 0xff);
+      raw[16 * q + 4 + m] = (float)((t >> 8) & 0xff);
+      raw[16 * q + 8 + m] = (float)((t >> 16) & 0xff);
+      raw[16 * q + 12 + m] = (float)(t >> 24);
+    }
+  }
+}
+// B = 1: byte k of (w >> m) & 0x01010101 is element 8k + m of the 32 a dword holds.
+template <> __device__ __forceinline__ void decode<TWA_U1MM>(const u32x4& v, float* raw) {
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    uint32_t t = (v[0] >> m) & 0x01010101u;
+    asm volatile("" : "+v"(t));
+    raw[0 + m] = (float)(t & 0xff);
+    raw[8 + m] = (float)((t >> 8) & 0xff);
+    raw[16 + m] = (float)((t >> 16) & 0xff);
+    raw[24 + m] = (float)(t >> 24);
+  }
+}
+
+// The kEPV stored elements of one lane, streamed: 128 bits for most types, 64 or 32 for the 2- and 1-bit
+// codes (the unused words of the result are zero and never read).
+template <int DT> __device__ __forceinline__ u32x4 load_codes(rsrc_t r, uint32_t voff) {
+  constexpr int kBits = Store<DT>::kEPV * Store<DT>::kBitsPerElem;
+  static_assert(kBits == 128 || kBits == 64 || kBits == 32, "a lane's elements are one load");
+  if constexpr (kBits == 128) {
+    return ld128_stream(r, voff);
+  } else if constexpr (kBits == 64) {
+    const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, 0, /*nt*/ 2);
+    return u32x4{t[0], t[1], 0u, 0u};
+  } else {
+    return u32x4{__builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, 0, /*nt*/ 2), 0u, 0u, 0u};
   }
 }
 

@@ -87,7 +87,7 @@ struct Expander {
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
           const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
-          raw[u][v] = ld128_stream(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
+          raw[u][v] = load_codes<DT>(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
           if constexpr (S::kScaled) {
             // scale index inside the tile's run of spans: [span][vector][block in span];
             // an unused column slot reads far outside the range and gets 0
@@ -450,6 +450,18 @@ static int launch_expand_any(const PView& P, int dtype, const float* s, const fl
     case TWA_U16MM:
       if constexpr (LAYERED) {
         launch_expand_cfg<TWA_U16MM, 2, 4, 6, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        break;
+      }
+      return TWA_ERR_DTYPE;
+    case TWA_U2MM:
+      if constexpr (LAYERED) {
+        launch_expand_cfg<TWA_U2MM, 8, 1, 5, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        break;
+      }
+      return TWA_ERR_DTYPE;
+    case TWA_U1MM:
+      if constexpr (LAYERED) {
+        launch_expand_cfg<TWA_U1MM, 8, 1, 5, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
         break;
       }
       return TWA_ERR_DTYPE;

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void layer_factors_kernel(const uint32_t* __re
 }
 
 // A thread packs EL consecutive elements of one vector into one dword: 2 words (c - 32768), 4 bytes
-// (c - 128) or 8 nibbles.
+// (c - 128), 8 nibbles, 16 two-bit or 32 one-bit codes (element e of the dword at bit e * B).
 template <int DT>
 __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restrict__ P, int64_t D, int64_t ldp,
                                                            uint8_t* __restrict__ codes, int64_t ld,
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
         }
         if constexpr (DT == TWA_U16MM) word |= ((c ^ 0x8000u) & 0xffffu) << (16 * e);   // c - 32768 as int16
         else if constexpr (DT == TWA_U8MM) word |= ((c ^ 0x80u) & 0xffu) << (8 * e);      // c - 128 as int8
-        else word |= (c & 0xfu) << (4 * e);                                          // even element in the low nibble
+        else word |= (c & ((1u << Store<DT>::kBitsPerElem) - 1u)) << (Store<DT>::kBitsPerElem * e);   // low bits first
       }
     } else if constexpr (DT == TWA_U8MM) {
       word = 0x80808080u;                       // padding: code 0
@@ -161,19 +161,21 @@ int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const 
   const int cus = device_cus();
   hipLaunchKernelGGL(layer_minmax_kernel, dim3(cus * 4), dim3(256), 0, st, P, D, n, ldp, plan, keys);
   hipLaunchKernelGGL(layer_factors_kernel, dim3(lgrid), dim3(256), 0, st, keys, L, levels, ab, a64);
-  const int el = dtype == TWA_U16MM ? 2 : dtype == TWA_U8MM ? 4 : 8;
+  const int el = dtype == TWA_U16MM ? 2 : dtype == TWA_U8MM ? 4 : dtype == TWA_U4MM ? 8 : dtype == TWA_U2MM ? 16 : 32;
   const int64_t nvec = ld / el;
   int gx = (int)((nvec + 255) / 256);
   if (gx > cus * 8) gx = cus * 8;
-  if (dtype == TWA_U16MM)
-    hipLaunchKernelGGL(minmax_codes_kernel<TWA_U16MM>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L,
-                       ab, a64, levels);
-  else if (dtype == TWA_U8MM)
-    hipLaunchKernelGGL(minmax_codes_kernel<TWA_U8MM>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L,
-                       ab, a64, levels);
-  else
-    hipLaunchKernelGGL(minmax_codes_kernel<TWA_U4MM>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L,
-                       ab, a64, levels);
+#define TWA_CODES(DT_)                                                                                               \
+  hipLaunchKernelGGL(minmax_codes_kernel<DT_>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L, ab, \
+                     a64, levels)
+  switch (dtype) {
+    case TWA_U16MM: TWA_CODES(TWA_U16MM); break;
+    case TWA_U8MM: TWA_CODES(TWA_U8MM); break;
+    case TWA_U4MM: TWA_CODES(TWA_U4MM); break;
+    case TWA_U2MM: TWA_CODES(TWA_U2MM); break;
+    default: TWA_CODES(TWA_U1MM); break;
+  }
+#undef TWA_CODES
   return hip_check(hipGetLastError());
 }
 

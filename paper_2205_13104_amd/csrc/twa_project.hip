@@ -177,7 +177,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
           const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
-          raw[u][v] = ld128_stream(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
+          raw[u][v] = load_codes<DT>(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
           if constexpr (S::kScaled) {
             // scale index inside the tile's run of spans: [span][vector][block in span];
             // an unused column slot reads far outside the range and gets 0
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(256) void project_batched_kernel(PView P, const flo
         const int col = valid ? c0 + slot : 0;
         const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
         const uint32_t loc = (uint32_t)lane * EPV;
-        raw[u] = ld128_stream(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
+        raw[u] = load_codes<DT>(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
         if constexpr (S::kScaled) {
           const uint32_t soff = valid ? ((((uint32_t)col) << gshift) + ((in_span + loc) >> P.block_shift)) *
                                             (uint32_t)S::kScaleBytes
@@ -598,6 +598,8 @@ int launch_project_layers(const PView& P, int dtype, const float* g, const void*
     case TWA_U8MM: return launch_project_layers_dt<TWA_U8MM, 2>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     case TWA_U4MM: return launch_project_layers_dt<TWA_U4MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     case TWA_U16MM: return launch_project_layers_dt<TWA_U16MM, 2>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_U2MM: return launch_project_layers_dt<TWA_U2MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_U1MM: return launch_project_layers_dt<TWA_U1MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     default: return TWA_ERR_DTYPE;
   }
 }
