@@ -29,18 +29,24 @@ constexpr int kMaxBlocksPerWave = 9;          // 8*9/2 upper-triangular blocks o
 __device__ __forceinline__ int mfma_row_f32(int lane, int r) { return 4 * (lane >> 4) + r; }
 __device__ __forceinline__ int mfma_row_f64(int lane, int r) { return 4 * r + (lane >> 4); }
 
-// Stage rows [i0, i0+kTileRows) of all NP (padded) columns into LDS as tile[col*stride + row];
-// rows >= D and columns >= n are zero.
-template <int STRIDE>
-__device__ __forceinline__ void stage_tile(const float* __restrict__ W, int64_t ldw, int64_t D, int n, int NP,
-                                           int64_t i0, float* tile) {
+// A tile = rows [i0, i0+kTileRows) of all NP (padded) columns; rows >= D and columns >= n are zero.
+// It travels in two steps so that the loads of the NEXT tile are in flight while the matrix cores work
+// on the current one: global memory -> registers (fetch_tile), registers -> LDS as tile[col*stride + row]
+// (store_tile).  Without this the two workgroups of a compute unit fall into step -- both load, then both
+// compute -- and the matrix cores idle half of the time (Gram 9.5 ms -> see the measurements).
+constexpr int kTileQuads = TWA_MAX_N * (kTileRows / 4) / 256;    // float4 per thread for the widest matrix: 8
+
+__device__ __forceinline__ void fetch_tile(const float* __restrict__ W, int64_t ldw, int64_t D, int n, int NP,
+                                           int64_t i0, float4 (&pre)[kTileQuads]) {
   constexpr int V = kTileRows / 4;              // float4 per column
-  for (int idx = threadIdx.x; idx < NP * V; idx += blockDim.x) {
+#pragma unroll
+  for (int k = 0; k < kTileQuads; ++k) {
+    const int idx = threadIdx.x + 256 * k;
     const int col = idx / V;
     const int r4 = idx - col * V;
     const int64_t row = i0 + 4 * r4;
     float4 x = {0.f, 0.f, 0.f, 0.f};
-    if (col < n) {
+    if (idx < NP * V && col < n) {
       const float* p = W + (int64_t)col * ldw + row;
       if (row + 4 <= D) {
         x = *reinterpret_cast<const float4*>(p);
@@ -51,9 +57,23 @@ __device__ __forceinline__ void stage_tile(const float* __restrict__ W, int64_t 
         if (row + 3 < D) x.w = p[3];
       }
     }
-    float* t = tile + col * STRIDE + 4 * r4;
-    *reinterpret_cast<float2*>(t) = make_float2(x.x, x.y);
-    *reinterpret_cast<float2*>(t + 2) = make_float2(x.z, x.w);
+    pre[k] = x;
+  }
+}
+
+template <int STRIDE>
+__device__ __forceinline__ void store_tile(int NP, const float4 (&pre)[kTileQuads], float* tile) {
+  constexpr int V = kTileRows / 4;
+#pragma unroll
+  for (int k = 0; k < kTileQuads; ++k) {
+    const int idx = threadIdx.x + 256 * k;
+    if (idx < NP * V) {
+      const int col = idx / V;
+      const int r4 = idx - col * V;
+      float* t = tile + col * STRIDE + 4 * r4;
+      *reinterpret_cast<float2*>(t) = make_float2(pre[k].x, pre[k].y);
+      *reinterpret_cast<float2*>(t + 2) = make_float2(pre[k].z, pre[k].w);
+    }
   }
 }
 
@@ -83,9 +103,12 @@ __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ W, 
   int64_t c0, c1;
   split_range(nchunks, (int)gridDim.x, (int)blockIdx.x, c0, c1);
   const int m = lane & 15, kq = lane >> 4;
+  float4 pre[kTileQuads];
+  if (c0 < c1) fetch_tile(W, ldw, D, n, NP, c0 * kTileRows, pre);
   for (int64_t c = c0; c < c1; ++c) {
-    stage_tile<kGramStride>(W, ldw, D, n, NP, c * kTileRows, tile);
+    store_tile<kGramStride>(NP, pre, tile);
     __syncthreads();
+    if (c + 1 < c1) fetch_tile(W, ldw, D, n, NP, (c + 1) * kTileRows, pre);     // in flight during the products
 #pragma unroll 4
     for (int kk = 0; kk < kTileRows / 4; ++kk) {
 #pragma unroll
@@ -150,10 +173,15 @@ __global__ __launch_bounds__(256) void apply_rinv_kernel(const float* __restrict
   const int64_t nchunks = (D + kTileRows - 1) / kTileRows;
   int64_t c0, c1;
   split_range(nchunks, (int)gridDim.x, (int)blockIdx.x, c0, c1);
+  float4 pre[kTileQuads];
+  if (c0 < c1) fetch_tile(W, ldw, D, n, NP, c0 * kTileRows, pre);
   for (int64_t c = c0; c < c1; ++c) {
     const int64_t i0 = c * kTileRows;
-    stage_tile<kApplyStride>(W, ldw, D, n, NP, i0, tile);
+    store_tile<kApplyStride>(NP, pre, tile);
     __syncthreads();
+    // the next tile's rows are other rows than this tile's, which are the only ones written below:
+    // fetching them now is safe also when Q overwrites W
+    if (c + 1 < c1) fetch_tile(W, ldw, D, n, NP, (c + 1) * kTileRows, pre);
     f32x4 acc[2][RG];
 #pragma unroll
     for (int jbi = 0; jbi < 2; ++jbi)
