@@ -66,9 +66,10 @@ typedef enum twa_dtype {
      `scales` of the descriptor points to the 2L floats a_0, b_0, a_1, b_1, ...; `block` and
      `gscale` are ignored.  Only the layer-wise calls accept these (with the plan of the same
      layer table the matrix was quantised with).                                               */
-  TWA_U8MM = 4, /* B = 8: the byte holds c - 128 as a two's-complement int8                      */
+  TWA_U8MM = 4, /* B <= 8: the byte holds c - 2^(B-1) as a two's-complement int8; the descriptor's
+                   `block` field carries B (0 means 8)                                           */
   TWA_U4MM = 5, /* B = 4: two codes per byte, element i in the LOW nibble when i is even         */
-  TWA_U16MM = 6, /* B = 16: the 16-bit word holds c - 32768 as a two's-complement int16          */
+  TWA_U16MM = 6, /* B <= 16: the 16-bit word holds c - 2^(B-1) as an int16; `block` carries B (0: 16) */
   TWA_U2MM = 7,  /* B = 2: four codes per byte, element i in bits 2*(i mod 4) .. 2*(i mod 4)+1    */
   TWA_U1MM = 8   /* B = 1: eight codes per byte, element i in bit i mod 8                         */
 } twa_dtype;
@@ -245,13 +246,13 @@ int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan
  * gives c = 0; the factors are stored rounded to binary32 (b_l exactly).  The stored value is
  * within a_l/2 of p.
  *   bits [in]     B: 1 with out->dtype TWA_U1MM, 1..2 with TWA_U2MM, 1..4 with TWA_U4MM, 1..8 with
- *                 TWA_U8MM, 16 with TWA_U16MM.  The paper studies B in {1, 2, 3, 4, 8, 16}: each has a
+ *                 TWA_U8MM, 1..16 with TWA_U16MM.  The paper studies B in {1, 2, 3, 4, 8, 16}: each has a
  *                 container of its own except B = 3, which travels in nibbles.  Codes of fewer bits than
  *                 the container holds are stored in it (same values and factors as B-bit storage would
- *                 give, without the extra saving of memory).  B = 9..15 is not provided: the stored word
- *                 c - 32768 is centred only when the codes fill it, and the fused dequantisation relies
- *                 on that.
- *   out  [in/out] one of the TWA_U*MM types; data and scales (2L floats) allocated by the caller
+ *                 give, without the extra saving of memory); bytes and words hold them centred,
+ *                 c - 2^(B-1), so that the fused dequantisation loses no bits to cancellation.
+ *   out  [in/out] one of the TWA_U*MM types; data and scales (2L floats) allocated by the caller;
+ *                 on return out->block = B, which the step calls read from the descriptor
  *                 (twa_pmat_bytes gives ld and the data size; it reports 0 scale bytes for these
  *                 types since it does not know L).
  *   ws, ws_bytes  device workspace of at least twa_quantize_minmax_workspace_bytes(L).

@@ -29,10 +29,9 @@ def to_oracle(pm, cols=None, layer_off=None) -> orc.Pmat:
             codes = np.empty((b.shape[0], per * b.shape[1]), dtype=np.uint16)
             for k in range(per):
                 codes[:, k::per] = (b >> (bits * k)) & ((1 << bits) - 1)
-        elif pm.dtype == U16MM:
-            codes = (raw.astype(np.int32) + 32768).astype(np.uint16)          # the word holds code - 32768
-        elif pm.dtype == U8MM:
-            codes = (raw.astype(np.int16) + 128).astype(np.uint16)            # the byte holds code - 128
+        elif pm.dtype in (U16MM, U8MM):
+            B = pm.block or (16 if pm.dtype == U16MM else 8)                   # bits of the codes
+            codes = (raw.astype(np.int32) + (1 << (B - 1))).astype(np.uint16)  # the container holds code - 2^(B-1)
         else:
             b = raw.astype(np.uint16)
             codes = np.empty((b.shape[0], 2 * b.shape[1]), dtype=np.uint16)

@@ -310,17 +310,17 @@ def expand_update_layers(P: Pmat, S: torch.Tensor, plan: LayerPlan, w: torch.Ten
 
 
 def quantize_minmax(P: torch.Tensor, D: int, plan: LayerPlan, bits: int = 4) -> Pmat:
-    """twa_quantize_minmax: the paper's per-layer min-max format (Sec. 4.6), B = 1..8 or 16 bits, in the
-    smallest container that holds them (1 and 2 bits packed, up to 4 in nibbles, up to 8 in bytes, 16 in words)."""
+    """twa_quantize_minmax: the paper's per-layer min-max format (Sec. 4.6), B = 1..16 bits, in the
+    smallest container that holds them (1 and 2 bits packed, up to 4 in nibbles, up to 8 in bytes, else words)."""
     assert P.dtype == torch.float32 and P.dim() == 2 and P.is_contiguous() and plan.D == D
-    assert 1 <= bits <= 8 or bits == 16
+    assert 1 <= bits <= 16
     dtype = U1MM if bits == 1 else U2MM if bits == 2 else U4MM if bits <= 4 else U8MM if bits <= 8 else U16MM
     n, ldp = P.shape
     ld, _, _ = pmat_bytes(dtype, D, n)
     cols = ld * BITS_OF[dtype] // 8 if BITS_OF[dtype] < 8 else ld
     data = torch.empty((n, cols), dtype=_TORCH_OF[dtype], device=P.device)
     ab = torch.empty((plan.L, 2), dtype=torch.float32, device=P.device)
-    out = Pmat(dtype, D, n, ld, data, ab, 0, 1.0)
+    out = Pmat(dtype, D, n, ld, data, ab, bits, 1.0)       # block carries B for these types
     nb = C.c_size_t()
     _check(lib().twa_quantize_minmax_workspace_bytes(plan.L, C.byref(nb)), "twa_quantize_minmax_workspace_bytes")
     ws = Workspace(int(nb.value) + 8, device=P.device)

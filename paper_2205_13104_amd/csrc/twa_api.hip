@@ -86,9 +86,16 @@ static int view_of(const twa_pmat* P, PView* v) {
   if (!aligned16(P->data)) return TWA_ERR_ALIGN;
   int shift = 0;
   float gscale = 1.0f;
+  float code_bias = 0.0f;
   if (minmax(P->dtype)) {
     if (!P->scales) return TWA_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(P->scales) & 7u) return TWA_ERR_ALIGN;
+    if (P->dtype == TWA_U8MM || P->dtype == TWA_U16MM) {
+      // `block` holds B, the bits of the codes (0: as many as the container has); the container holds c - 2^(B-1)
+      const int B = P->block ? P->block : bits;
+      if (B < 1 || B > bits) return TWA_ERR_SHAPE;
+      code_bias = (float)(1 << (B - 1));
+    }
   }
   if (scaled(P->dtype)) {
     if (!P->scales) return TWA_ERR_NULL;
@@ -109,6 +116,7 @@ static int view_of(const twa_pmat* P, PView* v) {
   v->n = P->n;
   v->block_shift = shift;
   v->gscale = gscale;
+  v->code_bias = code_bias;
   return TWA_OK;
 }
 
@@ -391,8 +399,6 @@ int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const
   if (!P || !out || !out->data || !out->scales) return TWA_ERR_NULL;
   if (!minmax(out->dtype)) return TWA_ERR_DTYPE;
   if (bits < 1 || bits > bits_of(out->dtype)) return TWA_ERR_SHAPE;
-  // (a 16-bit word holds c - 32768: centred only when the codes use the whole word)
-  if (out->dtype == TWA_U16MM && bits != 16) return TWA_ERR_SHAPE;
   if (out->D != D || out->n != n) return TWA_ERR_SHAPE;
   int rc = check_dims(D, n, ldp, TWA_F32);
   if (rc != TWA_OK) return rc;
@@ -404,6 +410,7 @@ int twa_quantize_minmax(const float* P, int64_t D, int32_t n, int64_t ldp, const
   if (!ws || ws_bytes < minmax_workspace_bytes(L)) return TWA_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 7u) return TWA_ERR_ALIGN;
   if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  out->block = bits;                       // the descriptor remembers B (the byte and word containers need it)
   return launch_quantize_minmax(P, D, n, ldp, plan, L, out->dtype, bits, static_cast<uint8_t*>(out->data), out->ld,
                                 static_cast<float*>(out->scales), ws, static_cast<hipStream_t>(stream));
 }

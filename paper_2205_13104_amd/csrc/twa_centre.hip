@@ -170,7 +170,7 @@ int launch_centre_normalise(const float* W, int64_t D, int n, int64_t ldw, const
                      lde);
   int rc = hip_check(hipGetLastError());
   if (rc != TWA_OK) return rc;
-  PView v{reinterpret_cast<const uint8_t*>(E), nullptr, D, lde, n, 0, 1.0f};
+  PView v{reinterpret_cast<const uint8_t*>(E), nullptr, D, lde, n, 0, 1.0f, 0.0f};
   rc = launch_layer_squares(v, plan_dev, L, Q, partial, max_grid, st);
   if (rc != TWA_OK) return rc;
   const int64_t count = (int64_t)L * n;

@@ -123,10 +123,9 @@ template <> struct Store<TWA_U1MM> {
 template <int DT>
 constexpr bool kMinMax = DT == TWA_U8MM || DT == TWA_U4MM || DT == TWA_U16MM || DT == TWA_U2MM || DT == TWA_U1MM;
 template <int DT> constexpr bool kNibbles = DT == TWA_I4 || DT == TWA_U4MM;
-// decoded code = c - kCodeBias<DT> for the min-max formats
-template <int DT> constexpr float kCodeBias = DT == TWA_U8MM ? 128.0f : DT == TWA_U16MM ? 32768.0f : 0.0f;
-// what the stored integer lacks of the code: the above, and 8 for nibbles (which the kernels decode as code + 8 - 8)
-template <int DT> constexpr float kStoredBias = kNibbles<DT> ? 8.0f : kCodeBias<DT>;
+// (The byte and word containers of the min-max formats hold c - 2^(B-1) for B-bit codes c: centred
+// whatever B is, so that the fused dequantisation does not lose bits to cancellation.  The bias travels
+// in the view, PView::code_bias.  Nibbles and narrower hold c itself.)
 
 // Decode one 128-bit vector into kEPV "raw" floats: the stored value up to the per-block
 // scale, and for I4 up to the bias and nibble position:
@@ -275,6 +274,7 @@ struct PView {
   int32_t n;
   int32_t block_shift;   // log2(block)
   float gscale;
+  float code_bias;       // TWA_U8MM, TWA_U16MM: 2^(B-1), what the stored integer lacks of the code; else 0
 };
 
 // Layer-wise processing (Sec. 4.5): the tiles of the step kernels are cut per layer.  Layer l =

@@ -332,7 +332,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
       if constexpr (kMinMax<DT>) {
         const float* ab = reinterpret_cast<const float*>(P.scales) + 2 * (int64_t)c;
         ma = ab[0];
-        mb = ab[1] + kCodeBias<DT> * ma;
+        mb = ab[1] + P.code_bias * ma;
       }
       return Where{e0, (uint32_t)lo, (uint32_t)hi, s + (int64_t)c * P.n, ma, mb};
     } else {

@@ -100,14 +100,15 @@ __global__ __launch_bounds__(256) void layer_factors_kernel(const uint32_t* __re
   a64[l] = a;
 }
 
-// A thread packs EL consecutive elements of one vector into one dword: 2 words (c - 32768), 4 bytes
-// (c - 128), 8 nibbles, 16 two-bit or 32 one-bit codes (element e of the dword at bit e * B).
+// A thread packs EL consecutive elements of one vector into one dword: 2 words or 4 bytes holding
+// c - half (half = 2^(B-1): centred whatever B is), or 8 nibbles, 16 two-bit or 32 one-bit codes c
+// (element e of the dword at bit e * width).
 template <int DT>
 __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restrict__ P, int64_t D, int64_t ldp,
                                                            uint8_t* __restrict__ codes, int64_t ld,
                                                            const int64_t* __restrict__ off, int L,
                                                            const float* __restrict__ ab,
-                                                           const double* __restrict__ a64, double levels) {
+                                                           const double* __restrict__ a64, double levels, uint32_t half) {
   constexpr int EL = 32 / Store<DT>::kBitsPerElem;
   const int j = blockIdx.y;
   const int64_t nvec = ld / EL;
@@ -135,14 +136,14 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
           q = q < 0.0 ? 0.0 : (q > levels ? levels : q);
           c = (uint32_t)q;
         }
-        if constexpr (DT == TWA_U16MM) word |= ((c ^ 0x8000u) & 0xffffu) << (16 * e);   // c - 32768 as int16
-        else if constexpr (DT == TWA_U8MM) word |= ((c ^ 0x80u) & 0xffu) << (8 * e);      // c - 128 as int8
+        if constexpr (DT == TWA_U16MM) word |= ((c - half) & 0xffffu) << (16 * e);      // two's complement int16
+        else if constexpr (DT == TWA_U8MM) word |= ((c - half) & 0xffu) << (8 * e);       // two's complement int8
         else word |= (c & ((1u << Store<DT>::kBitsPerElem) - 1u)) << (Store<DT>::kBitsPerElem * e);   // low bits first
       }
     } else if constexpr (DT == TWA_U8MM) {
-      word = 0x80808080u;                       // padding: code 0
+      word = ((0u - half) & 0xffu) * 0x01010101u;      // padding: code 0
     } else if constexpr (DT == TWA_U16MM) {
-      word = 0x80008000u;
+      word = ((0u - half) & 0xffffu) * 0x00010001u;
     }
     out[vec] = word;
   }
@@ -167,7 +168,7 @@ int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const 
   if (gx > cus * 8) gx = cus * 8;
 #define TWA_CODES(DT_)                                                                                               \
   hipLaunchKernelGGL(minmax_codes_kernel<DT_>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L, ab, \
-                     a64, levels)
+                     a64, levels, 1u << (bits - 1))
   switch (dtype) {
     case TWA_U16MM: TWA_CODES(TWA_U16MM); break;
     case TWA_U8MM: TWA_CODES(TWA_U8MM); break;

@@ -567,7 +567,9 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   int rc = launch_project_dt<DT, 1, VPL, true>(P, g, 0, 1, partial, max_grid, &grid, st, plan, partial_g);
   if (rc != TWA_OK) return rc;
   hipLaunchKernelGGL(project_layers_reduce_kernel<kMinMax<DT>>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial,
-                     partial_g, P.n, plan, grid, reinterpret_cast<const float*>(P.scales), kStoredBias<DT>,
+                     partial_g, P.n, plan, grid, reinterpret_cast<const float*>(P.scales),
+                     kNibbles<DT> ? 8.0f : P.code_bias,   // (nibbles are decoded as code + 8 - 8)
+                    
                      S, bs);
   return hip_check(hipGetLastError());
 }

@@ -72,7 +72,7 @@ def test_project_argument_errors():
     assert _project(_pm(data=0)) == twa.ERR_NULL
     assert _project(_pm(), g=0) == twa.ERR_NULL
     assert _project(_pm(), s=0) == twa.ERR_NULL
-    assert _project(_pm(dtype=9)) == twa.ERR_DTYPE
+    assert _project(_pm(dtype=99)) == twa.ERR_DTYPE
     assert _project(_pm(n=0)) == twa.ERR_SHAPE
     assert _project(_pm(n=129)) == twa.ERR_SHAPE
     assert _project(_pm(D=0)) == twa.ERR_SHAPE
@@ -149,6 +149,8 @@ def test_layerwise_entry_points_argument_errors():
     # the paper's min-max format: layer-wise calls only, factors required
     mm = _pm(dtype=twa.U4MM, ld=2048, scales=0)
     assert L.twa_project_layers(C.byref(mm), 0x2000, 0x9000, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_NULL
+    mm = _pm(dtype=twa.U8MM, ld=2048, scales=0x5000, block=9)            # a byte holds codes of at most 8 bits
+    assert L.twa_project_layers(C.byref(mm), 0x2000, 0x9000, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_SHAPE
     mm = _pm(dtype=twa.U4MM, ld=1024, scales=0x5000)
     assert L.twa_project_layers(C.byref(mm), 0x2000, 0x9000, 2, 0x3000, 0x4000, wsb, None) == twa.ERR_ALIGN
     out = _pm(dtype=twa.I8, block=128, scales=0x5000, ld=2048)
@@ -161,7 +163,6 @@ def test_layerwise_entry_points_argument_errors():
     assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 5, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
     out = _pm(dtype=twa.U16MM, scales=0x5000, ld=2048)
     assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 17, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
-    assert L.twa_quantize_minmax(0x6000, 1000, 4, 1024, 0x9000, 2, 12, C.byref(out), 0x4000, 1 << 20, None) == twa.ERR_SHAPE
     assert L.twa_centre_normalise(0x6000, 1000, 4, 1024, 0x9000, 2, None, 0x7000, 1024, None, 0x4000, 1 << 30,
                                   None) == twa.ERR_NULL
     assert L.twa_centre_normalise(0x6000, 1000, 4, 1000, 0x9000, 2, 0xa000, 0x7000, 1024, None, 0x4000, 1 << 30,

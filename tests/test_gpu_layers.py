@@ -131,7 +131,7 @@ def test_layer_rows_add_up_to_the_whole_model_projection():
 @pytest.mark.parametrize("bits,D,n", [(8, 70001, 7), (8, 300_017, 100), (8, 1_234_567, 33), (4, 70001, 7),
                                       (4, 300_017, 100), (4, 1_234_567, 33), (1, 300_017, 20), (2, 300_017, 20),
                                       (3, 70001, 7), (6, 70001, 7), (16, 70001, 7), (16, 300_017, 100),
-                                      (16, 1_234_567, 33),
+                                      (16, 1_234_567, 33), (12, 70001, 7), (9, 300_017, 20), (5, 300_017, 20),
                                       (2, 70001, 7), (2, 1_234_567, 100), (1, 70001, 7), (1, 1_234_567, 100)])
 def test_minmax_format_matches_oracle(bits, D, n):
     """The paper's own quantiser (Sec. 4.6): codes and factors bit-exact against the fp64 oracle, then the
