@@ -266,7 +266,7 @@ __host__ __device__ inline int pick_rounds(int64_t R, int max_grid, int most) {
 
 // One launch covers the `chunk`-th run of 4 * (HOLD + LH) * max_grid tiles (the last run is shorter).  In it
 // a wave owns `rounds` <= HOLD + LH tiles: tile index = first tile of the workgroup + 4*round + wave.  The
-// sums of the last HOLD of them are kept in registers, those of the one before in LDS (LH = 1), and all of
+// sums of the last HOLD of them are kept in registers, those of the LH before in LDS, and all of
 // them are written when the wave has finished reading.  (A matrix too long for that takes several
 // launches, one after the other: see launch_expand_cfg.)
 // LAYERED (Sec. 4.5): the tiles are cut per layer (see LayerPlan); a tile takes the coefficient row
@@ -340,11 +340,23 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
     }
   };
 
-  // ---- reading: the sums of the first round wait in LDS if the registers cannot take all rounds ...
+  // ---- reading: the sums of the first round(s) wait in LDS if the registers cannot take all rounds:
+  //      one tile in `lhold`, and with LH = 2 one more, the very first, in the wave's transposition buffer
+  //      (possible where that buffer is as large as a tile, VPL = 1) ...
+  static_assert(LH <= 1 || (LH == 2 && VPL == 1), "a second LDS tile lives in the transposition buffer");
   int cur = cur0;
-  const bool lds_tile = LH && rounds > HOLD && first < t_end;
-  if (lds_tile) {
+  const int nl = rounds > HOLD ? (rounds - HOLD < LH ? rounds - HOLD : LH) : 0;     // tiles that wait in LDS
+  const int64_t t_lds = first + 4 * (int64_t)(nl > 0 ? nl - 1 : 0);
+  const bool tb_tile = LH == 2 && nl == 2 && first < t_end;
+  const bool lds_tile = LH >= 1 && nl >= 1 && t_lds < t_end;
+  if (tb_tile) {
     const Where at = locate(first, cur);
+    float acc[VPL][EPV];
+    x.accumulate(at.e0, acc, at.sv, at.mm_a, at.mm_b);
+    x.rows_to_lds(acc[0], tbuf[wave]);
+  }
+  if (lds_tile) {
+    const Where at = locate(t_lds, cur);
     float acc[VPL][EPV];
     x.accumulate(at.e0, acc, at.sv, at.mm_a, at.mm_b);
 #pragma unroll
@@ -352,7 +364,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   }
   // ... those of the other rounds stay in registers.  (Every copy of the accumulation is ~5 KB of code:
   // a variant of this kernel that outgrew the instruction cache lost a quarter of its speed.)
-  const int reg0 = (LH && rounds > HOLD) ? 1 : 0;              // first round whose sums stay in registers
+  const int reg0 = nl;                                         // first round whose sums stay in registers
   float held[HOLD][VPL][EPV];
 #pragma unroll
   for (int i = 0; i < HOLD; ++i) {
@@ -365,14 +377,28 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   // ---- the burst, phase 1: the new weights are formed where the sums were (the same tiles again, found
   //      with a cursor of their own) ...
   int cur_w = cur0;
-  Where at_lds{0, 0u, 0u, nullptr, 0.0f, 0.0f};
+  Where at_tb{0, 0u, 0u, nullptr, 0.0f, 0.0f}, at_lds{0, 0u, 0u, nullptr, 0.0f, 0.0f};
+  if (tb_tile) {
+    at_tb = locate(first, cur_w);
+    u32x4 wv[VPL][EPV / 4];
+    x.load_w(at_tb.e0, wv);
+    wave_lds_sync();
+    x.update_rows_in_place(at_tb.e0, 0, tbuf[wave], wv[0], at_tb.lo, at_tb.hi);
+  }
   if (lds_tile) {
-    at_lds = locate(first, cur_w);
+    at_lds = locate(t_lds, cur_w);
     u32x4 wv[VPL][EPV / 4];
     x.load_w(at_lds.e0, wv);
     wave_lds_sync();
 #pragma unroll
     for (int v = 0; v < VPL; ++v) x.update_rows_in_place(at_lds.e0, v, lhold[wave][v], wv[v], at_lds.lo, at_lds.hi);
+  }
+  if (tb_tile) {
+    // the tile in the transposition buffer has to leave before the register tiles are transposed: its
+    // stores go out now (the one place where loads of w queue behind stores)
+    wave_lds_sync();
+    x.store_rows(at_tb.e0, 0, tbuf[wave], at_tb.lo, at_tb.hi);
+    wave_lds_sync();
   }
   int cur_s = cur_w;                                           // (a third walk, for the stores)
 #pragma unroll
@@ -440,7 +466,7 @@ static int launch_expand_any(const PView& P, int dtype, const float* s, const fl
     case TWA_F32: launch_expand_cfg<TWA_F32, 1, 8, 6, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
     case TWA_BF16: launch_expand_cfg<TWA_BF16, 2, 4, 6, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
     case TWA_I8: launch_expand_cfg<TWA_I8, 4, 2, 6, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
-    case TWA_I4: launch_expand_cfg<TWA_I4, 8, 1, 5, 1, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
+    case TWA_I4: launch_expand_cfg<TWA_I4, 8, 1, 5, 2, LAYERED>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L); break;
     case TWA_U8MM:
       if constexpr (LAYERED) {
         launch_expand_cfg<TWA_U8MM, 4, 2, 6, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
@@ -455,19 +481,19 @@ static int launch_expand_any(const PView& P, int dtype, const float* s, const fl
       return TWA_ERR_DTYPE;
     case TWA_U2MM:
       if constexpr (LAYERED) {
-        launch_expand_cfg<TWA_U2MM, 8, 1, 5, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        launch_expand_cfg<TWA_U2MM, 8, 1, 5, 2, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
         break;
       }
       return TWA_ERR_DTYPE;
     case TWA_U1MM:
       if constexpr (LAYERED) {
-        launch_expand_cfg<TWA_U1MM, 8, 1, 5, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        launch_expand_cfg<TWA_U1MM, 8, 1, 5, 2, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
         break;
       }
       return TWA_ERR_DTYPE;
     case TWA_U4MM:
       if constexpr (LAYERED) {
-        launch_expand_cfg<TWA_U4MM, 8, 1, 5, 1, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        launch_expand_cfg<TWA_U4MM, 8, 1, 5, 2, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
         break;
       }
       return TWA_ERR_DTYPE;
