@@ -382,3 +382,65 @@ def test_expand_in_several_launches(dtype, D):
     torch.cuda.synchronize()
     w2o = orc.weights_from_beta(po, S.cpu().numpy().astype(np.float64), off.numpy(), w0.cpu().numpy().astype(np.float64))
     assert rel_l2(w2.cpu().numpy(), w2o) <= REL_L2_TOL and torch.equal(wbar, w0)
+
+
+@pytest.mark.parametrize("dtype", [twa.F32, twa.I8, twa.I4], ids=["f32", "i8", "i4"])
+def test_expand_launch_partition_on_a_small_grid(dtype, monkeypatch):
+    """The cut of a vector into launches and of a launch into rounds, exercised with a grid of a few workgroups
+    so that short vectors already need several launches: every tile count around the capacity of one launch
+    (4 waves x 7 rounds x grid), remainders of every size, whole-model and layer-wise."""
+    n = 3
+    s = torch.tensor([0.7, -1.3, 0.2], device="cuda")
+    for grid in (1, 3):
+        monkeypatch.setenv("TWA_EXPAND_GRID", str(grid))
+        cap = 4 * 7 * grid                                    # tiles of 2048 elements one launch holds
+        for tiles in sorted({1, 2, 5, cap - 1, cap, cap + 1, cap + 4, 2 * cap - 3, 2 * cap, 2 * cap + 1, 3 * cap + 9}):
+            D = tiles * 2048 - 5
+            print("partition", dtype, "grid", grid, "tiles", tiles, flush=True)
+            pm = store_as(random_basis_like(D, n, seed=tiles), D, dtype)
+            po = to_oracle(pm)
+            w0 = synth.gradient(D, 0.05, seed=43, device="cuda")
+            w = w0.clone()
+            gt = torch.full((D,), float("nan"), device="cuda")
+            twa.expand_update(pm, s, w, 0.1, gt)
+            torch.cuda.synchronize()
+            wo = w0.cpu().numpy().astype(np.float64)
+            gto = orc.expand_update(po, s.cpu().numpy().astype(np.float64), wo, float(np.float32(0.1)), want_gt=True)
+            assert rel_l2(gt.cpu().numpy(), gto) <= REL_L2_TOL and rel_l2(w.cpu().numpy(), wo) <= REL_L2_TOL
+            # layer-wise over a ragged table: the device divides the plan's tiles with the same rule
+            off = synth.layer_offsets(synth.random_layer_sizes(D, 9, seed=tiles))
+            plan = twa.LayerPlan(off, D)
+            S = torch.randn((plan.L, n), generator=torch.Generator().manual_seed(tiles)).cuda()
+            w = w0.clone()
+            gt.fill_(float("nan"))
+            twa.expand_update_layers(pm, S, plan, w, 0.1, gt)
+            torch.cuda.synchronize()
+            wo = w0.cpu().numpy().astype(np.float64)
+            gto = orc.expand_update_layers(po, S.cpu().numpy().astype(np.float64), off.numpy(), wo,
+                                           float(np.float32(0.1)), want_gt=True)
+            assert rel_l2(gt.cpu().numpy(), gto) <= REL_L2_TOL and rel_l2(w.cpu().numpy(), wo) <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("dtype", [twa.F32, twa.I8, twa.I4], ids=["f32", "i8", "i4"])
+def test_project_tile_division_on_a_small_grid(dtype, monkeypatch):
+    """The division of the tiles over the workgroups of the projection (and the per-layer slots of its partial
+    sums), exercised with a grid of a few workgroups: many tiles per workgroup, workgroups without tiles."""
+    n = 5
+    for grid in (1, 3, 7):
+        monkeypatch.setenv("TWA_PROJECT_GRID", str(grid))
+        for tiles in (1, 2, grid, grid + 1, 5 * grid - 1, 11 * grid + 2):
+            D = tiles * 2048 - 3
+            print("division", dtype, "grid", grid, "tiles", tiles, flush=True)
+            pm = store_as(random_basis_like(D, n, seed=tiles + grid), D, dtype)
+            po = to_oracle(pm)
+            g = synth.gradient(D, 1e-2, seed=44, device="cuda")
+            s = twa.project(pm, g)
+            torch.cuda.synchronize()
+            so = orc.project(po, g.cpu().numpy().astype(np.float64))
+            assert rel_l2(s.cpu().numpy(), so) <= REL_L2_TOL
+            off = synth.layer_offsets(synth.random_layer_sizes(D, 9, seed=tiles))
+            plan = twa.LayerPlan(off, D)
+            S = twa.project_layers(pm, g, plan)
+            torch.cuda.synchronize()
+            So = orc.project_layers(po, g.cpu().numpy().astype(np.float64), off.numpy())
+            assert rel_l2(S.cpu().numpy(), So) <= REL_L2_TOL
