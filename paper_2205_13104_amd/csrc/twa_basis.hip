@@ -36,7 +36,7 @@ __device__ __forceinline__ int mfma_row_f64(int lane, int r) { return 4 * r + (l
 // compute -- and the matrix cores idle half of the time (Gram 9.5 ms -> see the measurements).
 constexpr int kTileQuads = TWA_MAX_N * (kTileRows / 4) / 256;    // float4 per thread for the widest matrix: 8
 
-__device__ __forceinline__ void fetch_tile(const float* __restrict__ W, int64_t ldw, int64_t D, int n, int NP,
+__device__ __forceinline__ void fetch_tile(const float* W, int64_t ldw, int64_t D, int n, int NP,
                                            int64_t i0, float4 (&pre)[kTileQuads]) {
   constexpr int V = kTileRows / 4;              // float4 per column
 #pragma unroll
@@ -148,8 +148,8 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restri
 // Q[:, j] = sum_{a <= j} W[:, a] * rinv[a][j];  rinv is NP x NP row major, zero outside the
 // upper triangle and outside n x n.  As an MFMA: D[m = j][n' = i] = sum_a A[m][a] B[a][n'] with
 // A = rinv^T (kept in registers for the wave's two column blocks) and B = the staged tile.
-__global__ __launch_bounds__(256) void apply_rinv_kernel(const float* __restrict__ W, int64_t ldw,
-                                                         float* __restrict__ Q, int64_t ldq, int64_t D, int n,
+// (W and Q carry no no-alias promise: Q may be W.)
+__global__ __launch_bounds__(256) void apply_rinv_kernel(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n,
                                                          int NP, const float* __restrict__ rinv) {
   __shared__ float tile[TWA_MAX_N * kApplyStride];
   const int lane = threadIdx.x & (kWave - 1);
