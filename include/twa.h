@@ -21,7 +21,7 @@
  *   - Return value: TWA_OK (0) or a negative twa_status.  Argument errors are detected on
  *     the host before anything is enqueued (no GPU needed to get them).
  *   - Device base pointers must be 16-byte aligned; `ld` is a multiple of TWA_LD_MULTIPLE
- *     (fp32, bf16) or of TWA_SCALE_SPAN (int8, int4) elements.  Padding elements must hold finite
+ *     (fp32, bf16) or of TWA_SCALE_SPAN (every integer-code type) elements.  Padding elements must hold finite
  *     values (the library's own producers write zeros there).
  *   - Limits: 1 <= n <= TWA_MAX_N, 1 <= k <= TWA_MAX_K, 1 <= D, and D * (bytes per stored
  *     element) < 2^32 for one vector (D <= 1.07e9 for fp32).
@@ -39,7 +39,7 @@ extern "C" {
 #define TWA_MAX_N 128
 #define TWA_MAX_K 8
 #define TWA_LD_MULTIPLE 128   /* ld of fp32 / bf16 matrices is a multiple of this many elements   */
-#define TWA_SCALE_SPAN 2048   /* ld of int8 / int4 matrices is a multiple of this many elements   */
+#define TWA_SCALE_SPAN 2048   /* ld of integer-code matrices is a multiple of this many elements  */
 
 typedef enum twa_status {
   TWA_OK = 0,
@@ -77,7 +77,8 @@ typedef enum twa_dtype {
 /*
  * Descriptor of a stored projection matrix P (Sec. 4.2: P = [e_1 .. e_n]; Sec. 4.6 for the
  * integer forms).  Filled by the caller; passed by pointer; never retained.
- *   data   : n runs of `ld` elements (F32: 4 B, BF16: 2 B, I8: 1 B, I4: 1/2 B per element).
+ *   data   : n runs of `ld` elements (F32: 4 B, BF16: 2 B, I8: 1 B, I4: 1/2 B per element; the min-max
+ *            types: their container width, see twa_dtype).
  *   scales : one scale per block; I8: float, I4: binary16 bits (uint16_t); NULL for F32/BF16.
  *            Block b of vector j covers elements [b*block, min((b+1)*block, D)) of THAT
  *            vector.  Storage is "span interleaved": with G = TWA_SCALE_SPAN/block, the scale
@@ -87,7 +88,9 @@ typedef enum twa_dtype {
  *            reads the scales of all vectors in one contiguous run.  (The paper keeps one
  *            scale pair per layer, Sec. 4.6; the per-block grouping is the finer-grained form
  *            of the benchmark configuration.)
- *   block  : power of two in {32, 64, 128, 256} (I8, I4); ignored for F32/BF16.
+ *   block  : power of two in {32, 64, 128, 256} (I8, I4); ignored for F32/BF16.  For TWA_U8MM and
+ *            TWA_U16MM: B, the bits of the codes (0 = the container's width); ignored by the
+ *            narrower min-max types.
  *   gscale : I4 only: a power of two multiplying every binary16 scale so that the scales of
  *            a matrix with tiny entries (|p| ~ D^-1/2) stay normal binary16 numbers.
  */
