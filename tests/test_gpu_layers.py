@@ -100,6 +100,18 @@ def test_layers_n128_many_workgroups(dtype):
     check_layers(D, 128, dtype, "random40", synth.random_layer_sizes(D, 40, seed=3), seed=77)
 
 
+@pytest.mark.parametrize("dtype", [twa.F32, twa.I8, twa.I4], ids=["f32", "i8", "i4"])
+def test_the_largest_layer_table(dtype):
+    """TWA_MAX_LAYERS layers: mostly one to a few elements each, some empty, so that nearly every tile holds
+    the boundaries of hundreds of layers."""
+    D, n, L = 150_001, 5, 65536
+    gen = np.random.default_rng(12)
+    cuts = np.sort(gen.integers(0, D + 1, size=L - 1))
+    sizes = np.diff(np.concatenate([[0], cuts, [D]])).tolist()
+    assert len(sizes) == L and sum(sizes) == D
+    check_layers(D, n, dtype, "max", sizes, seed=5)
+
+
 @pytest.mark.parametrize("dtype", DTYPES, ids=[NAMES[d] for d in DTYPES])
 def test_one_layer_reproduces_the_whole_model_calls_bit_for_bit(dtype):
     D, n = 2_000_003, 100
