@@ -102,7 +102,12 @@ def main():
         P32, w, _ = twa.centre_normalise(W, D, plan, out=W, want_norms=False)     # w = wbar: Alg. 1 starts at the mean
         wbar = w.clone()
     else:
-        P32, _ = twa.build_basis(W, D, out=W, want_R=False)
+        if wl.name == "large":
+            # this configuration's basis is built from 16 M-row panels (the calls a caller uses whose checkpoints
+            # do not sit in memory at once; here they do, so the panels are views)
+            P32, _ = twa.build_basis_panels(W, D, 1 << 24, out=W)
+        else:
+            P32, _ = twa.build_basis(W, D, out=W, want_R=False)
     torch.cuda.synchronize()
     t2 = time.time()
     if dtype == twa.F32:

@@ -149,6 +149,29 @@ int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P,
                     double* R_host, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same construction for checkpoints whose rows arrive in panels (a matrix that is generated, read or
+ * kept elsewhere piece by piece: the benchmark's largest configuration streams 16 M-row panels).  A panel
+ * is rows [r0, r0 + rows) of all n vectors: pointer W + r0 with the matrix' stride.  One pass of
+ * CholeskyQR is
+ *     for every panel:  twa_gram_accumulate   G += W_panel^T W_panel   (fp64; accumulate = 0 on the first)
+ *     once:             twa_gram_factor       G = R^T R on the host, R^-1 to the device (synchronises)
+ *     for every panel:  twa_apply_rinv        P_panel = W_panel R^-1   (may overwrite W_panel)
+ * and twa_build_basis is two such passes (the second over P) with R = R_2 R_1 -- `compose` = 1 in the
+ * second twa_gram_factor forms that product in R_host.
+ *   gram, rinv, ws  device buffers of the sizes twa_basis_state_bytes reports (contents opaque).
+ *   W, P            fp32, 16-byte aligned, strides multiples of 4 elements and >= rows.  Elements outside
+ *                   the panel are neither read nor written (padding of P is the caller's to zero).
+ *   R_host          n*n doubles, row major, upper triangular; optional unless compose = 1.
+ * Errors as for twa_build_basis; on TWA_ERR_RANK R_host[0] holds the index of the dependent checkpoint.
+ */
+int twa_basis_state_bytes(int32_t n, size_t* gram_bytes, size_t* rinv_bytes, size_t* ws_bytes);
+int twa_gram_accumulate(const float* W, int64_t rows, int32_t n, int64_t ldw, double* gram, int32_t accumulate,
+                        void* ws, size_t ws_bytes, void* stream);
+int twa_gram_factor(const double* gram, int32_t n, float* rinv, double* R_host, int32_t compose, void* stream);
+int twa_apply_rinv(const float* W, int64_t rows, int32_t n, int64_t ldw, const float* rinv, float* P, int64_t ldp,
+                   void* stream);
+
+/*
  * Store an fp32 matrix in the form described by `out`  (Sec. 4.6: P as B-bit integers plus
  * scaling factors).  `out->dtype, n, D, ld, data, scales, block` are preset by the caller;
  * buffers sized per twa_pmat_bytes.  Exact recipe (each step ONE correctly rounded binary32

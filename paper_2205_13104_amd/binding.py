@@ -69,6 +69,10 @@ def lib():
         L.twa_project_workspace_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
         L.twa_build_basis_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
         L.twa_build_basis.argtypes = [vp, i64, i32, i64, vp, i64, vp, vp, C.c_size_t, vp]
+        L.twa_basis_state_bytes.argtypes = [i32, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.twa_gram_accumulate.argtypes = [vp, i64, i32, i64, vp, i32, vp, C.c_size_t, vp]
+        L.twa_gram_factor.argtypes = [vp, i32, vp, vp, i32, vp]
+        L.twa_apply_rinv.argtypes = [vp, i64, i32, i64, vp, vp, i64, vp]
         L.twa_quantize.argtypes = [vp, i64, i32, i64, C.POINTER(_Pmat), vp]
         L.twa_project.argtypes = [C.POINTER(_Pmat), vp, i32, i64, vp, vp, C.c_size_t, vp]
         L.twa_expand_update.argtypes = [C.POINTER(_Pmat), vp, vp, f32, vp, vp]
@@ -90,7 +94,8 @@ def lib():
         L.twa_weights_from_beta.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, vp, vp]
         for f in (L.twa_project_layers_workspace_bytes, L.twa_project_layers, L.twa_expand_update_layers,
                   L.twa_layer_plan_bytes, L.twa_layer_plan, L.twa_centre_normalise_workspace_bytes,
-                  L.twa_centre_normalise, L.twa_beta_update, L.twa_beta_optim, L.twa_weights_from_beta):
+                  L.twa_centre_normalise, L.twa_beta_update, L.twa_beta_optim, L.twa_weights_from_beta,
+                  L.twa_basis_state_bytes, L.twa_gram_accumulate, L.twa_gram_factor, L.twa_apply_rinv):
             f.restype = C.c_int
         for f in (L.twa_pmat_bytes, L.twa_project_workspace_bytes, L.twa_build_basis_workspace_bytes,
                   L.twa_build_basis, L.twa_quantize, L.twa_project, L.twa_expand_update):
@@ -407,4 +412,35 @@ def build_basis(W: torch.Tensor, D: int, out: Optional[torch.Tensor] = None, wan
     if rc == ERR_RANK and R is not None:
         raise TwaError(rc, "twa_build_basis", f"(checkpoint {int(R[0, 0].item())})")
     _check(rc, "twa_build_basis")
+    return P, R
+
+
+def build_basis_panels(W: torch.Tensor, D: int, panel_rows: int, out: Optional[torch.Tensor] = None):
+    """CholeskyQR2 through the panel calls (twa_gram_accumulate / twa_gram_factor / twa_apply_rinv): the rows of
+    W ((n, ldw) float32 device tensor) are visited `panel_rows` at a time.  Returns (P, R as (n, n) float64 CPU)."""
+    assert W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous() and panel_rows % 4 == 0
+    n, ldw = W.shape
+    P = torch.empty_like(W) if out is None else out
+    if P.data_ptr() != W.data_ptr():
+        P[:, D:].zero_()                               # the panel calls leave the padding alone
+    ldp = int(P.shape[1])
+    gb, rb, wb = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().twa_basis_state_bytes(n, C.byref(gb), C.byref(rb), C.byref(wb)), "twa_basis_state_bytes")
+    gram, rinv, ws = Workspace(gb.value, device=W.device), Workspace(rb.value, device=W.device), Workspace(wb.value, device=W.device)
+    R = torch.zeros((n, n), dtype=torch.float64)
+    src, lds = W, ldw
+    for p in range(2):
+        for k, r0 in enumerate(range(0, D, panel_rows)):
+            rows = min(panel_rows, D - r0)
+            _check(lib().twa_gram_accumulate(src.data_ptr() + 4 * r0, rows, n, lds, gram.ptr, 1 if k else 0, ws.ptr,
+                                             ws.nbytes, _stream()), "twa_gram_accumulate")
+        rc = lib().twa_gram_factor(gram.ptr, n, rinv.ptr, _ptr(R), p, _stream())
+        if rc == ERR_RANK:
+            raise TwaError(rc, "twa_gram_factor", f"(checkpoint {int(R[0, 0].item())})")
+        _check(rc, "twa_gram_factor")
+        for r0 in range(0, D, panel_rows):
+            rows = min(panel_rows, D - r0)
+            _check(lib().twa_apply_rinv(src.data_ptr() + 4 * r0, rows, n, lds, rinv.ptr, P.data_ptr() + 4 * r0, ldp,
+                                        _stream()), "twa_apply_rinv")
+        src, lds = P, ldp
     return P, R

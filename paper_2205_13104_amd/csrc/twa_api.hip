@@ -493,6 +493,53 @@ int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* ou
   return launch_quantize(P, D, n, ldp, *out, st);
 }
 
+// Workgroups of the two basis kernels for a run of `rows` rows.
+static int basis_grid(int64_t rows) {
+  const int cus = device_cus();
+  if (cus <= 0) return -1;
+  const int64_t nchunks = (rows + 63) / 64;
+  int grid = cus * env_int("TWA_BASIS_WGS_PER_CU", 2);
+  if (grid > kGramMaxGrid) grid = kGramMaxGrid;
+  if (grid > nchunks) grid = (int)nchunks;
+  return grid;
+}
+
+// Gram matrix (device, NP x NP doubles, upper blocks) -> host: R with G = R^T R, and R^-1 as NP x NP floats
+// on the device.  Synchronises the stream twice.  Returns TWA_ERR_RANK with *bad = index of the failing pivot.
+static int factor_gram(const double* gram_dev, int n, float* rinv_dev, std::vector<double>& R, int* bad,
+                       hipStream_t st) {
+  const int NP = (n + 15) / 16 * 16;
+  std::vector<double> gram_pad((size_t)NP * NP), G((size_t)n * n), X;
+  std::vector<float> rinv_pad((size_t)NP * NP, 0.0f);
+  int rc = hip_check(hipMemcpyAsync(gram_pad.data(), gram_dev, sizeof(double) * NP * NP, hipMemcpyDeviceToHost, st));
+  if (rc != TWA_OK) return rc;
+  rc = hip_check(hipStreamSynchronize(st));
+  if (rc != TWA_OK) return rc;
+  for (int i = 0; i < n; ++i)
+    for (int j = 0; j < n; ++j)
+      G[(size_t)i * n + j] = (j >= i) ? gram_pad[(size_t)i * NP + j] : gram_pad[(size_t)j * NP + i];
+  *bad = cholesky_upper(G, n, 1e-12, R);
+  if (*bad >= 0) return TWA_ERR_RANK;
+  invert_upper(R, n, X);
+  for (int i = 0; i < n; ++i)
+    for (int j = i; j < n; ++j) rinv_pad[(size_t)i * NP + j] = (float)X[(size_t)i * n + j];
+  rc = hip_check(hipMemcpyAsync(rinv_dev, rinv_pad.data(), sizeof(float) * NP * NP, hipMemcpyHostToDevice, st));
+  if (rc != TWA_OK) return rc;
+  return hip_check(hipStreamSynchronize(st));     // rinv_pad leaves scope
+}
+
+// Rtot <- R * Rtot (both n x n upper triangular, row major):  W = Q1 Rtot, Q1 = P R  ->  W = P (R Rtot)
+static void compose_upper(const std::vector<double>& R, std::vector<double>& Rtot, int n) {
+  std::vector<double> T((size_t)n * n, 0.0);
+  for (int i = 0; i < n; ++i)
+    for (int j = i; j < n; ++j) {
+      double v = 0.0;
+      for (int k = i; k <= j; ++k) v += R[(size_t)i * n + k] * Rtot[(size_t)k * n + j];
+      T[(size_t)i * n + j] = v;
+    }
+  Rtot.swap(T);
+}
+
 int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P, int64_t ldp, double* R_host,
                     void* ws, size_t ws_bytes, void* stream) {
   if (!W || !P) return TWA_ERR_NULL;
@@ -510,63 +557,101 @@ int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P,
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   const int NP = (n + 15) / 16 * 16;
-  const int cus = device_cus();
-  if (cus <= 0) return TWA_ERR_NO_DEVICE;
-  const int64_t nchunks = (D + 63) / 64;
-  int grid = cus * env_int("TWA_BASIS_WGS_PER_CU", 2);
-  if (grid > kGramMaxGrid) grid = kGramMaxGrid;
-  if (grid > nchunks) grid = (int)nchunks;
+  const int grid = basis_grid(D);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
   double* partial = static_cast<double*>(ws);
   double* gram_dev = partial + (size_t)kGramMaxGrid * NP * NP;
   float* rinv_dev = reinterpret_cast<float*>(gram_dev + (size_t)NP * NP);
 
-  std::vector<double> gram_pad((size_t)NP * NP), G((size_t)n * n), R, X, Rtot;
-  std::vector<float> rinv_pad((size_t)NP * NP);
+  std::vector<double> R, Rtot;
   const float* src = W;
   int64_t lds = ldw;
   for (int pass = 0; pass < 2; ++pass) {
-    rc = launch_gram(src, D, n, lds, partial, grid, gram_dev, st);
+    rc = launch_gram(src, D, n, lds, partial, grid, gram_dev, false, st);
     if (rc != TWA_OK) return rc;
-    rc = hip_check(hipMemcpyAsync(gram_pad.data(), gram_dev, sizeof(double) * NP * NP, hipMemcpyDeviceToHost, st));
+    int bad = -1;
+    rc = factor_gram(gram_dev, n, rinv_dev, R, &bad, st);
+    if (rc == TWA_ERR_RANK && R_host) R_host[0] = (double)bad;
     if (rc != TWA_OK) return rc;
-    rc = hip_check(hipStreamSynchronize(st));
+    rc = launch_apply_rinv(src, lds, P, ldp, D, n, rinv_dev, grid, true, st);
     if (rc != TWA_OK) return rc;
-    for (int i = 0; i < n; ++i)
-      for (int j = 0; j < n; ++j)
-        G[(size_t)i * n + j] = (j >= i) ? gram_pad[(size_t)i * NP + j] : gram_pad[(size_t)j * NP + i];
-    const int bad = cholesky_upper(G, n, 1e-12, R);
-    if (bad >= 0) {
-      if (R_host) R_host[0] = (double)bad;
-      return TWA_ERR_RANK;
-    }
-    invert_upper(R, n, X);
-    std::fill(rinv_pad.begin(), rinv_pad.end(), 0.0f);
-    for (int i = 0; i < n; ++i)
-      for (int j = i; j < n; ++j) rinv_pad[(size_t)i * NP + j] = (float)X[(size_t)i * n + j];
-    rc = hip_check(hipMemcpyAsync(rinv_dev, rinv_pad.data(), sizeof(float) * NP * NP, hipMemcpyHostToDevice, st));
-    if (rc != TWA_OK) return rc;
-    rc = hip_check(hipStreamSynchronize(st));     // rinv_pad is reused by the next pass
-    if (rc != TWA_OK) return rc;
-    rc = launch_apply_rinv(src, lds, P, ldp, D, n, rinv_dev, grid, st);
-    if (rc != TWA_OK) return rc;
-    if (pass == 0) {
-      Rtot = R;
-    } else {
-      // W = Q1 R1, Q1 = P R2  ->  W = P (R2 R1)
-      std::vector<double> T((size_t)n * n, 0.0);
-      for (int i = 0; i < n; ++i)
-        for (int j = i; j < n; ++j) {
-          double v = 0.0;
-          for (int k = i; k <= j; ++k) v += R[(size_t)i * n + k] * Rtot[(size_t)k * n + j];
-          T[(size_t)i * n + j] = v;
-        }
-      Rtot.swap(T);
-    }
+    if (pass == 0) Rtot = R;
+    else compose_upper(R, Rtot, n);
     src = P;
     lds = ldp;
   }
   if (R_host) memcpy(R_host, Rtot.data(), sizeof(double) * (size_t)n * n);
   return TWA_OK;
+}
+
+// ---- the same construction for checkpoints whose rows arrive in panels -------------------------
+
+int twa_basis_state_bytes(int32_t n, size_t* gram_bytes, size_t* rinv_bytes, size_t* ws_bytes) {
+  if (!gram_bytes || !rinv_bytes || !ws_bytes) return TWA_ERR_NULL;
+  if (n <= 0 || n > TWA_MAX_N) return TWA_ERR_SHAPE;
+  const size_t NP = (size_t)(n + 15) / 16 * 16;
+  *gram_bytes = NP * NP * sizeof(double);
+  *rinv_bytes = NP * NP * sizeof(float);
+  *ws_bytes = (size_t)kGramMaxGrid * NP * NP * sizeof(double);
+  return TWA_OK;
+}
+
+static int check_panel(const float* W, int64_t rows, int32_t n, int64_t ldw) {
+  if (!W) return TWA_ERR_NULL;
+  if (rows <= 0 || n <= 0 || n > TWA_MAX_N || ldw < rows || rows * 4 >= ((int64_t)1 << 32)) return TWA_ERR_SHAPE;
+  if (!aligned16(W) || ldw % 4 != 0) return TWA_ERR_ALIGN;
+  return TWA_OK;
+}
+
+int twa_gram_accumulate(const float* W, int64_t rows, int32_t n, int64_t ldw, double* gram, int32_t accumulate,
+                        void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_panel(W, rows, n, ldw);
+  if (rc != TWA_OK) return rc;
+  if (!gram) return TWA_ERR_NULL;
+  size_t gb = 0, rb = 0, wb = 0;
+  twa_basis_state_bytes(n, &gb, &rb, &wb);
+  if (!ws || ws_bytes < wb) return TWA_ERR_WORKSPACE;
+  if (!aligned16(ws) || !aligned16(gram)) return TWA_ERR_ALIGN;
+  const int grid = basis_grid(rows);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_gram(W, rows, n, ldw, static_cast<double*>(ws), grid, gram, accumulate != 0,
+                     static_cast<hipStream_t>(stream));
+}
+
+int twa_gram_factor(const double* gram, int32_t n, float* rinv, double* R_host, int32_t compose, void* stream) {
+  if (!gram || !rinv) return TWA_ERR_NULL;
+  if (n <= 0 || n > TWA_MAX_N) return TWA_ERR_SHAPE;
+  if (compose && !R_host) return TWA_ERR_NULL;
+  if (!aligned16(gram) || !aligned16(rinv)) return TWA_ERR_ALIGN;
+  if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  std::vector<double> R;
+  int bad = -1;
+  int rc = factor_gram(gram, n, rinv, R, &bad, static_cast<hipStream_t>(stream));
+  if (rc == TWA_ERR_RANK && R_host) R_host[0] = (double)bad;
+  if (rc != TWA_OK) return rc;
+  if (R_host) {
+    if (compose) {
+      std::vector<double> Rtot(R_host, R_host + (size_t)n * n);
+      compose_upper(R, Rtot, n);
+      memcpy(R_host, Rtot.data(), sizeof(double) * (size_t)n * n);
+    } else {
+      memcpy(R_host, R.data(), sizeof(double) * (size_t)n * n);
+    }
+  }
+  return TWA_OK;
+}
+
+int twa_apply_rinv(const float* W, int64_t rows, int32_t n, int64_t ldw, const float* rinv, float* P, int64_t ldp,
+                   void* stream) {
+  int rc = check_panel(W, rows, n, ldw);
+  if (rc != TWA_OK) return rc;
+  if (!rinv || !P) return TWA_ERR_NULL;
+  if (ldp < rows) return TWA_ERR_SHAPE;
+  if (!aligned16(P) || !aligned16(rinv) || ldp % 4 != 0) return TWA_ERR_ALIGN;
+  if (static_cast<const void*>(W) == static_cast<const void*>(P) && ldw != ldp) return TWA_ERR_SHAPE;
+  const int grid = basis_grid(rows);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_apply_rinv(W, ldw, P, ldp, rows, n, rinv, grid, false, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

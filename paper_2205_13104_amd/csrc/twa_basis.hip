@@ -134,15 +134,16 @@ __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ W, 
 }
 
 // gram[i*NP + j] = sum over workgroups in workgroup order (upper-triangular blocks only).
+// `accumulate`: the sum is added to what gram holds (rows that arrive in panels).
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ partial, int nparts, int NP,
-                                                          double* __restrict__ gram) {
+                                                          double* __restrict__ gram, int accumulate) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= NP * NP) return;
   const int i = idx / NP, j = idx - i * NP;
   double a = 0.0;
   if ((j >> 4) >= (i >> 4))
     for (int b = 0; b < nparts; ++b) a += partial[(int64_t)b * NP * NP + idx];
-  gram[idx] = a;
+  gram[idx] = accumulate ? gram[idx] + a : a;
 }
 
 // Q[:, j] = sum_{a <= j} W[:, a] * rinv[a][j];  rinv is NP x NP row major, zero outside the
@@ -230,18 +231,19 @@ __global__ __launch_bounds__(256) void zero_padding_kernel(float* __restrict__ Q
 }
 
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram,
-                hipStream_t st) {
+                bool accumulate, hipStream_t st) {
   const int NP = (n + 15) / 16 * 16;
   hipLaunchKernelGGL(gram_kernel, dim3(grid), dim3(256), 0, st, W, D, n, ldw, NP, partial);
-  hipLaunchKernelGGL(gram_reduce_kernel, dim3((NP * NP + 255) / 256), dim3(256), 0, st, partial, grid, NP, gram);
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3((NP * NP + 255) / 256), dim3(256), 0, st, partial, grid, NP, gram,
+                     accumulate ? 1 : 0);
   return hip_check(hipGetLastError());
 }
 
 int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
-                      int grid, hipStream_t st) {
+                      int grid, bool zero_padding, hipStream_t st) {
   const int NP = (n + 15) / 16 * 16;
   hipLaunchKernelGGL(apply_rinv_kernel, dim3(grid), dim3(256), 0, st, W, ldw, Q, ldq, D, n, NP, rinv_dev);
-  if (ldq > D) hipLaunchKernelGGL(zero_padding_kernel, dim3(1, n), dim3(256), 0, st, Q, D, ldq);
+  if (zero_padding && ldq > D) hipLaunchKernelGGL(zero_padding_kernel, dim3(1, n), dim3(256), 0, st, Q, D, ldq);
   return hip_check(hipGetLastError());
 }
 

@@ -175,3 +175,25 @@ def test_valid_call_without_a_gpu_fails_loudly():
         pytest.skip("a GPU is present")
     # every argument is acceptable, so the only thing missing is the device: no silent fallback
     assert _project(_pm()) == twa.ERR_NO_DEVICE
+
+
+def test_panel_calls_argument_errors():
+    L = twa.lib()
+    gb, rb, wb = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    assert L.twa_basis_state_bytes(100, C.byref(gb), C.byref(rb), C.byref(wb)) == twa.OK
+    assert gb.value == 112 * 112 * 8 and rb.value == 112 * 112 * 4 and wb.value == 512 * 112 * 112 * 8
+    assert L.twa_basis_state_bytes(129, C.byref(gb), C.byref(rb), C.byref(wb)) == twa.ERR_SHAPE
+    assert L.twa_basis_state_bytes(4, None, C.byref(rb), C.byref(wb)) == twa.ERR_NULL
+    big = 1 << 30
+    assert L.twa_gram_accumulate(None, 1000, 4, 1024, 0x2000, 0, 0x4000, big, None) == twa.ERR_NULL
+    assert L.twa_gram_accumulate(0x1000, 1000, 4, 1024, None, 0, 0x4000, big, None) == twa.ERR_NULL
+    assert L.twa_gram_accumulate(0x1000, 1000, 4, 999, 0x2000, 0, 0x4000, big, None) == twa.ERR_SHAPE     # stride < rows
+    assert L.twa_gram_accumulate(0x1000, 1000, 4, 1002, 0x2000, 0, 0x4000, big, None) == twa.ERR_ALIGN     # stride % 4
+    assert L.twa_gram_accumulate(0x1004, 1000, 4, 1024, 0x2000, 0, 0x4000, big, None) == twa.ERR_ALIGN
+    assert L.twa_gram_accumulate(0x1000, 1000, 4, 1024, 0x2000, 0, 0x4000, 64, None) == twa.ERR_WORKSPACE
+    assert L.twa_gram_factor(None, 4, 0x3000, None, 0, None) == twa.ERR_NULL
+    assert L.twa_gram_factor(0x2000, 4, 0x3000, None, 1, None) == twa.ERR_NULL                            # compose needs R
+    assert L.twa_gram_factor(0x2000, 0, 0x3000, None, 0, None) == twa.ERR_SHAPE
+    assert L.twa_apply_rinv(0x1000, 1000, 4, 1024, None, 0x5000, 1024, None) == twa.ERR_NULL
+    assert L.twa_apply_rinv(0x1000, 1000, 4, 1024, 0x3000, 0x5000, 996, None) == twa.ERR_SHAPE
+    assert L.twa_apply_rinv(0x1000, 1000, 4, 1024, 0x3000, 0x1000, 2048, None) == twa.ERR_SHAPE            # in place: same stride

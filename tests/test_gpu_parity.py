@@ -262,6 +262,35 @@ def test_build_basis_in_place_and_n1():
     assert rel_l2(P1[0, :D].cpu().numpy(), w1[0, :D].cpu().numpy().astype(np.float64) / nrm) <= 1e-6
 
 
+@pytest.mark.parametrize("name,D,n,panel", [("tiny", 200003, 10, 65536), ("cifar_resnet18", 60017, 100, 4096),
+                                            ("large", 300_011, 128, 100_000), ("tiny", 64, 5, 16)])
+def test_build_basis_from_panels_of_rows(name, D, n, panel):
+    """CholeskyQR2 with the rows arriving in panels (the largest configuration streams its checkpoints that way):
+    the same invariants, the same R as the fp64 oracle, and a basis that agrees with the one-shot call to the
+    rounding of a Gram matrix summed in another order."""
+    say("build_basis panels", name, D, n, panel)
+    wl = synth.WORKLOADS[name]
+    W = synth.checkpoints(wl, seed=1, device="cuda", D=D, n=n)
+    P, R = twa.build_basis_panels(W, D, panel)
+    Wh, Ph = _basis_checks(W, P, R, D, n)
+    assert not P[:, D:].any()
+    Po, Ro = orc.build_basis(Wh)
+    assert np.linalg.norm(R.numpy() - Ro) <= 1e-5 * np.linalg.norm(Ro)
+    P1, R1 = twa.build_basis(W, D)
+    assert np.linalg.norm(R.numpy() - R1.numpy()) <= 1e-6 * np.linalg.norm(R1.numpy())
+    # in place, panel by panel
+    W2 = W.clone()
+    P2, R2 = twa.build_basis_panels(W2, D, panel, out=W2)
+    assert P2.data_ptr() == W2.data_ptr() and torch.equal(P2[:, :D], P[:, :D]) and torch.equal(R2, R)
+    # a dependent checkpoint is reported by the factorisation
+    W3 = W.clone()
+    if n >= 5:
+        W3[4] = 0.25 * W3[1] - 3.0 * W3[2]
+        with pytest.raises(twa.TwaError) as ei:
+            twa.build_basis_panels(W3, D, panel)
+        assert ei.value.code == twa.ERR_RANK and "checkpoint 4" in str(ei.value)
+
+
 def test_build_basis_rank_deficient():
     D, n = 5000, 6
     W = random_basis_like(D, n, seed=8)
