@@ -205,6 +205,22 @@ def main():
                 "other_kernel": {"kernel": min(dur, key=dur.get), "avg_launch_ms": round(min(dur.values()), 5),
                                  "achieved": round(alg[min(dur, key=dur.get)] / (min(dur.values()) * 1e-3) / 1e9, 1)}}
 
+    # ---- the read ceiling of this device, measured: plain non-temporal reads over the stored codes ----
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    probe_buf = pm.data if pm.data.numel() * pm.data.element_size() >= (1 << 28) else torch.empty(1 << 28, dtype=torch.int32, device=dev).random_()
+    for _ in range(3):
+        twa.probe_read(probe_buf, sink)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(20):
+        twa.probe_read(probe_buf, sink)
+    c1.record()
+    torch.cuda.synchronize()
+    read_ceiling = 20 * probe_buf.numel() * probe_buf.element_size() / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    roofline["measured_read_ceiling_GBps"] = round(read_ceiling, 1)
+    roofline["frac_of_measured_read_ceiling"] = round(achieved / read_ceiling, 4)
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same stored P ---------
     cpu = None
     if not args.no_cpu_baseline:

@@ -367,6 +367,14 @@ int twa_beta_step(const twa_pmat* P, const float* g, const void* plan, int32_t L
 int twa_weights_from_beta(const twa_pmat* P, const float* beta, const void* plan, int32_t L, const float* wbar,
                           float* w, void* stream);
 
+/*
+ * Measurement aid, no part of the method: one plain pass of non-temporal 128-bit reads over `bytes` bytes
+ * (rounded down to 16) of `buf`, for callers that want the read ceiling of the device they run on next
+ * to the rates of the step kernels (the benchmark reports both).
+ *   buf  [in]  device, 16-byte aligned.     sink [out] device, 4 bytes; left alone in practice.
+ */
+int twa_probe_read(const void* buf, size_t bytes, uint32_t* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

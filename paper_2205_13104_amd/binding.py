@@ -69,6 +69,7 @@ def lib():
         L.twa_project_workspace_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
         L.twa_build_basis_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
         L.twa_build_basis.argtypes = [vp, i64, i32, i64, vp, i64, vp, vp, C.c_size_t, vp]
+        L.twa_probe_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.twa_basis_state_bytes.argtypes = [i32, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.twa_gram_accumulate.argtypes = [vp, i64, i32, i64, vp, i32, vp, C.c_size_t, vp]
         L.twa_gram_factor.argtypes = [vp, i32, vp, vp, i32, vp]
@@ -95,7 +96,8 @@ def lib():
         for f in (L.twa_project_layers_workspace_bytes, L.twa_project_layers, L.twa_expand_update_layers,
                   L.twa_layer_plan_bytes, L.twa_layer_plan, L.twa_centre_normalise_workspace_bytes,
                   L.twa_centre_normalise, L.twa_beta_update, L.twa_beta_optim, L.twa_weights_from_beta,
-                  L.twa_basis_state_bytes, L.twa_gram_accumulate, L.twa_gram_factor, L.twa_apply_rinv):
+                  L.twa_basis_state_bytes, L.twa_gram_accumulate, L.twa_gram_factor, L.twa_apply_rinv,
+                  L.twa_probe_read):
             f.restype = C.c_int
         for f in (L.twa_pmat_bytes, L.twa_project_workspace_bytes, L.twa_build_basis_workspace_bytes,
                   L.twa_build_basis, L.twa_quantize, L.twa_project, L.twa_expand_update):
@@ -444,3 +446,9 @@ def build_basis_panels(W: torch.Tensor, D: int, panel_rows: int, out: Optional[t
                                         _stream()), "twa_apply_rinv")
         src, lds = P, ldp
     return P, R
+
+
+def probe_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    """twa_probe_read: one plain read pass over `buf` (measurement aid)."""
+    assert buf.is_contiguous() and sink.numel() >= 1 and sink.element_size() == 4
+    _check(lib().twa_probe_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()), "twa_probe_read")

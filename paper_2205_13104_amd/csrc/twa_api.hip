@@ -586,6 +586,14 @@ int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P,
 
 // ---- the same construction for checkpoints whose rows arrive in panels -------------------------
 
+int twa_probe_read(const void* buf, size_t bytes, uint32_t* sink, void* stream) {
+  if (!buf || !sink) return TWA_ERR_NULL;
+  if (bytes < 16 || bytes / 65536 >= ((size_t)1 << 31)) return TWA_ERR_SHAPE;
+  if (!aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return TWA_ERR_ALIGN;
+  if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_read_probe(buf, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
 int twa_basis_state_bytes(int32_t n, size_t* gram_bytes, size_t* rinv_bytes, size_t* ws_bytes) {
   if (!gram_bytes || !rinv_bytes || !ws_bytes) return TWA_ERR_NULL;
   if (n <= 0 || n > TWA_MAX_N) return TWA_ERR_SHAPE;

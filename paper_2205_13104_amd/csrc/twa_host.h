@@ -59,4 +59,6 @@ int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, 
 int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
                       int grid, bool zero_padding, hipStream_t st);
 
+int launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st);
+
 }  // namespace twa

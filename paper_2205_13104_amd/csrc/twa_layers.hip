@@ -90,4 +90,23 @@ int launch_layer_plan(const int64_t* layer_off, int L, int64_t D, void* plan_dev
   return hip_check(hipGetLastError());
 }
 
+// Measurement aid: one plain pass of non-temporal 128-bit reads over a buffer, 64 KB per workgroup in the
+// order of the workgroup index -- the read ceiling of the device a benchmark runs on.  The XOR of the
+// words read goes to `sink` only if it has one improbable value, so the loads cannot be dropped.
+__global__ __launch_bounds__(256) void read_probe_kernel(const u32x4* __restrict__ p, int64_t nvec, uint32_t* sink) {
+  constexpr int64_t kPer = 65536 / 16;                     // 128-bit words per workgroup
+  const int64_t v0 = (int64_t)blockIdx.x * kPer;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (int64_t i = v0 + threadIdx.x; i < v0 + kPer && i < nvec; i += 256) acc ^= __builtin_nontemporal_load(p + i);
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) *sink = 1u;
+}
+
+int launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st) {
+  const int64_t nvec = (int64_t)(bytes / 16);
+  const int64_t grid = (nvec + 4095) / 4096;
+  hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)grid), dim3(256), 0, st, static_cast<const u32x4*>(buf), nvec,
+                     sink);
+  return hip_check(hipGetLastError());
+}
+
 }  // namespace twa

@@ -197,3 +197,11 @@ def test_panel_calls_argument_errors():
     assert L.twa_apply_rinv(0x1000, 1000, 4, 1024, None, 0x5000, 1024, None) == twa.ERR_NULL
     assert L.twa_apply_rinv(0x1000, 1000, 4, 1024, 0x3000, 0x5000, 996, None) == twa.ERR_SHAPE
     assert L.twa_apply_rinv(0x1000, 1000, 4, 1024, 0x3000, 0x1000, 2048, None) == twa.ERR_SHAPE            # in place: same stride
+
+
+def test_read_probe_argument_errors():
+    L = twa.lib()
+    assert L.twa_probe_read(None, 1 << 20, 0x2000, None) == twa.ERR_NULL
+    assert L.twa_probe_read(0x1000, 1 << 20, None, None) == twa.ERR_NULL
+    assert L.twa_probe_read(0x1000, 8, 0x2000, None) == twa.ERR_SHAPE
+    assert L.twa_probe_read(0x1008, 1 << 20, 0x2000, None) == twa.ERR_ALIGN
