@@ -201,7 +201,8 @@ def test_vit_b16_bf16_batched_full_size():
 
 
 def test_large_int4_int8_full_size():
-    """D = 350 M, n = 128: basis in place on the 179 GB checkpoint matrix, int4 and int8 storage, one step each."""
+    """D = 350 M, n = 128: basis in place on the 179 GB checkpoint matrix, built from 16 M-row panels as the
+    configuration says, int4 and int8 storage, one step each."""
     wl = synth.WORKLOADS["large"]
     D, n = wl.D, wl.n
     free, total = torch.cuda.mem_get_info()
@@ -211,7 +212,7 @@ def test_large_int4_int8_full_size():
     say("full size", wl.name, D, n, f"free {free / 2**30:.0f} GiB")
     W = synth.checkpoints(wl, seed=0, device="cuda")
     w = W[:, :D].mean(dim=0).contiguous()
-    P, R = twa.build_basis(W, D, out=W)
+    P, R = twa.build_basis_panels(W, D, 1 << 24, out=W)
     del W
     ortho = np.max(np.abs(gram_fp64(P, D) - np.eye(n)))
     say("  max|PtP-I|", ortho)
