@@ -362,8 +362,8 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
 #pragma unroll
     for (int v = 0; v < VPL; ++v) x.rows_to_lds(acc[v], lhold[wave][v]);
   }
-  // ... those of the other rounds stay in registers.  (Every copy of the accumulation is ~5 KB of code:
-  // a variant of this kernel that outgrew the instruction cache lost a quarter of its speed.)
+  // ... those of the other rounds stay in registers.  (Every copy of the accumulation is ~5 KB of code and
+  // the instruction cache holds 64 KB: one call site per phase, no more.)
   const int reg0 = nl;                                         // first round whose sums stay in registers
   float held[HOLD][VPL][EPV];
 #pragma unroll
