@@ -365,14 +365,17 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   // ... those of the other rounds stay in registers.  (Every copy of the accumulation is ~5 KB of code and
   // the instruction cache holds 64 KB: one call site per phase, no more.)
   const int reg0 = nl;                                         // first round whose sums stay in registers
+  // (The place of the NEXT tile is looked up before this tile is accumulated: layer-wise that is a chain of
+  //  scalar loads from the plan, which then has a whole tile's time to arrive.)
   float held[HOLD][VPL][EPV];
+  auto owned = [&](int i) { return i < HOLD && reg0 + i < rounds && first + 4 * (int64_t)(reg0 + i) < t_end; };
+  Where ahead{0, 0u, 0u, nullptr, 0.0f, 0.0f};
+  if (owned(0)) ahead = locate(first + 4 * (int64_t)reg0, cur);
 #pragma unroll
   for (int i = 0; i < HOLD; ++i) {
-    const int64_t t = first + 4 * (int64_t)(reg0 + i);
-    if (reg0 + i < rounds && t < t_end) {
-      const Where at = locate(t, cur);
-      x.accumulate(at.e0, held[i], at.sv, at.mm_a, at.mm_b);
-    }
+    const Where at = ahead;
+    if (owned(i + 1)) ahead = locate(first + 4 * (int64_t)(reg0 + i + 1), cur);
+    if (owned(i)) x.accumulate(at.e0, held[i], at.sv, at.mm_a, at.mm_b);
   }
   // ---- the burst, phase 1: the new weights are formed where the sums were (the same tiles again, found
   //      with a cursor of their own) ...
