@@ -269,3 +269,81 @@ def test_large_int4_int8_full_size():
         assert e_gt <= REL_L2_TOL and e_w <= REL_L2_TOL
         del pm, w1, gt, ws
         torch.cuda.empty_cache()
+
+
+def test_imagenet_resnet50_algorithm_1_minmax4_full_size():
+    """The paper's default configuration at the benchmark shape, as bench.py --mode layerwise --storage mm4 runs it:
+    layer-wise centre+normalise basis (Sec. 4.1, 4.5), 4-bit per-layer min-max codes (Sec. 4.6), coefficient step
+    with weight decay and w = wbar + P beta (Alg. 1).  Sampled: wbar and E on blocks, codes and factors of whole
+    layers through the oracle's quantiser, coefficient columns over all of D, w on blocks next to layer boundaries."""
+    wl = synth.WORKLOADS["imagenet_resnet50"]
+    D, n = wl.D, wl.n
+    off_cpu = synth.workload_layers(wl.name)
+    offs = off_cpu.numpy()
+    L = len(offs) - 1
+    say("full size, Alg. 1, 4-bit min-max", wl.name, D, n, "L", L)
+    W = synth.checkpoints(wl, seed=0, device="cuda")
+    plan = twa.LayerPlan(off_cpu, D)
+    # ---- basis: mean bit-exact and centred/normalised vectors within the bar, on sampled layers (whole layers)
+    sizes = np.diff(offs)
+    order = np.argsort(sizes)
+    layers = sorted(set(order[:6].tolist() + order[L // 2 - 2:L // 2 + 2].tolist() + [0, L - 1]
+                        + [int(np.argmin(np.abs(sizes - 590_000)))]))
+    W_host = {l: W[:, offs[l]:offs[l + 1]].cpu().numpy().astype(np.float64) for l in layers}
+    E, wbar, _ = twa.centre_normalise(W, D, plan, out=W, want_norms=False)
+    torch.cuda.synchronize()
+    for l in layers:
+        a, b = int(offs[l]), int(offs[l + 1])
+        Eo, wbo, _ = orc.centre_normalise_layers(W_host[l], np.array([0, b - a], dtype=np.int64))
+        assert np.array_equal(wbar[a:b].cpu().numpy(), wbo.astype(np.float32)), l
+        assert rel_l2(E[:, a:b].cpu().numpy(), Eo) <= REL_L2_TOL, l
+    # ---- 4-bit codes and factors of those layers, bit-exact
+    E_host = {l: E[:, offs[l]:offs[l + 1]].cpu().numpy().astype(np.float64) for l in layers}
+    pm = twa.quantize_minmax(E, D, plan, bits=4)
+    torch.cuda.synchronize()
+    ab = pm.scales.cpu().numpy()
+    for l in layers:
+        a, b = int(offs[l]), int(offs[l + 1])
+        co, ao, bo = orc.quantize_minmax(E_host[l], 4, np.array([0, b - a], dtype=np.int64))
+        idx = torch.arange(a, b, device="cuda")
+        by = pm.data[:, idx // 2]
+        codes = ((by >> (4 * (idx & 1)).to(torch.uint8)) & 0xF).cpu().numpy().astype(np.uint16)
+        assert np.array_equal(codes, co), l
+        assert ab[l, 0] == np.float32(ao[0]) and ab[l, 1] == np.float32(bo[0]), l
+    del W, E, W_host, E_host
+    torch.cuda.empty_cache()
+    # ---- one step of Alg. 1 from beta = 0
+    lr, lam = wl.lr, 1e-4
+    g = synth.gradient(D, wl.sigma_g, seed=0, step=0, device="cuda")
+    beta = torch.zeros((L, n), device="cuda")
+    S = torch.empty((L, n), device="cuda")
+    twa.beta_step(pm, g, plan, beta, lr, lam, S=S)
+    w = twa.weights_from_beta(pm, beta, plan, wbar)
+    torch.cuda.synchronize()
+    cols = [0, 57, n - 1]
+    So = orc.project_layers(to_oracle(pm, cols=cols, layer_off=offs), g.cpu().numpy().astype(np.float64), offs)
+    e_s = rel_l2(S[:, cols].cpu().numpy(), So)
+    say("  rel_l2 S[:, sampled]", e_s)
+    assert e_s <= REL_L2_TOL
+    beta_o = np.zeros((L, n))
+    orc.beta_step(beta_o, S.cpu().numpy().astype(np.float64), float(np.float32(lr)), float(np.float32(lam)))
+    assert rel_l2(beta.cpu().numpy(), beta_o) <= REL_L2_TOL
+    # w on sampled 128-element blocks: next to layer boundaries, first, last, random
+    block = 128
+    nb = D // block
+    r = np.random.default_rng(7)
+    near = [int(o) // block for o in offs[1:-1]] + [max(0, int(o) // block - 1) for o in offs[1:-1]]
+    ids = sorted(set([0, nb - 1] + r.integers(0, nb, size=48).tolist() + r.choice(near, size=40).tolist()))
+    rows = torch.cat([torch.arange(b * block, (b + 1) * block) for b in ids]).cuda()
+    by = pm.data[:, rows // 2]
+    codes = ((by >> (4 * (rows & 1)).to(torch.uint8)) & 0xF).cpu().numpy().astype(np.uint16)
+    rows_np = rows.cpu().numpy()
+    off_sub = np.searchsorted(rows_np, offs, side="left").astype(np.int64)
+    po = orc.Pmat(orc.MM, int(rows.numel()), np.ascontiguousarray(codes), np.ascontiguousarray(ab, dtype=np.float32), 0, 1.0,
+                  off_sub)
+    wo = orc.weights_from_beta(po, beta.cpu().numpy().astype(np.float64), off_sub, wbar[rows].cpu().numpy().astype(np.float64))
+    e_w = rel_l2(w[rows].cpu().numpy(), wo)
+    e_d = rel_l2((w[rows] - wbar[rows]).double().cpu().numpy(), wo - wbar[rows].cpu().numpy().astype(np.float64))
+    say("  rel_l2 w[sampled]", e_w, "displacement", e_d)
+    assert e_w <= REL_L2_TOL and e_d <= 2 * REL_L2_TOL
+    assert torch.isfinite(w).all()
