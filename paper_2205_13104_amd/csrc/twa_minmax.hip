@@ -82,9 +82,11 @@ __global__ __launch_bounds__(256) void layer_minmax_kernel(const float* __restri
   merge(lc.cur);
 }
 
-// ab[2l] = (float)a_l, ab[2l+1] = b_l; a64[l] = a_l in fp64.  An empty layer gets (0, 0).
+// ab[2l] = (float)a_l, ab[2l+1] = b_l; a64[l] = a_l in fp64 and ra64[l] = 1 / a_l (0 for a_l = 0).  An empty
+// layer gets (0, 0).
 __global__ __launch_bounds__(256) void layer_factors_kernel(const uint32_t* __restrict__ keys, int L, double levels,
-                                                            float* __restrict__ ab, double* __restrict__ a64) {
+                                                            float* __restrict__ ab, double* __restrict__ a64,
+                                                            double* __restrict__ ra64) {
   const int l = blockIdx.x * 256 + threadIdx.x;
   if (l >= L) return;
   const uint32_t kmin = keys[2 * l], kmax = keys[2 * l + 1];
@@ -98,77 +100,120 @@ __global__ __launch_bounds__(256) void layer_factors_kernel(const uint32_t* __re
   ab[2 * l] = (float)a;
   ab[2 * l + 1] = b;
   a64[l] = a;
+  ra64[l] = a > 0.0 ? 1.0 / a : 0.0;
 }
 
-// A thread packs EL consecutive elements of one vector into one dword: 2 words or 4 bytes holding
-// c - half (half = 2^(B-1): centred whatever B is), or 8 nibbles, 16 two-bit or 32 one-bit codes c
-// (element e of the dword at bit e * width).
+// A thread packs 4 * EL consecutive elements of one vector into four dwords (one 128-bit store); a dword
+// holds EL elements: 2 words or 4 bytes holding c - half (half = 2^(B-1): centred whatever B is), or 8
+// nibbles, 16 two-bit or 32 one-bit codes c (element e of the dword at bit e * width).  The layer of the
+// first element is found by bisection, once per thread and trip; after that the thread only watches for the
+// next boundary.
 template <int DT>
 __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restrict__ P, int64_t D, int64_t ldp,
                                                            uint8_t* __restrict__ codes, int64_t ld,
                                                            const int64_t* __restrict__ off, int L,
                                                            const float* __restrict__ ab,
-                                                           const double* __restrict__ a64, double levels, uint32_t half) {
-  constexpr int EL = 32 / Store<DT>::kBitsPerElem;
+                                                           const double* __restrict__ a64,
+                                                           const double* __restrict__ ra64, double levels,
+                                                           uint32_t half) {
+  constexpr int BITS = Store<DT>::kBitsPerElem;
+  constexpr int EL = 32 / BITS;                 // elements per dword
   const int j = blockIdx.y;
-  const int64_t nvec = ld / EL;
+  const int64_t nquad = ld / (4 * EL);          // 128-bit groups per vector (ld is a multiple of 2048)
   const float* p = P + (int64_t)j * ldp;
-  uint32_t* out = reinterpret_cast<uint32_t*>(codes + (((int64_t)j * ld * Store<DT>::kBitsPerElem) >> 3));
-  for (int64_t vec = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; vec < nvec;
-       vec += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t i0 = vec * EL;
-    uint32_t word = 0;
+  u32x4* out = reinterpret_cast<u32x4*>(codes + (((int64_t)j * ld * BITS) >> 3));
+  uint32_t pad = 0;                             // padding: code 0
+  if constexpr (DT == TWA_U8MM) pad = ((0u - half) & 0xffu) * 0x01010101u;
+  if constexpr (DT == TWA_U16MM) pad = ((0u - half) & 0xffffu) * 0x00010001u;
+  for (int64_t quad = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; quad < nquad;
+       quad += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i0 = quad * 4 * EL;
+    u32x4 words = {pad, pad, pad, pad};
     if (i0 < D) {
-      int a_ = 0, b_ = L - 1;                   // largest l with off[l] <= i0
-      while (a_ < b_) {
-        const int mid = (a_ + b_ + 1) >> 1;
-        if (off[mid] <= i0) a_ = mid; else b_ = mid - 1;
+      int lo = 0, hi = L - 1;                   // largest l with off[l] <= i0
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (off[mid] <= i0) lo = mid; else hi = mid - 1;
       }
-      int l = a_;
+      int l = lo;
+      int64_t next = l < L - 1 ? off[l + 1] : D;         // first element of the following layer
+      double a = a64[l], ra = ra64[l], b = (double)ab[2 * l + 1];
 #pragma unroll
-      for (int e = 0; e < EL; ++e) {
-        const int64_t i = i0 + e;
-        uint32_t c = 0;
-        if (i < D) {
-          while (l < L - 1 && off[l + 1] <= i) ++l;
-          const double a = a64[l], b = (double)ab[2 * l + 1];
-          double q = a > 0.0 ? rint(((double)p[i] - b) / a) : 0.0;
-          q = q < 0.0 ? 0.0 : (q > levels ? levels : q);
-          c = (uint32_t)q;
+      for (int w = 0; w < 4; ++w) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int e4 = 0; e4 < EL; e4 += 4) {
+          const int64_t i4 = i0 + w * EL + e4;
+          float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+          if constexpr (EL >= 4) {
+            if (i4 + 4 <= D) {
+              const float4 t = *reinterpret_cast<const float4*>(p + i4);
+              v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) v[r] = i4 + r < D ? p[i4 + r] : 0.0f;
+            }
+          } else {
+#pragma unroll
+            for (int r = 0; r < EL; ++r) v[r] = i4 + r < D ? p[i4 + r] : 0.0f;
+          }
+#pragma unroll
+          for (int r = 0; r < (EL < 4 ? EL : 4); ++r) {
+            const int64_t i = i4 + r;
+            uint32_t c = 0;
+            if (i < D) {
+              if (i >= next) {                               // into the next layer that has elements
+                while (l < L - 1 && off[l + 1] <= i) ++l;
+                next = l < L - 1 ? off[l + 1] : D;
+                a = a64[l];
+                ra = ra64[l];
+                b = (double)ab[2 * l + 1];
+              }
+              // c = rint((p - b) / a) with the quotient in fp64, as the definition says.  p - b is exact in
+              // fp64; times 1/a it is within a few ulp (< 1e-10) of the quotient, so the two round to the same
+              // integer unless the product lies that close to a tie; only then (a few elements in a million)
+              // the quotient itself decides.
+              const double t = (double)v[r] - b;
+              const double x = t * ra;
+              double q = rint(x);
+              if (fabs(fabs(x - q) - 0.5) < 1e-6) q = rint(t / a);      // (a = 0: x = 0, q = 0, never here)
+              q = q < 0.0 ? 0.0 : (q > levels ? levels : q);
+              c = (uint32_t)q;
+            }
+            const int e = e4 + r;
+            if constexpr (DT == TWA_U16MM) word |= ((c - half) & 0xffffu) << (16 * e);      // two's complement int16
+            else if constexpr (DT == TWA_U8MM) word |= ((c - half) & 0xffu) << (8 * e);       // two's complement int8
+            else word |= (c & ((1u << BITS) - 1u)) << (BITS * e);                            // low bits first
+          }
         }
-        if constexpr (DT == TWA_U16MM) word |= ((c - half) & 0xffffu) << (16 * e);      // two's complement int16
-        else if constexpr (DT == TWA_U8MM) word |= ((c - half) & 0xffu) << (8 * e);       // two's complement int8
-        else word |= (c & ((1u << Store<DT>::kBitsPerElem) - 1u)) << (Store<DT>::kBitsPerElem * e);   // low bits first
+        words[w] = word;
       }
-    } else if constexpr (DT == TWA_U8MM) {
-      word = ((0u - half) & 0xffu) * 0x01010101u;      // padding: code 0
-    } else if constexpr (DT == TWA_U16MM) {
-      word = ((0u - half) & 0xffffu) * 0x00010001u;
     }
-    out[vec] = word;
+    out[quad] = words;
   }
 }
 
-size_t minmax_workspace_bytes(int L) { return (size_t)L * (2 * sizeof(uint32_t) + sizeof(double)); }
+size_t minmax_workspace_bytes(int L) { return (size_t)L * (2 * sizeof(uint32_t) + 2 * sizeof(double)); }
 
 int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const void* plan_dev, int L, int dtype,
                            int bits, uint8_t* codes, int64_t ld, float* ab, void* ws, hipStream_t st) {
   double* a64 = static_cast<double*>(ws);                         // 8-byte aligned first
-  uint32_t* keys = reinterpret_cast<uint32_t*>(a64 + L);
+  double* ra64 = a64 + L;
+  uint32_t* keys = reinterpret_cast<uint32_t*>(ra64 + L);
   const LayerPlan plan = plan_view(plan_dev, L, 2048);
   const double levels = (double)((1 << bits) - 1);              // codes 0 .. 2^B - 1, whatever the container
   const int lgrid = (L + 255) / 256;
   hipLaunchKernelGGL(minmax_init_kernel, dim3(lgrid), dim3(256), 0, st, keys, L);
   const int cus = device_cus();
   hipLaunchKernelGGL(layer_minmax_kernel, dim3(cus * 4), dim3(256), 0, st, P, D, n, ldp, plan, keys);
-  hipLaunchKernelGGL(layer_factors_kernel, dim3(lgrid), dim3(256), 0, st, keys, L, levels, ab, a64);
+  hipLaunchKernelGGL(layer_factors_kernel, dim3(lgrid), dim3(256), 0, st, keys, L, levels, ab, a64, ra64);
   const int el = dtype == TWA_U16MM ? 2 : dtype == TWA_U8MM ? 4 : dtype == TWA_U4MM ? 8 : dtype == TWA_U2MM ? 16 : 32;
-  const int64_t nvec = ld / el;
-  int gx = (int)((nvec + 255) / 256);
+  const int64_t nquad = ld / (4 * el);             // a thread writes four dwords
+  int gx = (int)((nquad + 255) / 256);
   if (gx > cus * 8) gx = cus * 8;
 #define TWA_CODES(DT_)                                                                                               \
   hipLaunchKernelGGL(minmax_codes_kernel<DT_>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L, ab, \
-                     a64, levels, 1u << (bits - 1))
+                     a64, ra64, levels, 1u << (bits - 1))
   switch (dtype) {
     case TWA_U16MM: TWA_CODES(TWA_U16MM); break;
     case TWA_U8MM: TWA_CODES(TWA_U8MM); break;

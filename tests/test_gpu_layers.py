@@ -196,6 +196,36 @@ def test_minmax_format_matches_oracle(bits, D, n):
     assert e.value.code == twa.ERR_DTYPE
 
 
+@pytest.mark.parametrize("bits,top", [(4, 15.0), (4, 45.0), (8, 255.0), (8, 765.0), (2, 3.0), (16, 65535.0)])
+def test_minmax_codes_at_exact_ties(bits, top):
+    """Values whose quotient (p - b) / a is exactly half way between two codes, for a step a that is and is not a
+    power of two: the quantiser takes these through the true quotient and rounds them to even, as the oracle does."""
+    D, n = 6000, 3
+    levels = (1 << bits) - 1
+    a = top / levels                                       # 1 or 3: min 0, max top
+    P32 = torch.zeros((n, 6144), dtype=torch.float32)
+    k = torch.arange(0, 2000) % levels
+    P32[0, :2000] = (k.float() + 0.5) * a                  # ties k + 1/2
+    P32[1, :2000] = k.float() * a                          # exact codes
+    P32[2, :2000] = (k.float() + 0.25) * a
+    P32[0, 0], P32[0, 1] = 0.0, top                        # the layer's range
+    gen = torch.Generator().manual_seed(4)
+    P32[:, 2000:D] = torch.randn((n, D - 2000), generator=gen)
+    P32 = P32.cuda()
+    off = np.array([0, 2000, D], dtype=np.int64)
+    plan = twa.LayerPlan(off, D)
+    pm = twa.quantize_minmax(P32, D, plan, bits=bits)
+    torch.cuda.synchronize()
+    codes_o, a_o, b_o = orc.quantize_minmax(P32[:, :D].cpu().numpy().astype(np.float64), bits, off)
+    po = to_oracle(pm, layer_off=off)
+    assert a_o[0] == a and b_o[0] == 0.0
+    assert np.array_equal(po.data[:, :D], codes_o)
+    # and they are ties indeed: rounded to even
+    q = codes_o[0, 2:2000].astype(np.int64)
+    kk = k[2:2000].numpy()
+    assert np.array_equal(q, np.where(kk % 2 == 0, kk, kk + 1))
+
+
 def test_plan_tables():
     D = 10_000
     plan = twa.LayerPlan([0, 5, 5, 40, 2100, 2100, 9000, D], D)
