@@ -103,12 +103,12 @@ __global__ __launch_bounds__(256) void layer_factors_kernel(const uint32_t* __re
   ra64[l] = a > 0.0 ? 1.0 / a : 0.0;
 }
 
-// A thread packs 4 * EL consecutive elements of one vector into four dwords (one 128-bit store); a dword
+// A thread packs WPT * EL consecutive elements of one vector into WPT dwords; a dword
 // holds EL elements: 2 words or 4 bytes holding c - half (half = 2^(B-1): centred whatever B is), or 8
 // nibbles, 16 two-bit or 32 one-bit codes c (element e of the dword at bit e * width).  The layer of the
 // first element is found by bisection, once per thread and trip; after that the thread only watches for the
 // next boundary.
-template <int DT>
+template <int DT, int WPT>
 __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restrict__ P, int64_t D, int64_t ldp,
                                                            uint8_t* __restrict__ codes, int64_t ld,
                                                            const int64_t* __restrict__ off, int L,
@@ -119,16 +119,18 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
   constexpr int BITS = Store<DT>::kBitsPerElem;
   constexpr int EL = 32 / BITS;                 // elements per dword
   const int j = blockIdx.y;
-  const int64_t nquad = ld / (4 * EL);          // 128-bit groups per vector (ld is a multiple of 2048)
+  const int64_t nquad = ld / (WPT * EL);        // groups of WPT dwords per vector (ld is a multiple of 2048)
   const float* p = P + (int64_t)j * ldp;
-  u32x4* out = reinterpret_cast<u32x4*>(codes + (((int64_t)j * ld * BITS) >> 3));
+  uint32_t* out = reinterpret_cast<uint32_t*>(codes + (((int64_t)j * ld * BITS) >> 3));
   uint32_t pad = 0;                             // padding: code 0
   if constexpr (DT == TWA_U8MM) pad = ((0u - half) & 0xffu) * 0x01010101u;
   if constexpr (DT == TWA_U16MM) pad = ((0u - half) & 0xffffu) * 0x00010001u;
   for (int64_t quad = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; quad < nquad;
        quad += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t i0 = quad * 4 * EL;
-    u32x4 words = {pad, pad, pad, pad};
+    const int64_t i0 = quad * WPT * EL;
+    uint32_t words[WPT];
+#pragma unroll
+    for (int w = 0; w < WPT; ++w) words[w] = pad;
     if (i0 < D) {
       int lo = 0, hi = L - 1;                   // largest l with off[l] <= i0
       while (lo < hi) {
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
       int64_t next = l < L - 1 ? off[l + 1] : D;         // first element of the following layer
       double a = a64[l], ra = ra64[l], b = (double)ab[2 * l + 1];
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
+      for (int w = 0; w < WPT; ++w) {
         uint32_t word = 0;
 #pragma unroll
         for (int e4 = 0; e4 < EL; e4 += 4) {
@@ -189,7 +191,12 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
         words[w] = word;
       }
     }
-    out[quad] = words;
+    if constexpr (WPT == 4) {
+      *reinterpret_cast<u32x4*>(out + 4 * quad) = u32x4{words[0], words[1], words[2], words[3]};
+    } else {
+#pragma unroll
+      for (int w = 0; w < WPT; ++w) out[quad * WPT + w] = words[w];
+    }
   }
 }
 
@@ -208,18 +215,22 @@ int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const 
   hipLaunchKernelGGL(layer_minmax_kernel, dim3(cus * 4), dim3(256), 0, st, P, D, n, ldp, plan, keys);
   hipLaunchKernelGGL(layer_factors_kernel, dim3(lgrid), dim3(256), 0, st, keys, L, levels, ab, a64, ra64);
   const int el = dtype == TWA_U16MM ? 2 : dtype == TWA_U8MM ? 4 : dtype == TWA_U4MM ? 8 : dtype == TWA_U2MM ? 16 : 32;
-  const int64_t nquad = ld / (4 * el);             // a thread writes four dwords
-  int gx = (int)((nquad + 255) / 256);
+  // dwords of codes a thread writes per trip, per container: measured at the ResNet-50 shape (code pass in ms
+  // for 1 / 2 / 4 dwords: 16 bits 11.2 / 7.7 / 6.8, 8 bits 5.9 / 3.9 / 3.3, 4 bits 3.7 / 3.1 / 4.5,
+  // 2 bits 3.0 / 4.5 / 4.4, 1 bit 4.5 / 4.3 / 3.9)
+  const int wpt = dtype == TWA_U4MM ? 2 : dtype == TWA_U2MM ? 1 : 4;
+  const int64_t ngroups = ld / (wpt * el);
+  int gx = (int)((ngroups + 255) / 256);
   if (gx > cus * 8) gx = cus * 8;
-#define TWA_CODES(DT_)                                                                                               \
-  hipLaunchKernelGGL(minmax_codes_kernel<DT_>, dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L, ab, \
-                     a64, ra64, levels, 1u << (bits - 1))
+#define TWA_CODES(DT_, WPT_)                                                                                       \
+  hipLaunchKernelGGL((minmax_codes_kernel<DT_, WPT_>), dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L, \
+                     ab, a64, ra64, levels, 1u << (bits - 1))
   switch (dtype) {
-    case TWA_U16MM: TWA_CODES(TWA_U16MM); break;
-    case TWA_U8MM: TWA_CODES(TWA_U8MM); break;
-    case TWA_U4MM: TWA_CODES(TWA_U4MM); break;
-    case TWA_U2MM: TWA_CODES(TWA_U2MM); break;
-    default: TWA_CODES(TWA_U1MM); break;
+    case TWA_U16MM: TWA_CODES(TWA_U16MM, 4); break;
+    case TWA_U8MM: TWA_CODES(TWA_U8MM, 4); break;
+    case TWA_U4MM: TWA_CODES(TWA_U4MM, 2); break;
+    case TWA_U2MM: TWA_CODES(TWA_U2MM, 1); break;
+    default: TWA_CODES(TWA_U1MM, 4); break;
   }
 #undef TWA_CODES
   return hip_check(hipGetLastError());
