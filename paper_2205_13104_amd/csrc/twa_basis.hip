@@ -10,6 +10,14 @@
 //                      order by gram_reduce_kernel.
 //   apply_rinv_kernel  Q = W R^-1 (R^-1 upper triangular, fp32) with v_mfma_f32_16x16x4_f32;
 //                      a workgroup owns a tile of rows for ALL n columns, so Q may overwrite W.
+//
+// Both kernels are compiled per number of 16-column blocks (1..8), and inside them every wave runs its own
+// copy of the product loop in which block indices, operand registers and trip counts are constants: with
+// run-time block indices the loop had a branch per block, the compiler could not move the LDS reads of a
+// block ahead of the matrix instruction of the previous one, and every instruction waited out an LDS
+// latency (Gram 7.7 -> 6.2 ms, apply 6.5 -> 4.9 ms at D = 25.6 M, n = 100).
+#include <utility>
+
 #include "twa_device.h"
 #include "twa_host.h"
 
@@ -21,7 +29,6 @@ using f32x4 = float __attribute__((ext_vector_type(4)));
 constexpr int kTileRows = 64;                 // rows of W (along D) staged in LDS per step
 constexpr int kGramStride = kTileRows + 2;    // floats; (2*col + row) mod 32 banks -> conflict free
 constexpr int kApplyStride = kTileRows + 16;  // floats; 16-lane row groups land on disjoint banks
-constexpr int kMaxBlocksPerWave = 9;          // 8*9/2 upper-triangular blocks over 4 waves
 
 // Row of the 16x16 result held by register r of lane l (both MFMA shapes used here):
 //   v_mfma_f32_16x16x4_f32 : row = 4*(l/16) + r
@@ -77,27 +84,70 @@ __device__ __forceinline__ void store_tile(int NP, const float4 (&pre)[kTileQuad
   }
 }
 
-__global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ W, int64_t D, int n, int64_t ldw,
-                                                   int NP, double* __restrict__ partial) {
-  __shared__ float tile[TWA_MAX_N * kGramStride];
+// The upper-triangular 16x16 blocks (a, b >= a) of an NB x NB block matrix, enumerated row by row; wave w
+// owns blocks t = w, w + 4, ...  Everything here is a compile-time constant, so that the operands and the
+// sums of a wave's blocks sit in registers with static indices and the compiler can order the LDS reads
+// of a k-step ahead of its matrix instructions.
+template <int NB> struct GramBlocks {
+  static constexpr int T = NB * (NB + 1) / 2;
+  static constexpr int NQ = (T + 3) / 4;                 // blocks per wave, at most
+  static constexpr int row_of(int t) { int a = 0; while (t >= NB - a) { t -= NB - a; ++a; } return a; }
+  static constexpr int col_of(int t) { int a = 0; while (t >= NB - a) { t -= NB - a; ++a; } return a + t; }
+};
+
+template <int NB, int WV, int Q>
+__device__ __forceinline__ void gram_block_step(const double (&x)[NB], f64x4 (&acc)[GramBlocks<NB>::NQ]) {
+  using B = GramBlocks<NB>;
+  if constexpr (WV + 4 * Q < B::T) {
+    constexpr int a = B::row_of(WV + 4 * Q), b = B::col_of(WV + 4 * Q);
+    acc[Q] = __builtin_amdgcn_mfma_f64_16x16x4f64(x[a], x[b], acc[Q], 0, 0, 0);
+  }
+}
+template <int NB, int WV, int... Q>
+__device__ __forceinline__ void gram_k_step(const double (&x)[NB], f64x4 (&acc)[GramBlocks<NB>::NQ],
+                                            std::integer_sequence<int, Q...>) {
+  (gram_block_step<NB, WV, Q>(x, acc), ...);
+}
+// One staged tile: kTileRows / 4 k-steps.  Lane (m, kq) holds element [16c + m][4kk + kq] of column block c,
+// which is its share of the block both as the left and as the right operand.
+template <int NB, int WV>
+__device__ __forceinline__ void gram_tile_products(const float* tile, int m, int kq,
+                                                   f64x4 (&acc)[GramBlocks<NB>::NQ]) {
+  constexpr int kSteps = NB == 8 ? 8 : 16;      // unrolled k-steps: the widest matrix has no registers for 16 steps' operands
+#pragma unroll kSteps
+  for (int kk = 0; kk < kTileRows / 4; ++kk) {
+    double x[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) x[c] = (double)tile[(16 * c + m) * kGramStride + 4 * kk + kq];
+    gram_k_step<NB, WV>(x, acc, std::make_integer_sequence<int, GramBlocks<NB>::NQ>{});
+  }
+}
+template <int NB, int WV, int Q>
+__device__ __forceinline__ void gram_block_out(const f64x4 (&acc)[GramBlocks<NB>::NQ], double* out, int NP, int lane) {
+  using B = GramBlocks<NB>;
+  if constexpr (WV + 4 * Q < B::T) {
+    constexpr int a = B::row_of(WV + 4 * Q), b = B::col_of(WV + 4 * Q);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) out[(16 * a + mfma_row_f64(lane, r)) * NP + 16 * b + (lane & 15)] = acc[Q][r];
+  }
+}
+template <int NB, int WV, int... Q>
+__device__ __forceinline__ void gram_out(const f64x4 (&acc)[GramBlocks<NB>::NQ], double* out, int NP, int lane,
+                                         std::integer_sequence<int, Q...>) {
+  (gram_block_out<NB, WV, Q>(acc, out, NP, lane), ...);
+}
+
+template <int NB>
+__global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ W, int64_t D, int n, int64_t ldw,
+                                                   double* __restrict__ partial) {
+  using B = GramBlocks<NB>;
+  constexpr int NP = 16 * NB;
+  __shared__ float tile[NP * kGramStride];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nb = NP / 16;
-  const int T = nb * (nb + 1) / 2;
-
-  // upper-triangular blocks t = wave, wave+4, ... of the enumeration (a, b >= a)
-  int blk_a[kMaxBlocksPerWave], blk_b[kMaxBlocksPerWave];
+  f64x4 acc[B::NQ];
 #pragma unroll
-  for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-    int t = wave + 4 * q, a = 0;
-    if (t >= T) t = T - 1;                       // unused slot: any valid block, result discarded
-    while (t >= nb - a) { t -= nb - a; ++a; }
-    blk_a[q] = a;
-    blk_b[q] = a + t;
-  }
-  f64x4 acc[kMaxBlocksPerWave];
-#pragma unroll
-  for (int q = 0; q < kMaxBlocksPerWave; ++q) acc[q] = {0.0, 0.0, 0.0, 0.0};
+  for (int q = 0; q < B::NQ; ++q) acc[q] = {0.0, 0.0, 0.0, 0.0};
 
   const int64_t nchunks = (D + kTileRows - 1) / kTileRows;
   int64_t c0, c1;
@@ -109,65 +159,113 @@ __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ W, 
     store_tile<kGramStride>(NP, pre, tile);
     __syncthreads();
     if (c + 1 < c1) fetch_tile(W, ldw, D, n, NP, (c + 1) * kTileRows, pre);     // in flight during the products
-#pragma unroll 4
-    for (int kk = 0; kk < kTileRows / 4; ++kk) {
-#pragma unroll
-      for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-        if (wave + 4 * q < T) {
-          const double a = (double)tile[(16 * blk_a[q] + m) * kGramStride + 4 * kk + kq];
-          const double b = (double)tile[(16 * blk_b[q] + m) * kGramStride + 4 * kk + kq];
-          acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[q], 0, 0, 0);
-        }
-      }
+    switch (wave) {                                                             // uniform per wave
+      case 0: gram_tile_products<NB, 0>(tile, m, kq, acc); break;
+      case 1: gram_tile_products<NB, 1>(tile, m, kq, acc); break;
+      case 2: gram_tile_products<NB, 2>(tile, m, kq, acc); break;
+      default: gram_tile_products<NB, 3>(tile, m, kq, acc); break;
     }
     __syncthreads();
   }
   double* out = partial + (int64_t)blockIdx.x * NP * NP;
-#pragma unroll
-  for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-    if (wave + 4 * q < T) {
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        out[(16 * blk_a[q] + mfma_row_f64(lane, r)) * NP + 16 * blk_b[q] + m] = acc[q][r];
-    }
+  constexpr auto slots = std::make_integer_sequence<int, B::NQ>{};
+  switch (wave) {
+    case 0: gram_out<NB, 0>(acc, out, NP, lane, slots); break;
+    case 1: gram_out<NB, 1>(acc, out, NP, lane, slots); break;
+    case 2: gram_out<NB, 2>(acc, out, NP, lane, slots); break;
+    default: gram_out<NB, 3>(acc, out, NP, lane, slots); break;
   }
 }
 
-// gram[i*NP + j] = sum over workgroups in workgroup order (upper-triangular blocks only).
+// gram[i*NP + j] = sum of the workgroups' partial sums (upper-triangular blocks only), in a fixed order:
+// eight threads per element each add every eighth workgroup's term in rising order, then the eight
+// subtotals are added in rising order -- one thread per element walked all the partial matrices alone
+// and took 0.16 ms for 512 of them.
 // `accumulate`: the sum is added to what gram holds (rows that arrive in panels).
+constexpr int kReduceSplit = 8;
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ partial, int nparts, int NP,
                                                           double* __restrict__ gram, int accumulate) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= NP * NP) return;
-  const int i = idx / NP, j = idx - i * NP;
+  constexpr int kElems = 256 / kReduceSplit;
+  __shared__ double sub[kReduceSplit][kElems];
+  const int e = threadIdx.x % kElems, part = threadIdx.x / kElems;
+  const int idx = blockIdx.x * kElems + e;
+  const bool live = idx < NP * NP && ((idx % NP) >> 4) >= ((idx / NP) >> 4);
   double a = 0.0;
-  if ((j >> 4) >= (i >> 4))
-    for (int b = 0; b < nparts; ++b) a += partial[(int64_t)b * NP * NP + idx];
-  gram[idx] = accumulate ? gram[idx] + a : a;
+  if (live)
+    for (int b = part; b < nparts; b += kReduceSplit) a += partial[(int64_t)b * NP * NP + idx];
+  sub[part][e] = a;
+  __syncthreads();
+  if (part == 0 && idx < NP * NP) {
+    double t = 0.0;
+#pragma unroll
+    for (int q = 0; q < kReduceSplit; ++q) t += sub[q][e];
+    gram[idx] = accumulate ? gram[idx] + t : t;
+  }
 }
 
 // Q[:, j] = sum_{a <= j} W[:, a] * rinv[a][j];  rinv is NP x NP row major, zero outside the
 // upper triangle and outside n x n.  As an MFMA: D[m = j][n' = i] = sum_a A[m][a] B[a][n'] with
 // A = rinv^T (kept in registers for the wave's two column blocks) and B = the staged tile.
 // (W and Q carry no no-alias promise: Q may be W.)
-__global__ __launch_bounds__(256) void apply_rinv_kernel(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n,
-                                                         int NP, const float* __restrict__ rinv) {
-  __shared__ float tile[TWA_MAX_N * kApplyStride];
+//
+// Column block jb needs the k-steps of rows 0 .. 16 (jb + 1) only (rinv is upper triangular): its cost is
+// jb + 1.  A wave takes at most two blocks, chosen at compile time so that the four waves carry the same
+// load: the four widest blocks go to waves 0..3 in falling order, the remaining NB - 4 narrow ones in
+// rising order to the LAST waves (NB = 7: {6}, {5,0}, {4,1}, {3,2}, seven units each).  -1 = no block.
+template <int NB>
+__host__ __device__ constexpr int apply_block_of(int wave, int which) {
+  if (NB <= 4) return (which == 0 && wave < NB) ? wave : -1;
+  if (which == 0) return NB - 1 - wave;
+  return wave - (8 - NB) >= 0 ? wave - (8 - NB) : -1;
+}
+
+constexpr int kApplyRowGroups = kTileRows / 16;
+
+// The products of one staged tile for wave WV: every index is a compile-time constant, so the LDS reads
+// of later k-steps are issued while the matrix cores work on earlier ones.
+template <int NB, int WV>
+__device__ __forceinline__ void apply_tile_products(const float* tile, const float (&afrag)[2][4 * NB], int m, int kq,
+                                                    f32x4 (&acc)[2][kApplyRowGroups]) {
+  constexpr int RG = kApplyRowGroups;
+  constexpr int jb0 = apply_block_of<NB>(WV, 0), jb1 = apply_block_of<NB>(WV, 1);
+  constexpr int ksteps = 4 * ((jb0 > jb1 ? jb0 : jb1) + 1);
+#pragma unroll
+  for (int kk = 0; kk < ksteps; ++kk) {
+    float b[RG];
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) b[rg] = tile[(4 * kk + kq) * kApplyStride + 16 * rg + m];
+    if (kk < 4 * (jb0 + 1)) {
+#pragma unroll
+      for (int rg = 0; rg < RG; ++rg)
+        acc[0][rg] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag[0][kk], b[rg], acc[0][rg], 0, 0, 0);
+    }
+    if (kk < 4 * (jb1 + 1)) {
+#pragma unroll
+      for (int rg = 0; rg < RG; ++rg)
+        acc[1][rg] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag[1][kk], b[rg], acc[1][rg], 0, 0, 0);
+    }
+  }
+}
+
+template <int NB>
+__global__ __launch_bounds__(256, 2) void apply_rinv_kernel(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D,
+                                                            int n, const float* __restrict__ rinv) {
+  constexpr int NP = 16 * NB;
+  constexpr int KK = 4 * NB;                    // k-steps of the widest block
+  constexpr int RG = kApplyRowGroups;           // row groups per tile
+  __shared__ float tile[NP * kApplyStride];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nb = NP / 16;
   const int m = lane & 15, kq = lane >> 4;
-  constexpr int KK = TWA_MAX_N / 4;             // 32 k-steps at most
-  constexpr int RG = kTileRows / 16;            // row groups per tile
+  const int jbs[2] = {apply_block_of<NB>(wave, 0), apply_block_of<NB>(wave, 1)};
 
   float afrag[2][KK];
 #pragma unroll
   for (int jbi = 0; jbi < 2; ++jbi) {
-    const int jb = wave + 4 * jbi;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      const int a = 4 * kk + kq, j = 16 * jb + m;
-      afrag[jbi][kk] = (jb < nb && a < NP) ? rinv[a * NP + j] : 0.0f;
+      const int a = 4 * kk + kq, j = 16 * jbs[jbi] + m;
+      afrag[jbi][kk] = jbs[jbi] >= 0 ? rinv[a * NP + j] : 0.0f;
     }
   }
 
@@ -188,28 +286,17 @@ __global__ __launch_bounds__(256) void apply_rinv_kernel(const float* W, int64_t
     for (int jbi = 0; jbi < 2; ++jbi)
 #pragma unroll
       for (int rg = 0; rg < RG; ++rg) acc[jbi][rg] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      if (4 * kk < NP) {                                           // uniform
-        float b[RG];
-#pragma unroll
-        for (int rg = 0; rg < RG; ++rg) b[rg] = tile[(4 * kk + kq) * kApplyStride + 16 * rg + m];
-#pragma unroll
-        for (int jbi = 0; jbi < 2; ++jbi) {
-          const int jb = wave + 4 * jbi;
-          if (jb < nb && 4 * kk < 16 * (jb + 1)) {                 // uniform; rinv is upper triangular
-#pragma unroll
-            for (int rg = 0; rg < RG; ++rg)
-              acc[jbi][rg] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag[jbi][kk], b[rg], acc[jbi][rg], 0, 0, 0);
-          }
-        }
-      }
+    switch (wave) {                                                 // uniform per wave
+      case 0: apply_tile_products<NB, 0>(tile, afrag, m, kq, acc); break;
+      case 1: apply_tile_products<NB, 1>(tile, afrag, m, kq, acc); break;
+      case 2: apply_tile_products<NB, 2>(tile, afrag, m, kq, acc); break;
+      default: apply_tile_products<NB, 3>(tile, afrag, m, kq, acc); break;
     }
-    __syncthreads();      // every wave has read the tile; safe to overwrite W rows in place
+    __syncthreads();      // every wave has read the tile in LDS; the next one may replace it
 #pragma unroll
     for (int jbi = 0; jbi < 2; ++jbi) {
-      const int jb = wave + 4 * jbi;
-      if (jb < nb) {
+      const int jb = jbs[jbi];
+      if (jb >= 0) {
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) {
           const int64_t row = i0 + 16 * rg + m;
@@ -233,16 +320,27 @@ __global__ __launch_bounds__(256) void zero_padding_kernel(float* __restrict__ Q
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram,
                 bool accumulate, hipStream_t st) {
   const int NP = (n + 15) / 16 * 16;
-  hipLaunchKernelGGL(gram_kernel, dim3(grid), dim3(256), 0, st, W, D, n, ldw, NP, partial);
-  hipLaunchKernelGGL(gram_reduce_kernel, dim3((NP * NP + 255) / 256), dim3(256), 0, st, partial, grid, NP, gram,
-                     accumulate ? 1 : 0);
+  switch (NP / 16) {
+#define TWA_GRAM(NB_) case NB_: hipLaunchKernelGGL(gram_kernel<NB_>, dim3(grid), dim3(256), 0, st, W, D, n, ldw, partial); break
+    TWA_GRAM(1); TWA_GRAM(2); TWA_GRAM(3); TWA_GRAM(4); TWA_GRAM(5); TWA_GRAM(6); TWA_GRAM(7); TWA_GRAM(8);
+#undef TWA_GRAM
+    default: return TWA_ERR_SHAPE;
+  }
+  constexpr int kElems = 256 / kReduceSplit;
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3((NP * NP + kElems - 1) / kElems), dim3(256), 0, st, partial, grid, NP,
+                     gram, accumulate ? 1 : 0);
   return hip_check(hipGetLastError());
 }
 
 int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
                       int grid, bool zero_padding, hipStream_t st) {
   const int NP = (n + 15) / 16 * 16;
-  hipLaunchKernelGGL(apply_rinv_kernel, dim3(grid), dim3(256), 0, st, W, ldw, Q, ldq, D, n, NP, rinv_dev);
+  switch (NP / 16) {
+#define TWA_APPLY(NB_) case NB_: hipLaunchKernelGGL(apply_rinv_kernel<NB_>, dim3(grid), dim3(256), 0, st, W, ldw, Q, ldq, D, n, rinv_dev); break
+    TWA_APPLY(1); TWA_APPLY(2); TWA_APPLY(3); TWA_APPLY(4); TWA_APPLY(5); TWA_APPLY(6); TWA_APPLY(7); TWA_APPLY(8);
+#undef TWA_APPLY
+    default: return TWA_ERR_SHAPE;
+  }
   if (zero_padding && ldq > D) hipLaunchKernelGGL(zero_padding_kernel, dim3(1, n), dim3(256), 0, st, Q, D, ldq);
   return hip_check(hipGetLastError());
 }
