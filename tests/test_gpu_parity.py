@@ -245,6 +245,22 @@ def test_build_basis_invariants(name, D, n):
     assert np.linalg.norm(R.numpy() - Ro) <= 1e-5 * np.linalg.norm(Ro)
 
 
+@pytest.mark.parametrize("n", [16, 17, 33, 48, 49, 64, 65, 81, 96, 97, 112, 113])
+def test_build_basis_every_count_of_column_blocks(n):
+    # the Gram and apply kernels are compiled per number of 16-column blocks, and the waves' shares of the
+    # blocks differ with it: every count from 1 to 8, at a full last block and at a last block of one column;
+    # D leaves a ragged last tile of rows and gives several workgroups several tiles each
+    D = 70001
+    say("build_basis, column blocks", (n + 15) // 16, "n", n)
+    W = synth.checkpoints(synth.WORKLOADS["cifar_resnet18"], seed=3, device="cuda", D=D, n=n)
+    P, R = twa.build_basis(W, D)
+    Wh, Ph = _basis_checks(W, P, R, D, n)
+    assert not P[:, D:].any()
+    assert np.linalg.norm(Wh - (Wh @ Ph.T) @ Ph) <= 1e-5 * np.linalg.norm(Wh)
+    _, Ro = orc.build_basis(Wh)
+    assert np.linalg.norm(R.numpy() - Ro) <= 1e-5 * np.linalg.norm(Ro)
+
+
 def test_build_basis_in_place_and_n1():
     D = 40001
     wl = synth.WORKLOADS["tiny"]
