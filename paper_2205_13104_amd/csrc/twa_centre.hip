@@ -44,27 +44,6 @@ __global__ __launch_bounds__(kEltThreads) void mean_kernel(const float* __restri
   }
 }
 
-// E[j][i] = (W[j][i] - hi[i]) - lo[i] for i < D, 0 for D <= i < lde.
-__global__ __launch_bounds__(kEltThreads) void centre_kernel(const float* W, int64_t D, int n, int64_t ldw,
-                                                             const float* __restrict__ wbar,
-                                                             const float* __restrict__ wbar_lo, float* E,
-                                                             int64_t lde) {   // E may be W
-  const uint32_t bytes = (uint32_t)(D * 4);
-  const rsrc_t rh = make_rsrc(wbar, bytes), rl = make_rsrc(wbar_lo, bytes);
-  const int64_t nvec = lde / 4;
-  for (int64_t q = (int64_t)blockIdx.x * kEltThreads + threadIdx.x; q < nvec; q += (int64_t)gridDim.x * kEltThreads) {
-    const u32x4 h = ld128(rh, (uint32_t)q * 16u), l = ld128(rl, (uint32_t)q * 16u);
-    for (int j = 0; j < n; ++j) {
-      const u32x4 x = ld128_stream(make_rsrc(W + (int64_t)j * ldw, bytes), (uint32_t)q * 16u);
-      u32x4 y;
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        y[r] = 4 * q + r < D ? as_u32((as_f32(x[r]) - as_f32(h[r])) - as_f32(l[r])) : 0u;
-      *reinterpret_cast<u32x4*>(E + (int64_t)j * lde + 4 * q) = y;
-    }
-  }
-}
-
 // rinv[l][j] = 1/sqrt(Q[l][j]) (0 where Q is 0); norms[l][j] = sqrt(Q[l][j]) if wanted.
 __global__ __launch_bounds__(kEltThreads) void rinv_kernel(const float* __restrict__ Q, int64_t count,
                                                            float* __restrict__ rinv, float* __restrict__ norms) {
@@ -76,12 +55,16 @@ __global__ __launch_bounds__(kEltThreads) void rinv_kernel(const float* __restri
   if (norms) norms[q] = (float)r;
 }
 
-// E[j][i] *= rinv[layer of i][j].  4 consecutive elements per thread; the layer of the first one by
-// bisection, the others follow.
-__global__ __launch_bounds__(kEltThreads) void scale_kernel(float* __restrict__ E, int64_t D, int n, int64_t lde,
-                                                            const int64_t* __restrict__ off, int L,
-                                                            const float* __restrict__ rinv) {
-  const int64_t nvec = (D + 3) / 4;
+// E[j][i] = ((W[j][i] - hi[i]) - lo[i]) * rinv[layer of i][j] for i < D, 0 for D <= i < lde  (E may be W).
+// 4 consecutive elements per thread; the layer of the first one by bisection, the others follow.
+__global__ __launch_bounds__(kEltThreads) void centre_scale_kernel(const float* W, int64_t D, int n, int64_t ldw,
+                                                                   const float* __restrict__ wbar,
+                                                                   const float* __restrict__ wbar_lo, float* E,
+                                                                   int64_t lde, const int64_t* __restrict__ off, int L,
+                                                                   const float* __restrict__ rinv) {
+  const uint32_t bytes = (uint32_t)(D * 4);
+  const rsrc_t rh = make_rsrc(wbar, bytes), rl = make_rsrc(wbar_lo, bytes);
+  const int64_t nvec = lde / 4;
   for (int64_t q = (int64_t)blockIdx.x * kEltThreads + threadIdx.x; q < nvec; q += (int64_t)gridDim.x * kEltThreads) {
     const int64_t i0 = 4 * q;
     int a = 0, b = L - 1;                       // largest l with off[l] <= i0
@@ -96,14 +79,16 @@ __global__ __launch_bounds__(kEltThreads) void scale_kernel(float* __restrict__ 
       while (l < L - 1 && off[l + 1] <= i0 + r) ++l;
       lay[r] = l;
     }
+    const u32x4 h = ld128(rh, (uint32_t)q * 16u), lo = ld128(rl, (uint32_t)q * 16u);      // past D: zeros
     for (int j = 0; j < n; ++j) {
-      float4* p = reinterpret_cast<float4*>(E + (int64_t)j * lde + i0);      // lde % 4 == 0: inside the row
-      float4 x = *p;
-      x.x *= rinv[(int64_t)lay[0] * n + j];
-      x.y *= rinv[(int64_t)lay[1] * n + j];
-      x.z *= rinv[(int64_t)lay[2] * n + j];
-      x.w *= rinv[(int64_t)lay[3] * n + j];
-      *p = x;                                                                // padding: 0 * finite = 0
+      const u32x4 x = ld128_stream(make_rsrc(W + (int64_t)j * ldw, bytes), (uint32_t)q * 16u);
+      u32x4 y;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float c = (as_f32(x[r]) - as_f32(h[r])) - as_f32(lo[r]);
+        y[r] = i0 + r < D ? as_u32(c * rinv[(int64_t)lay[r] * n + j]) : 0u;
+      }
+      *reinterpret_cast<u32x4*>(E + (int64_t)j * lde + i0) = y;
     }
   }
 }
@@ -166,19 +151,19 @@ int launch_centre_normalise(const float* W, int64_t D, int n, int64_t ldw, const
   float* rinv = Q + (size_t)L * n;
   float* partial = rinv + (size_t)L * n;
   hipLaunchKernelGGL(mean_kernel, dim3(elt_grid((D + 3) / 4)), dim3(kEltThreads), 0, st, W, D, n, ldw, wbar, wbar_lo);
-  hipLaunchKernelGGL(centre_kernel, dim3(elt_grid(lde / 4)), dim3(kEltThreads), 0, st, W, D, n, ldw, wbar, wbar_lo, E,
-                     lde);
   int rc = hip_check(hipGetLastError());
   if (rc != TWA_OK) return rc;
-  PView v{reinterpret_cast<const uint8_t*>(E), nullptr, D, lde, n, 0, 1.0f, 0.0f};
-  rc = launch_layer_squares(v, plan_dev, L, Q, partial, max_grid, st);
+  // the squared norms are taken from W centred on the fly, and the centred matrix is written once,
+  // already scaled: four passes over the n x D matrix (three reads, one write) instead of six
+  PView v{reinterpret_cast<const uint8_t*>(W), nullptr, D, ldw, n, 0, 1.0f, 0.0f};
+  rc = launch_layer_squares(v, wbar, wbar_lo, plan_dev, L, Q, partial, max_grid, st);
   if (rc != TWA_OK) return rc;
   const int64_t count = (int64_t)L * n;
   hipLaunchKernelGGL(rinv_kernel, dim3((unsigned)((count + kEltThreads - 1) / kEltThreads)), dim3(kEltThreads), 0, st, Q,
                      count, rinv, norms);
   const LayerPlan plan = plan_view(plan_dev, L, 2048);
-  hipLaunchKernelGGL(scale_kernel, dim3(elt_grid((D + 3) / 4)), dim3(kEltThreads), 0, st, E, D, n, lde, plan.off, L,
-                     rinv);
+  hipLaunchKernelGGL(centre_scale_kernel, dim3(elt_grid(lde / 4)), dim3(kEltThreads), 0, st, W, D, n, ldw, wbar, wbar_lo,
+                     E, lde, plan.off, L, rinv);
   return hip_check(hipGetLastError());
 }
 

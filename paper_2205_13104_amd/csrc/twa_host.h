@@ -40,8 +40,8 @@ int launch_project_layers(const PView& P, int dtype, const float* g, const void*
 int launch_expand_update_layers(const PView& P, int dtype, const float* s, const void* plan_dev, int L,
                                 const float* w_in, float* w_out, float lr, float* g_tilde, int max_grid,
                                 hipStream_t st);
-int launch_layer_squares(const PView& P, const void* plan_dev, int L, float* Q, float* partial, int max_grid,
-                         hipStream_t st);
+int launch_layer_squares(const PView& P, const float* mean_hi, float* mean_lo, const void* plan_dev, int L, float* Q,
+                         float* partial, int max_grid, hipStream_t st);
 size_t centre_workspace_bytes(int64_t D, int n, int L);
 int launch_centre_normalise(const float* W, int64_t D, int n, int64_t ldw, const void* plan_dev, int L, float* wbar,
                             float* E, int64_t lde, float* norms, void* ws, int max_grid, hipStream_t st);

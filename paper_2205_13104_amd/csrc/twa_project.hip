@@ -30,8 +30,9 @@ namespace twa {
 // walks into the next layer it reduces its running sums and writes them to partial slot
 // (workgroup + layer): along the walk both indices only grow, so the slot is unique, and the
 // reduction kernel knows from the plan which workgroups contributed to a layer.
-// SQUARES (with LAYERED, F32): no gradient; the sums are the squares of the stored elements of the
-// layer, sum_i P_ij^2 -- the squared norms that the layer-wise basis divides by (Sec. 4.5).
+// SQUARES (with LAYERED, F32): no gradient; the sums are the squares of the CENTRED elements of the
+// layer, sum_i ((W_ij - hi_i) - lo_i)^2 -- the squared norms that the layer-wise basis divides by
+// (Sec. 4.1, 4.5).  The mean arrives as two binary32 words per element: `g` holds hi, `partial_g` lo.
 template <int DT, int KB, int U, int NCH, int VPL, bool LAYERED, bool SQUARES = false>
 __device__ __forceinline__ void project_body(PView P, const float* __restrict__ g, int64_t ldg, int kvalid,
                                              float* __restrict__ partial, int cpw, int tiles_per_wg, LayerPlan plan,
@@ -117,6 +118,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
     //      the layer), and the range check is per dword, so elements past that end arrive as 0 --
     float gs[KB][VPL][EPV];
     float gcorr[KB][VPL];
+    float mean_hi[SQUARES ? VPL : 1][EPV], mean_lo[SQUARES ? VPL : 1][EPV];     // SQUARES: this lane's slice of the mean
 #pragma unroll
     for (int c = 0; c < KB; ++c) {
       const rsrc_t rg = make_rsrc(g + (int64_t)c * ldg, c < kvalid ? g_bytes : 0u);
@@ -127,6 +129,16 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
           const uint32_t rel = (uint32_t)(v * kWave + lane) * EPV;
 #pragma unroll
           for (int e = 0; e < EPV; ++e) gs[c][v][e] = (rel + e >= head && rel + e < tail) ? 1.0f : 0.0f;
+          const rsrc_t rl = make_rsrc(partial_g, g_bytes);
+#pragma unroll
+          for (int q = 0; q < EPV / 4; ++q) {
+            const u32x4 h = ld128(rg, (elem + 4u * q) * 4u), l = ld128(rl, (elem + 4u * q) * 4u);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              mean_hi[v][4 * q + r] = as_f32(h[r]);
+              mean_lo[v][4 * q + r] = as_f32(l[r]);
+            }
+          }
         } else {
 #pragma unroll
           for (int q = 0; q < EPV / 4; ++q) {
@@ -202,6 +214,10 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
         for (int v = 0; v < VPL; ++v) {
           float x[EPV];
           decode<DT>(raw[u][v], x);
+          if constexpr (SQUARES) {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) x[e] = (x[e] - mean_hi[v][e]) - mean_lo[v][e];
+          }
 #pragma unroll
           for (int c = 0; c < KB; ++c) {
             if constexpr (S::kScaled) {
@@ -466,7 +482,23 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
       hipLaunchKernelGGL((project_kernel<DT, KB, U_, NCH_, VPL>), dim3(grid), dim3(256), 0, st, P, g, ldg, kvalid, \
                          partial, cpw, tiles_per_wg);                                                         \
   } while (0)
-  {
+  if constexpr (SQUARES) {
+    // the slices of the two mean words take 32 registers more: chunks of 3 column slots keep the kernel
+    // inside its register budget
+    switch ((cpw + 2) / 3) {
+      case 1: TWA_LAUNCH(3, 1); break;
+      case 2: TWA_LAUNCH(3, 2); break;
+      case 3: TWA_LAUNCH(3, 3); break;
+      case 4: TWA_LAUNCH(3, 4); break;
+      case 5: TWA_LAUNCH(3, 5); break;
+      case 6: TWA_LAUNCH(3, 6); break;
+      case 7: TWA_LAUNCH(3, 7); break;
+      case 8: TWA_LAUNCH(3, 8); break;
+      case 9: TWA_LAUNCH(3, 9); break;
+      case 10: TWA_LAUNCH(3, 10); break;
+      default: TWA_LAUNCH(3, 11); break;
+    }
+  } else {
     if (cpw == 25) {
       TWA_LAUNCH(5, 5);
     } else {
@@ -574,13 +606,14 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   return hip_check(hipGetLastError());
 }
 
-// Per-layer squared norms of the vectors of an fp32 matrix: Q[l][j] = sum over layer l of P_ij^2.
-int launch_layer_squares(const PView& P, const void* plan_dev, int L, float* Q, float* partial, int max_grid,
-                         hipStream_t st) {
+// Per-layer squared norms of the centred vectors of an fp32 matrix:
+// Q[l][j] = sum over layer l of ((P_ij - mean_hi_i) - mean_lo_i)^2.
+int launch_layer_squares(const PView& P, const float* mean_hi, float* mean_lo, const void* plan_dev, int L, float* Q,
+                         float* partial, int max_grid, hipStream_t st) {
   constexpr int tile = kWave * 4 * Store<TWA_F32>::kEPV;
   const LayerPlan plan = plan_view(plan_dev, L, tile);
   int grid = 0;
-  int rc = launch_project_dt<TWA_F32, 1, 4, true, true>(P, nullptr, 0, 1, partial, max_grid, &grid, st, plan);
+  int rc = launch_project_dt<TWA_F32, 1, 4, true, true>(P, mean_hi, 0, 1, partial, max_grid, &grid, st, plan, mean_lo);
   if (rc != TWA_OK) return rc;
   hipLaunchKernelGGL(project_layers_reduce_kernel<false>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial, nullptr,
                      P.n, plan, grid, nullptr, 0.0f, Q, BetaStep{nullptr, 0.0f, 0.0f});
