@@ -2,14 +2,15 @@
 // Sec. 4.5, its layer-wise form; Alg. 1, first steps):
 //   wbar = (1/n) sum_j w_j ,   e_j^l = (w_j^l - wbar^l) / || w_j^l - wbar^l ||_2 .
 // One-time work that is bound by a few passes over the n x D checkpoint matrix:
-//   1. mean_kernel        reads W, writes wbar (the sum is kept in fp64; besides the fp32 mean its
-//                         rounding error is kept too, so that step 2 subtracts the mean to almost
-//                         fp64 accuracy: layers that hardly move between checkpoints have
-//                         |w_j - wbar| << |wbar| and would otherwise lose most of their digits);
-//   2. centre_kernel      E = (W - wbar_hi) - wbar_lo, zero padding; may run in place;
-//   3. the per-layer squared norms of E (the layer-wise projection kernel in its squares mode);
-//   4. rinv_kernel        1/norm per (layer, vector), 0 for a zero vector; the norms if wanted;
-//   5. scale_kernel       E_ij *= 1/norm of (layer of i, j).
+//   1. mean_kernel          reads W, writes wbar (the sum is kept in fp64; besides the fp32 mean its
+//                           rounding error is kept too, so that the later steps subtract the mean to
+//                           almost fp64 accuracy: layers that hardly move between checkpoints have
+//                           |w_j - wbar| << |wbar| and would otherwise lose most of their digits);
+//   2. the per-layer squared norms of c = (W - wbar_hi) - wbar_lo, centred in registers (the layer-wise
+//      projection kernel in its squares mode);
+//   3. rinv_kernel          1/norm per (layer, vector), 0 for a zero vector; the norms if wanted;
+//   4. centre_scale_kernel  E_ij = c_ij * 1/norm of (layer of i, j), zero padding; may run in place.
+// W is read three times and E written once; the centred matrix is never stored unscaled.
 #include "twa_device.h"
 #include "twa_host.h"
 
