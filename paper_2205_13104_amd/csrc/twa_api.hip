@@ -69,8 +69,10 @@ static int64_t ld_multiple(int dtype) { return scaled(dtype) || minmax(dtype) ? 
 static int check_dims(int64_t D, int32_t n, int64_t ld, int dtype) {
   const int bits = bits_of(dtype);
   if (D <= 0 || n <= 0 || n > TWA_MAX_N || ld < D) return TWA_ERR_SHAPE;
-  if ((D * (int64_t)bits + 7) / 8 >= ((int64_t)1 << 32)) return TWA_ERR_SHAPE;
-  if (D * 4 >= ((int64_t)1 << 32)) return TWA_ERR_SHAPE;          // g and w are fp32 vectors of length D
+  // byte offsets inside a stored vector, g and w are 32-bit, and "one access past the end" must not wrap
+  constexpr int64_t kOffsetLimit = ((int64_t)1 << 32) - 64;
+  if ((D * (int64_t)bits + 7) / 8 >= kOffsetLimit) return TWA_ERR_SHAPE;
+  if (D * 4 >= kOffsetLimit) return TWA_ERR_SHAPE;                 // g and w are fp32 vectors of length D
   if (ld % ld_multiple(dtype) != 0) return TWA_ERR_ALIGN;
   return TWA_OK;
 }

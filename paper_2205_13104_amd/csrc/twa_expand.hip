@@ -54,9 +54,22 @@ struct Expander {
   // corrections are applied at the end)
   // Min-max formats (Sec. 4.6): mm_a scales every coefficient, and mm_b * sum_j s_j is added at the end
   // (mm_b = b_l + bias * a_l for codes stored relative to `bias`).
+  // Layer-wise, [lo, hi) are the layer's elements: the stored vectors are read through a descriptor that ends
+  // with the layer, and a lane whose elements all lie in front of the layer reads at the descriptor's end --
+  // out-of-range loads return 0 and move no memory, so a tile of a short layer costs the layer's bytes.
   __device__ __forceinline__ void accumulate(int64_t e0, float (&acc)[VPL][EPV], const float* __restrict__ sv,
-                                             float mm_a = 1.0f, float mm_b = 0.0f) const {
+                                             float mm_a = 1.0f, float mm_b = 0.0f, uint32_t lo = 0u,
+                                             uint32_t hi = 0u) const {
     const int n = P.n;
+    uint32_t p_bytes = col_bytes;
+    uint32_t voff[VPL];
+    if constexpr (LAYERED) p_bytes = (uint32_t)(((((int64_t)hi * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
+      voff[v] = (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3);
+      if constexpr (LAYERED) voff[v] = e0 + loc + EPV <= (int64_t)lo ? p_bytes : voff[v];
+    }
     float ssum = 0.0f;
     float tsum[VPL];
 #pragma unroll
@@ -83,11 +96,11 @@ struct Expander {
           ssum += sj;
           sj *= mm_a;
         }
-        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
+        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? p_bytes : 0u);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
           const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
-          raw[u][v] = load_codes<DT>(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
+          raw[u][v] = load_codes<DT>(rc, voff[v]);
           if constexpr (S::kScaled) {
             // scale index inside the tile's run of spans: [span][vector][block in span];
             // an unused column slot reads far outside the range and gets 0
@@ -352,13 +365,13 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   if (tb_tile) {
     const Where at = locate(first, cur);
     float acc[VPL][EPV];
-    x.accumulate(at.e0, acc, at.sv, at.mm_a, at.mm_b);
+    x.accumulate(at.e0, acc, at.sv, at.mm_a, at.mm_b, at.lo, at.hi);
     x.rows_to_lds(acc[0], tbuf[wave]);
   }
   if (lds_tile) {
     const Where at = locate(t_lds, cur);
     float acc[VPL][EPV];
-    x.accumulate(at.e0, acc, at.sv, at.mm_a, at.mm_b);
+    x.accumulate(at.e0, acc, at.sv, at.mm_a, at.mm_b, at.lo, at.hi);
 #pragma unroll
     for (int v = 0; v < VPL; ++v) x.rows_to_lds(acc[v], lhold[wave][v]);
   }
@@ -375,7 +388,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   for (int i = 0; i < HOLD; ++i) {
     const Where at = ahead;
     if (owned(i + 1)) ahead = locate(first + 4 * (int64_t)(reg0 + i + 1), cur);
-    if (owned(i)) x.accumulate(at.e0, held[i], at.sv, at.mm_a, at.mm_b);
+    if (owned(i)) x.accumulate(at.e0, held[i], at.sv, at.mm_a, at.mm_b, at.lo, at.hi);
   }
   // ---- the burst, phase 1: the new weights are formed where the sums were (the same tiles again, found
   //      with a cursor of their own) ...

@@ -102,6 +102,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
     uint32_t g_bytes = (uint32_t)(D * 4);
     uint32_t head = 0;                  // elements of this tile in front of its layer's first element
     uint32_t tail = TILE;               // elements of this tile up to its layer's end
+    uint32_t p_bytes = col_bytes;       // bytes of a stored vector that this tile may read: up to its layer's end
     if constexpr (LAYERED) {
       if (lc.behind(plan, t)) {                                  // this tile starts the next (non-empty) layer
         flush((int)blockIdx.x + lc.cur);                         // a workgroup never holds a layer without tiles
@@ -112,6 +113,21 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
       g_bytes = (uint32_t)(hi * 4);                              // the gradient ends with the layer
       head = lc.lo > e0 ? (uint32_t)(lc.lo - e0 < TILE ? lc.lo - e0 : TILE) : 0u;
       tail = hi - e0 < TILE ? (uint32_t)(hi > e0 ? hi - e0 : 0) : (uint32_t)TILE;
+      p_bytes = (uint32_t)((((hi * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
+    }
+    // Where this lane's elements sit in a stored vector.  A tile of a short layer is mostly outside the
+    // layer: the descriptor ends with the layer, and a lane whose elements all lie in front of the layer
+    // reads at the descriptor's end instead -- out-of-range loads return 0 and move no memory, so such a
+    // tile costs the layer's bytes, not a whole tile's.
+    uint32_t voff[VPL];
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;
+      voff[v] = (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3);
+      if constexpr (LAYERED) {
+        voff[v] = loc + EPV <= head ? p_bytes : voff[v];
+        asm volatile("" : "+v"(voff[v]));      // one register per vector, formed once per tile
+      }
     }
 
     // ---- this lane's slice of the gradient(s); the descriptor ends at element D (at the end of
@@ -185,11 +201,11 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
         const int slot = ch * U + u;
         const bool valid = slot < ncol;
         const int col = valid ? c0 + slot : 0;
-        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
+        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? p_bytes : 0u);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
           const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
-          raw[u][v] = load_codes<DT>(rc, (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3));
+          raw[u][v] = load_codes<DT>(rc, voff[v]);
           if constexpr (S::kScaled) {
             // scale index inside the tile's run of spans: [span][vector][block in span];
             // an unused column slot reads far outside the range and gets 0
