@@ -53,7 +53,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1000,
                     help="untimed steps; the device needs ~0.5 s of this load before the step time settles")
     ap.add_argument("--workload", default="imagenet_resnet50", help="name in synth.WORKLOADS")
-    ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4", "mm16", "mm8", "mm4", "mm2", "mm1"],
+    ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4", "mm16", "mm8", "mm4", "mm3", "mm2", "mm1"],
                     help="mm16 .. mm1: the paper's per-layer min-max codes of that many bits (layer-wise mode only)")
     ap.add_argument("--mode", default="whole", choices=["whole", "layerwise"],
                     help="whole: the headline step (orthonormal basis, s = P^T g, w -= lr P s).  layerwise: Alg. 1 as "
@@ -84,7 +84,7 @@ def main():
     D = args.D or wl.D
     n = wl.n
     dtype = {"f32": twa.F32, "bf16": twa.BF16, "i8": twa.I8, "i4": twa.I4, "mm8": twa.U8MM, "mm4": twa.U4MM,
-             "mm16": twa.U16MM, "mm2": twa.U2MM, "mm1": twa.U1MM}[args.storage]
+             "mm16": twa.U16MM, "mm3": twa.U3MM, "mm2": twa.U2MM, "mm1": twa.U1MM}[args.storage]
     layerwise = args.mode == "layerwise"
     if dtype in twa.MINMAX_TYPES and not layerwise:
         sys.exit("bench.py: the min-max formats exist for the layer-wise calls only (use --mode layerwise)")

@@ -71,7 +71,13 @@ typedef enum twa_dtype {
   TWA_U4MM = 5, /* B = 4: two codes per byte, element i in the LOW nibble when i is even         */
   TWA_U16MM = 6, /* B <= 16: the 16-bit word holds c - 2^(B-1) as an int16; `block` carries B (0: 16) */
   TWA_U2MM = 7,  /* B = 2: four codes per byte, element i in bits 2*(i mod 4) .. 2*(i mod 4)+1    */
-  TWA_U1MM = 8   /* B = 1: eight codes per byte, element i in bit i mod 8                         */
+  TWA_U1MM = 8,  /* B = 1: eight codes per byte, element i in bit i mod 8                         */
+  TWA_U3MM = 9   /* B = 3 in exactly 3 bits: every 32 consecutive elements are three 32-bit words.
+                    Element e = 16h + 4k + m of the group (h in 0..1, k in 0..3, m in 0..3) has its
+                    two LOW bits in word h at bits 2(4k+m) .. 2(4k+m)+1 -- words 0 and 1 are the
+                    TWA_U2MM layout of c mod 4 -- and its HIGH bit in word 2 at bit 8k + m + 4h, so
+                    that one shift and mask of word 2 lines four high bits up with four byte lanes of
+                    low parts                                                                       */
 } twa_dtype;
 
 /*
@@ -271,9 +277,9 @@ int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan
  * evaluated in fp64 with ties to even (the paper names no tie rule); a_l = 0 (a constant layer)
  * gives c = 0; the factors are stored rounded to binary32 (b_l exactly).  The stored value is
  * within a_l/2 of p.
- *   bits [in]     B: 1 with out->dtype TWA_U1MM, 1..2 with TWA_U2MM, 1..4 with TWA_U4MM, 1..8 with
- *                 TWA_U8MM, 1..16 with TWA_U16MM.  The paper studies B in {1, 2, 3, 4, 8, 16}: each has a
- *                 container of its own except B = 3, which travels in nibbles.  Codes of fewer bits than
+ *   bits [in]     B: 1 with out->dtype TWA_U1MM, 1..2 with TWA_U2MM, 1..3 with TWA_U3MM, 1..4 with TWA_U4MM,
+ *                 1..8 with TWA_U8MM, 1..16 with TWA_U16MM.  Each of the widths 1, 2, 3, 4, 8 and 16 has a
+ *                 container of exactly that many bits per code.  Codes of fewer bits than
  *                 the container holds are stored in it (same values and factors as B-bit storage would
  *                 give, without the extra saving of memory); bytes and words hold them centred,
  *                 c - 2^(B-1), so that the fused dequantisation loses no bits to cancellation.

@@ -11,7 +11,7 @@ import torch
 from . import twa_oracle as orc
 
 
-U8MM, U4MM, U16MM, U2MM, U1MM = 4, 5, 6, 7, 8      # dtype codes of the paper's min-max format in the C descriptor
+U8MM, U4MM, U16MM, U2MM, U1MM, U3MM = 4, 5, 6, 7, 8, 9      # dtype codes of the paper's min-max format in the C descriptor
 
 
 def to_oracle(pm, cols=None, layer_off=None) -> orc.Pmat:
@@ -20,9 +20,20 @@ def to_oracle(pm, cols=None, layer_off=None) -> orc.Pmat:
     The min-max formats need the layer table (`layer_off`, L+1 offsets) the matrix was quantised with;
     their packed codes are spread out to one unsigned 16-bit code per element, as the oracle keeps them."""
     data = pm.data if cols is None else pm.data[cols]
-    if pm.dtype in (U8MM, U4MM, U16MM, U2MM, U1MM):
+    if pm.dtype in (U8MM, U4MM, U16MM, U2MM, U1MM, U3MM):
         raw = data.cpu().numpy()
-        if pm.dtype in (U2MM, U1MM):
+        if pm.dtype == U3MM:
+            # groups of 32 elements = three little-endian 32-bit words: element e = 16h + 4k + m has its two low
+            # bits in word h at bit 2(4k + m), its high bit in word 2 at bit 8k + m + 4h
+            w = np.ascontiguousarray(raw).view(np.uint32).reshape(raw.shape[0], -1, 3).astype(np.uint64)
+            codes = np.empty((w.shape[0], w.shape[1], 32), dtype=np.uint16)
+            for e in range(32):
+                h, f = e >> 4, e & 15
+                k, m = f >> 2, f & 3
+                codes[:, :, e] = ((w[:, :, h] >> np.uint64(2 * f)) & np.uint64(3)) | \
+                                 (((w[:, :, 2] >> np.uint64(8 * k + m + 4 * h)) & np.uint64(1)) << np.uint64(2))
+            codes = codes.reshape(w.shape[0], -1)
+        elif pm.dtype in (U2MM, U1MM):
             bits = 2 if pm.dtype == U2MM else 1
             per = 8 // bits                                                     # codes per byte, low bits first
             b = raw.astype(np.uint16)

@@ -16,9 +16,9 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtwa.so")
 
-F32, BF16, I8, I4, U8MM, U4MM, U16MM, U2MM, U1MM = 0, 1, 2, 3, 4, 5, 6, 7, 8
-MINMAX_TYPES = (U8MM, U4MM, U16MM, U2MM, U1MM)
-BITS_OF = {F32: 32, BF16: 16, I8: 8, I4: 4, U8MM: 8, U4MM: 4, U16MM: 16, U2MM: 2, U1MM: 1}
+F32, BF16, I8, I4, U8MM, U4MM, U16MM, U2MM, U1MM, U3MM = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
+MINMAX_TYPES = (U8MM, U4MM, U16MM, U2MM, U1MM, U3MM)
+BITS_OF = {F32: 32, BF16: 16, I8: 8, I4: 4, U8MM: 8, U4MM: 4, U16MM: 16, U2MM: 2, U1MM: 1, U3MM: 3}
 MAX_N, MAX_K, LD_MULTIPLE, SCALE_SPAN, MAX_LAYERS = 128, 8, 128, 2048, 65536
 DEFAULT_BLOCK = {I8: 128, I4: 64}
 
@@ -144,7 +144,7 @@ def build_basis_workspace_bytes(n: int) -> int:
 
 
 _TORCH_OF = {F32: torch.float32, BF16: torch.bfloat16, I8: torch.int8, I4: torch.uint8, U8MM: torch.int8,
-             U4MM: torch.uint8, U16MM: torch.int16, U2MM: torch.uint8, U1MM: torch.uint8}
+             U4MM: torch.uint8, U16MM: torch.int16, U2MM: torch.uint8, U1MM: torch.uint8, U3MM: torch.uint8}
 
 
 @dataclass
@@ -318,10 +318,11 @@ def expand_update_layers(P: Pmat, S: torch.Tensor, plan: LayerPlan, w: torch.Ten
 
 def quantize_minmax(P: torch.Tensor, D: int, plan: LayerPlan, bits: int = 4) -> Pmat:
     """twa_quantize_minmax: the paper's per-layer min-max format (Sec. 4.6), B = 1..16 bits, in the
-    smallest container that holds them (1 and 2 bits packed, up to 4 in nibbles, up to 8 in bytes, else words)."""
+    smallest container that holds them (1, 2, 3 and 4 bits packed at that width, up to 8 in bytes, else words)."""
     assert P.dtype == torch.float32 and P.dim() == 2 and P.is_contiguous() and plan.D == D
     assert 1 <= bits <= 16
-    dtype = U1MM if bits == 1 else U2MM if bits == 2 else U4MM if bits <= 4 else U8MM if bits <= 8 else U16MM
+    dtype = (U1MM if bits == 1 else U2MM if bits == 2 else U3MM if bits == 3 else U4MM if bits == 4
+             else U8MM if bits <= 8 else U16MM)
     n, ldp = P.shape
     ld, _, _ = pmat_bytes(dtype, D, n)
     cols = ld * BITS_OF[dtype] // 8 if BITS_OF[dtype] < 8 else ld

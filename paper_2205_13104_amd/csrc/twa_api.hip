@@ -47,7 +47,8 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 static bool scaled(int dtype) { return dtype == TWA_I8 || dtype == TWA_I4; }
 static bool minmax(int dtype) {
-  return dtype == TWA_U8MM || dtype == TWA_U4MM || dtype == TWA_U16MM || dtype == TWA_U2MM || dtype == TWA_U1MM;
+  return dtype == TWA_U8MM || dtype == TWA_U4MM || dtype == TWA_U16MM || dtype == TWA_U2MM || dtype == TWA_U1MM ||
+         dtype == TWA_U3MM;
 }
 static int bits_of(int dtype) {
   switch (dtype) {
@@ -60,6 +61,7 @@ static int bits_of(int dtype) {
     case TWA_U16MM: return 16;
     case TWA_U2MM: return 2;
     case TWA_U1MM: return 1;
+    case TWA_U3MM: return 3;
     default: return 0;
   }
 }

@@ -10,6 +10,7 @@ namespace twa {
 
 using u32x4 = unsigned int __attribute__((ext_vector_type(4)));
 using u32x2 = unsigned int __attribute__((ext_vector_type(2)));
+using u32x3 = unsigned int __attribute__((ext_vector_type(3)));
 using rsrc_t = __amdgpu_buffer_rsrc_t;
 
 constexpr int kWave = 64;
@@ -120,8 +121,16 @@ template <> struct Store<TWA_U1MM> {
   static constexpr bool kScaled = false;
   static constexpr int kScaleBytes = 0;
 };
+// Three bits per code, packed exactly: a lane's 32 elements are 12 bytes, fetched with a 96-bit load.
+template <> struct Store<TWA_U3MM> {
+  static constexpr int kEPV = 32;
+  static constexpr int kBitsPerElem = 3;
+  static constexpr bool kScaled = false;
+  static constexpr int kScaleBytes = 0;
+};
 template <int DT>
-constexpr bool kMinMax = DT == TWA_U8MM || DT == TWA_U4MM || DT == TWA_U16MM || DT == TWA_U2MM || DT == TWA_U1MM;
+constexpr bool kMinMax = DT == TWA_U8MM || DT == TWA_U4MM || DT == TWA_U16MM || DT == TWA_U2MM || DT == TWA_U1MM ||
+                         DT == TWA_U3MM;
 template <int DT> constexpr bool kNibbles = DT == TWA_I4 || DT == TWA_U4MM;
 // (The byte and word containers of the min-max formats hold c - 2^(B-1) for B-bit codes c: centred
 // whatever B is, so that the fused dequantisation does not lose bits to cancellation.  The bias travels
@@ -213,13 +222,43 @@ template <> __device__ __forceinline__ void decode<TWA_U1MM>(const u32x4& v, flo
   }
 }
 
+// B = 3: words 0 and 1 hold the low two bits like U2MM, word 2 the high bits, placed so that
+// (w2 >> (m + 4h)) & 0x01010101 has the high bit of element 16h + 4k + m in byte k -- the element whose low
+// part (w_h >> 2m) & 0x03030303 has in byte k.
+template <> __device__ __forceinline__ void decode<TWA_U3MM>(const u32x4& v, float* raw) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const uint32_t hi = (v[2] >> (m + 4 * h)) & 0x01010101u;
+      uint32_t t = ((v[h] >> (2 * m)) & 0x03030303u) | (hi << 2);
+      asm volatile("" : "+v"(t));                          // keep the combined word: one byte convert per element
+      raw[16 * h + 0 + m] = (float)(t & 0xff);
+      raw[16 * h + 4 + m] = (float)((t >> 8) & 0xff);
+      raw[16 * h + 8 + m] = (float)((t >> 16) & 0xff);
+      raw[16 * h + 12 + m] = (float)(t >> 24);
+    }
+  }
+}
+
+// Bytes of a stored vector that hold its first `elems` elements, rounded up to whole dwords (the range check of a
+// descriptor drops a dword that is only partly inside).  The 3-bit type is packed in groups of 32 elements whose
+// third word carries a bit of every element of the group: whole groups.
+template <int DT> __device__ __forceinline__ uint32_t stored_bytes(int64_t elems) {
+  if constexpr (DT == TWA_U3MM) return (uint32_t)(((elems + 31) >> 5) * 12);
+  return (uint32_t)((((elems * Store<DT>::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
+}
+
 // The kEPV stored elements of one lane, streamed: 128 bits for most types, 64 or 32 for the 2- and 1-bit
 // codes (the unused words of the result are zero and never read).
 template <int DT> __device__ __forceinline__ u32x4 load_codes(rsrc_t r, uint32_t voff) {
   constexpr int kBits = Store<DT>::kEPV * Store<DT>::kBitsPerElem;
-  static_assert(kBits == 128 || kBits == 64 || kBits == 32, "a lane's elements are one load");
+  static_assert(kBits == 128 || kBits == 96 || kBits == 64 || kBits == 32, "a lane's elements are one load");
   if constexpr (kBits == 128) {
     return ld128_stream(r, voff);
+  } else if constexpr (kBits == 96) {
+    const u32x3 t = __builtin_amdgcn_raw_buffer_load_b96(r, (int)voff, 0, /*nt*/ 2);
+    return u32x4{t[0], t[1], t[2], 0u};
   } else if constexpr (kBits == 64) {
     const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, 0, /*nt*/ 2);
     return u32x4{t[0], t[1], 0u, 0u};

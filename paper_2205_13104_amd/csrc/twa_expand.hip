@@ -63,7 +63,7 @@ struct Expander {
     const int n = P.n;
     uint32_t p_bytes = col_bytes;
     uint32_t voff[VPL];
-    if constexpr (LAYERED) p_bytes = (uint32_t)(((((int64_t)hi * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
+    if constexpr (LAYERED) p_bytes = stored_bytes<DT>((int64_t)hi);
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
@@ -312,7 +312,7 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   // is only partly inside, and the tail bytes are padding of the same vector (ld >= D, ld % 128 == 0)
   const X x{P,
             lane,
-            (uint32_t)((((D * X::S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3),
+            stored_bytes<DT>(D),
             (P.ld * X::S::kBitsPerElem) >> 3,
             kScaleSpanShift - P.block_shift,
             X::S::kScaled ? ((uint32_t)P.n << (kScaleSpanShift - P.block_shift)) * (uint32_t)X::S::kScaleBytes : 0u,
@@ -504,6 +504,12 @@ static int launch_expand_any(const PView& P, int dtype, const float* s, const fl
     case TWA_U1MM:
       if constexpr (LAYERED) {
         launch_expand_cfg<TWA_U1MM, 8, 1, 5, 2, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
+        break;
+      }
+      return TWA_ERR_DTYPE;
+    case TWA_U3MM:
+      if constexpr (LAYERED) {
+        launch_expand_cfg<TWA_U3MM, 8, 1, 5, 2, true>(P, s, w_in, w, lr, g_tilde, max_grid, st, plan_dev, L);
         break;
       }
       return TWA_ERR_DTYPE;

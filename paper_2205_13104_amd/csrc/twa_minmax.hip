@@ -200,6 +200,75 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
   }
 }
 
+// B = 3, packed exactly: a thread owns a group of 32 consecutive elements = three dwords.  Element
+// e = 16h + 4k + m of the group has its two low bits in word h at bits 2(4k+m).., its high bit in word 2 at
+// bit 8k + m + 4h (the layout the step kernels' decoder lines up with byte lanes).  Same arithmetic as above.
+__global__ __launch_bounds__(256) void minmax_codes3_kernel(const float* __restrict__ P, int64_t D, int64_t ldp,
+                                                            uint8_t* __restrict__ codes, int64_t ld,
+                                                            const int64_t* __restrict__ off, int L,
+                                                            const float* __restrict__ ab,
+                                                            const double* __restrict__ a64,
+                                                            const double* __restrict__ ra64, double levels) {
+  const int j = blockIdx.y;
+  const int64_t ngroups = ld / 32;
+  const float* p = P + (int64_t)j * ldp;
+  uint32_t* out = reinterpret_cast<uint32_t*>(codes + (((int64_t)j * ld * 3) >> 3));
+  for (int64_t grp = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; grp < ngroups;
+       grp += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i0 = grp * 32;
+    uint32_t w0 = 0, w1 = 0, w2 = 0;                 // padding: code 0
+    if (i0 < D) {
+      int lo = 0, hi = L - 1;                        // largest l with off[l] <= i0
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (off[mid] <= i0) lo = mid; else hi = mid - 1;
+      }
+      int l = lo;
+      int64_t next = l < L - 1 ? off[l + 1] : D;
+      double a = a64[l], ra = ra64[l], b = (double)ab[2 * l + 1];
+#pragma unroll
+      for (int e4 = 0; e4 < 32; e4 += 4) {
+        const int64_t i4 = i0 + e4;
+        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (i4 + 4 <= D) {
+          const float4 t = *reinterpret_cast<const float4*>(p + i4);
+          v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = i4 + r < D ? p[i4 + r] : 0.0f;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int64_t i = i4 + r;
+          uint32_t c = 0;
+          if (i < D) {
+            if (i >= next) {
+              while (l < L - 1 && off[l + 1] <= i) ++l;
+              next = l < L - 1 ? off[l + 1] : D;
+              a = a64[l];
+              ra = ra64[l];
+              b = (double)ab[2 * l + 1];
+            }
+            const double t = (double)v[r] - b;
+            const double x = t * ra;
+            double q = rint(x);
+            if (fabs(fabs(x - q) - 0.5) < 1e-6) q = rint(t / a);
+            q = q < 0.0 ? 0.0 : (q > levels ? levels : q);
+            c = (uint32_t)q;
+          }
+          const int e = e4 + r;                      // compile-time after unrolling
+          const int h = e >> 4, f = e & 15, k = f >> 2, m = f & 3;
+          if (h == 0) w0 |= (c & 3u) << (2 * f); else w1 |= (c & 3u) << (2 * f);
+          w2 |= ((c >> 2) & 1u) << (8 * k + m + 4 * h);
+        }
+      }
+    }
+    out[3 * grp] = w0;
+    out[3 * grp + 1] = w1;
+    out[3 * grp + 2] = w2;
+  }
+}
+
 size_t minmax_workspace_bytes(int L) { return (size_t)L * (2 * sizeof(uint32_t) + 2 * sizeof(double)); }
 
 int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const void* plan_dev, int L, int dtype,
@@ -225,6 +294,14 @@ int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const 
 #define TWA_CODES(DT_, WPT_)                                                                                       \
   hipLaunchKernelGGL((minmax_codes_kernel<DT_, WPT_>), dim3(gx, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L, \
                      ab, a64, ra64, levels, 1u << (bits - 1))
+  if (dtype == TWA_U3MM) {
+    const int64_t ng = ld / 32;
+    int g3 = (int)((ng + 255) / 256);
+    if (g3 > cus * 8) g3 = cus * 8;
+    hipLaunchKernelGGL(minmax_codes3_kernel, dim3(g3, n), dim3(256), 0, st, P, D, ldp, codes, ld, plan.off, L, ab, a64,
+                       ra64, levels);
+    return hip_check(hipGetLastError());
+  }
   switch (dtype) {
     case TWA_U16MM: TWA_CODES(TWA_U16MM, 4); break;
     case TWA_U8MM: TWA_CODES(TWA_U8MM, 4); break;

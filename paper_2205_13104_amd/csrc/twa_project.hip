@@ -60,7 +60,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
 
   // bytes of one stored vector, rounded up to whole dwords: the range check drops a dword that
   // is only partly inside, and the tail bytes are padding of the same vector (ld >= D, ld % 128 == 0)
-  const uint32_t col_bytes = (uint32_t)((((D * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
+  const uint32_t col_bytes = stored_bytes<DT>(D);
   const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
   const int gshift = kScaleSpanShift - P.block_shift;            // log2(scales per span and vector)
   const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes : 0u;
@@ -113,7 +113,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
       g_bytes = (uint32_t)(hi * 4);                              // the gradient ends with the layer
       head = lc.lo > e0 ? (uint32_t)(lc.lo - e0 < TILE ? lc.lo - e0 : TILE) : 0u;
       tail = hi - e0 < TILE ? (uint32_t)(hi > e0 ? hi - e0 : 0) : (uint32_t)TILE;
-      p_bytes = (uint32_t)((((hi * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
+      p_bytes = stored_bytes<DT>(hi);
     }
     // Where this lane's elements sit in a stored vector.  A tile of a short layer is mostly outside the
     // layer: the descriptor ends with the layer, and a lane whose elements all lie in front of the layer
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(256) void project_batched_kernel(PView P, const flo
   const int c0 = wave * cpw;
   int ncol = P.n - c0;
   ncol = ncol < 0 ? 0 : (ncol > cpw ? cpw : ncol);
-  const uint32_t col_bytes = (uint32_t)((((D * S::kBitsPerElem + 7) >> 3) + 3) & ~(int64_t)3);
+  const uint32_t col_bytes = stored_bytes<DT>(D);
   const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
   const int gshift = kScaleSpanShift - P.block_shift;
   const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes : 0u;
@@ -651,6 +651,7 @@ int launch_project_layers(const PView& P, int dtype, const float* g, const void*
     case TWA_U16MM: return launch_project_layers_dt<TWA_U16MM, 2>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     case TWA_U2MM: return launch_project_layers_dt<TWA_U2MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     case TWA_U1MM: return launch_project_layers_dt<TWA_U1MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
+    case TWA_U3MM: return launch_project_layers_dt<TWA_U3MM, 1>(P, g, plan_dev, L, S, partial, max_grid, st, bs);
     default: return TWA_ERR_DTYPE;
   }
 }

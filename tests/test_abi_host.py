@@ -46,7 +46,7 @@ def test_pmat_bytes_follow_the_memory_table():
         twa.pmat_bytes(99, D, n)
     assert e.value.code == twa.ERR_DTYPE
     # the paper's formats at B bits: nBD/8 bytes of codes (the 8L bytes of factors are the caller's)
-    for dt, B in ((twa.U16MM, 16), (twa.U8MM, 8), (twa.U4MM, 4), (twa.U2MM, 2), (twa.U1MM, 1)):
+    for dt, B in ((twa.U16MM, 16), (twa.U8MM, 8), (twa.U4MM, 4), (twa.U3MM, 3), (twa.U2MM, 2), (twa.U1MM, 1)):
         ld, db, sb = twa.pmat_bytes(dt, D, n)
         assert ld == (D + 2047) // 2048 * 2048 and db == n * B * ld // 8 and sb == 0
     with pytest.raises(twa.TwaError) as e:

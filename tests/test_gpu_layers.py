@@ -144,7 +144,8 @@ def test_layer_rows_add_up_to_the_whole_model_projection():
                                       (4, 300_017, 100), (4, 1_234_567, 33), (1, 300_017, 20), (2, 300_017, 20),
                                       (3, 70001, 7), (6, 70001, 7), (16, 70001, 7), (16, 300_017, 100),
                                       (16, 1_234_567, 33), (12, 70001, 7), (9, 300_017, 20), (5, 300_017, 20),
-                                      (2, 70001, 7), (2, 1_234_567, 100), (1, 70001, 7), (1, 1_234_567, 100)])
+                                      (2, 70001, 7), (2, 1_234_567, 100), (1, 70001, 7), (1, 1_234_567, 100),
+                                      (3, 300_017, 100), (3, 1_234_567, 33)])
 def test_minmax_format_matches_oracle(bits, D, n):
     """The paper's own quantiser (Sec. 4.6): codes and factors bit-exact against the fp64 oracle, then the
     layer-wise step on the stored matrix within the bar."""
@@ -196,7 +197,8 @@ def test_minmax_format_matches_oracle(bits, D, n):
     assert e.value.code == twa.ERR_DTYPE
 
 
-@pytest.mark.parametrize("bits,top", [(4, 15.0), (4, 45.0), (8, 255.0), (8, 765.0), (2, 3.0), (16, 65535.0)])
+@pytest.mark.parametrize("bits,top", [(4, 15.0), (4, 45.0), (8, 255.0), (8, 765.0), (2, 3.0), (16, 65535.0), (3, 7.0),
+                                      (3, 21.0)])
 def test_minmax_codes_at_exact_ties(bits, top):
     """Values whose quotient (p - b) / a is exactly half way between two codes, for a step a that is and is not a
     power of two: the quantiser takes these through the true quotient and rounds them to even, as the oracle does."""
