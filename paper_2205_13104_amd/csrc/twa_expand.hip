@@ -54,21 +54,19 @@ struct Expander {
   // corrections are applied at the end)
   // Min-max formats (Sec. 4.6): mm_a scales every coefficient, and mm_b * sum_j s_j is added at the end
   // (mm_b = b_l + bias * a_l for codes stored relative to `bias`).
-  // Layer-wise, [lo, hi) are the layer's elements: the stored vectors are read through a descriptor that ends
-  // with the layer, and a lane whose elements all lie in front of the layer reads at the descriptor's end --
-  // out-of-range loads return 0 and move no memory, so a tile of a short layer costs the layer's bytes.
+  // Layer-wise, [lo, hi) are the layer's elements: a lane whose elements all lie in front of the layer or
+  // behind it reads at the end of the descriptor -- out-of-range loads return 0 and move no memory, so a
+  // tile of a short layer costs the layer's bytes.  (The descriptors stay the same for every tile.)
   __device__ __forceinline__ void accumulate(int64_t e0, float (&acc)[VPL][EPV], const float* __restrict__ sv,
                                              float mm_a = 1.0f, float mm_b = 0.0f, uint32_t lo = 0u,
                                              uint32_t hi = 0u) const {
     const int n = P.n;
-    uint32_t p_bytes = col_bytes;
     uint32_t voff[VPL];
-    if constexpr (LAYERED) p_bytes = stored_bytes<DT>((int64_t)hi);
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
       voff[v] = (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3);
-      if constexpr (LAYERED) voff[v] = e0 + loc + EPV <= (int64_t)lo ? p_bytes : voff[v];
+      if constexpr (LAYERED) voff[v] = (e0 + loc + EPV <= (int64_t)lo || e0 + loc >= (int64_t)hi) ? col_bytes : voff[v];
     }
     float ssum = 0.0f;
     float tsum[VPL];
@@ -96,7 +94,7 @@ struct Expander {
           ssum += sj;
           sj *= mm_a;
         }
-        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? p_bytes : 0u);
+        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
           const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile

@@ -102,7 +102,6 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
     uint32_t g_bytes = (uint32_t)(D * 4);
     uint32_t head = 0;                  // elements of this tile in front of its layer's first element
     uint32_t tail = TILE;               // elements of this tile up to its layer's end
-    uint32_t p_bytes = col_bytes;       // bytes of a stored vector that this tile may read: up to its layer's end
     if constexpr (LAYERED) {
       if (lc.behind(plan, t)) {                                  // this tile starts the next (non-empty) layer
         flush((int)blockIdx.x + lc.cur);                         // a workgroup never holds a layer without tiles
@@ -113,19 +112,19 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
       g_bytes = (uint32_t)(hi * 4);                              // the gradient ends with the layer
       head = lc.lo > e0 ? (uint32_t)(lc.lo - e0 < TILE ? lc.lo - e0 : TILE) : 0u;
       tail = hi - e0 < TILE ? (uint32_t)(hi > e0 ? hi - e0 : 0) : (uint32_t)TILE;
-      p_bytes = stored_bytes<DT>(hi);
     }
     // Where this lane's elements sit in a stored vector.  A tile of a short layer is mostly outside the
-    // layer: the descriptor ends with the layer, and a lane whose elements all lie in front of the layer
-    // reads at the descriptor's end instead -- out-of-range loads return 0 and move no memory, so such a
-    // tile costs the layer's bytes, not a whole tile's.
+    // layer: a lane whose elements all lie in front of the layer or behind it reads at the end of the
+    // descriptor instead -- out-of-range loads return 0 and move no memory, so such a tile costs the
+    // layer's bytes, not a whole tile's.  (The descriptors themselves stay the same for every tile: ending
+    // them with the layer made them loop-variant and cost the 1- and 2-bit kernels 15-28 %.)
     uint32_t voff[VPL];
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;
       voff[v] = (uint32_t)((((uint64_t)e0 + loc) * S::kBitsPerElem) >> 3);
       if constexpr (LAYERED) {
-        voff[v] = loc + EPV <= head ? p_bytes : voff[v];
+        voff[v] = (loc + EPV <= head || loc >= tail) ? col_bytes : voff[v];
         asm volatile("" : "+v"(voff[v]));      // one register per vector, formed once per tile
       }
     }
@@ -201,7 +200,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
         const int slot = ch * U + u;
         const bool valid = slot < ncol;
         const int col = valid ? c0 + slot : 0;
-        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? p_bytes : 0u);
+        const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
           const uint32_t loc = (uint32_t)(v * kWave + lane) * EPV;     // element inside the tile
