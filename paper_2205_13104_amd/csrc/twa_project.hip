@@ -32,11 +32,13 @@ namespace twa {
 // reduction kernel knows from the plan which workgroups contributed to a layer.
 // SQUARES (with LAYERED, F32): no gradient; the sums are the squares of the CENTRED elements of the
 // layer, sum_i ((W_ij - hi_i) - lo_i)^2 -- the squared norms that the layer-wise basis divides by
-// (Sec. 4.1, 4.5).  The mean arrives as two binary32 words per element: `g` holds hi, `partial_g` lo.
+// (Sec. 4.1, 4.5).  The mean arrives as two binary32 words per element: `g` holds hi, `aux` lo.
+// `aux` is the one extra buffer of a mode: written for the min-max formats (per-workgroup sums of the
+// gradient, which the zero points b_l multiply), read in the squares mode (the mean's low words), unused else.
 template <int DT, int KB, int U, int NCH, int VPL, bool LAYERED, bool SQUARES = false>
 __device__ __forceinline__ void project_body(PView P, const float* __restrict__ g, int64_t ldg, int kvalid,
                                              float* __restrict__ partial, int cpw, int tiles_per_wg, LayerPlan plan,
-                                             float* __restrict__ partial_g) {
+                                             float* __restrict__ aux) {
   using S = Store<DT>;
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
@@ -77,7 +79,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
   auto flush = [&](int slot_row) {
     if constexpr (kMinMax<DT>) {
       const float tot = wave_sum_to_last_lane(gsum);
-      if (wave == 0 && lane == kSumLane) partial_g[slot_row] = tot;
+      if (wave == 0 && lane == kSumLane) aux[slot_row] = tot;
       gsum = 0.0f;
     }
 #pragma unroll
@@ -144,7 +146,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
           const uint32_t rel = (uint32_t)(v * kWave + lane) * EPV;
 #pragma unroll
           for (int e = 0; e < EPV; ++e) gs[c][v][e] = (rel + e >= head && rel + e < tail) ? 1.0f : 0.0f;
-          const rsrc_t rl = make_rsrc(partial_g, g_bytes);
+          const rsrc_t rl = make_rsrc(aux, g_bytes);
 #pragma unroll
           for (int q = 0; q < EPV / 4; ++q) {
             const u32x4 h = ld128(rg, (elem + 4u * q) * 4u), l = ld128(rl, (elem + 4u * q) * 4u);
@@ -295,8 +297,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 template <int DT, int U, int NCH, int VPL, bool SQUARES>
 __global__ __launch_bounds__(256, 2) void project_layers_kernel(PView P, const float* __restrict__ g,
                                                                 float* __restrict__ partial, int cpw, LayerPlan plan,
-                                                                float* __restrict__ partial_g) {
-  project_body<DT, 1, U, NCH, VPL, true, SQUARES>(P, g, 0, 1, partial, cpw, 0, plan, partial_g);
+                                                                float* __restrict__ aux) {
+  project_body<DT, 1, U, NCH, VPL, true, SQUARES>(P, g, 0, 1, partial, cpw, 0, plan, aux);
 }
 
 // S = P^T G for up to TWA_MAX_K gradients in ONE pass over P (n <= 32 basis vectors; not int4).
@@ -477,7 +479,7 @@ static void divide_tiles(int64_t D, int tile, int max_grid, int* grid, int* tile
 template <int DT, int KB, int VPL, bool LAYERED = false, bool SQUARES = false>
 static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kvalid, float* partial, int max_grid,
                              int* grid_out, hipStream_t st, LayerPlan plan = LayerPlan{nullptr, nullptr, 1},
-                             float* partial_g = nullptr) {
+                             float* aux = nullptr) {
   const int cpw = (P.n + 3) / 4;
   constexpr int tile = kWave * VPL * Store<DT>::kEPV;
   int grid, tiles_per_wg;
@@ -489,7 +491,7 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   do {                                                                                                        \
     if constexpr (LAYERED)                                                                                    \
       hipLaunchKernelGGL((project_layers_kernel<DT, U_, NCH_, VPL, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, \
-                         partial, cpw, plan, partial_g);                                                      \
+                         partial, cpw, plan, aux);                                                            \
     else if constexpr (NCH_ <= 4)                                                                             \
       hipLaunchKernelGGL((project_kernel_two_waves<DT, KB, U_, NCH_, VPL>), dim3(grid), dim3(256), 0, st, P, g, ldg, \
                          kvalid, partial, cpw, tiles_per_wg);                                                 \
