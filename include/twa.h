@@ -146,7 +146,9 @@ int twa_build_basis_workspace_bytes(int32_t n, size_t* bytes);
  *   R_host [out, HOST, optional] n*n doubles, row major, R[a*n + b] (zero below diagonal).
  *   ws, ws_bytes  device workspace of at least twa_build_basis_workspace_bytes(n).
  * Method: CholeskyQR2 -- twice { Gram matrix accumulated in fp64 on the matrix cores,
- * Cholesky factor in fp64 on the host, P <- P R^-1 in fp32 }.  SYNCHRONISES `stream` twice
+ * Cholesky factor in fp64 on the host, P <- P R^-1 in fp32 }; in the second round, whose input is
+ * orthonormal to ~1e-4 already, the products of a 64-row tile are formed and summed in fp32 matrix
+ * instructions and the tiles' sums added in fp64.  SYNCHRONISES `stream` twice
  * (the n x n Gram matrix travels to the host).  On TWA_ERR_RANK (a Cholesky pivot <=
  * 1e-12 * largest diagonal entry) R_host[0], if given, holds the 0-based index of the
  * offending checkpoint and P is unspecified.

@@ -571,7 +571,7 @@ int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P,
   const float* src = W;
   int64_t lds = ldw;
   for (int pass = 0; pass < 2; ++pass) {
-    rc = launch_gram(src, D, n, lds, partial, grid, gram_dev, false, st);
+    rc = launch_gram(src, D, n, lds, partial, grid, gram_dev, false, /*orthonormal_input=*/pass == 1, st);
     if (rc != TWA_OK) return rc;
     int bad = -1;
     rc = factor_gram(gram_dev, n, rinv_dev, R, &bad, st);
@@ -627,7 +627,7 @@ int twa_gram_accumulate(const float* W, int64_t rows, int32_t n, int64_t ldw, do
   const int grid = basis_grid(rows);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   return launch_gram(W, rows, n, ldw, static_cast<double*>(ws), grid, gram, accumulate != 0,
-                     static_cast<hipStream_t>(stream));
+                     /*orthonormal_input=*/false, static_cast<hipStream_t>(stream));
 }
 
 int twa_gram_factor(const double* gram, int32_t n, float* rinv, double* R_host, int32_t compose, void* stream) {

@@ -7,7 +7,8 @@
 //   gram_kernel        G = W^T W, fp32 inputs widened to fp64 (products exact), accumulated with
 //                      v_mfma_f64_16x16x4_f64; LDS-staged D-tiles; only the upper-triangular
 //                      16x16 blocks are computed; per-workgroup partial sums, reduced in a fixed
-//                      order by gram_reduce_kernel.
+//                      order by gram_reduce_kernel.  For the second pass (input orthonormal to ~1e-4)
+//                      the products of a tile run on v_mfma_f32_16x16x4_f32 and the tiles are summed in fp64.
 //   apply_rinv_kernel  Q = W R^-1 (R^-1 upper triangular, fp32) with v_mfma_f32_16x16x4_f32;
 //                      a workgroup owns a tile of rows for ALL n columns, so Q may overwrite W.
 //
@@ -16,6 +17,7 @@
 // run-time block indices the loop had a branch per block, the compiler could not move the LDS reads of a
 // block ahead of the matrix instruction of the previous one, and every instruction waited out an LDS
 // latency (Gram 7.7 -> 6.2 ms, apply 6.5 -> 4.9 ms at D = 25.6 M, n = 100).
+#include <type_traits>
 #include <utility>
 
 #include "twa_device.h"
@@ -95,52 +97,65 @@ template <int NB> struct GramBlocks {
   static constexpr int col_of(int t) { int a = 0; while (t >= NB - a) { t -= NB - a; ++a; } return a + t; }
 };
 
-template <int NB, int WV, int Q>
-__device__ __forceinline__ void gram_block_step(const double (&x)[NB], f64x4 (&acc)[GramBlocks<NB>::NQ]) {
+// T = double: fp32 inputs widened, v_mfma_f64_16x16x4_f64 (products and sums exact to fp64 rounding: what the
+// first pass needs, whose Gram matrix has a condition number near 1/eps32).  T = float: v_mfma_f32_16x16x4_f32 at
+// twice the rate, for a matrix that is orthonormal already to ~1e-4 (the second pass): the caller adds every
+// tile's fp32 sums (16 k-steps) to fp64 sums, so rounding does not build up along D.
+template <typename T> struct GramAcc;
+template <> struct GramAcc<double> { using type = f64x4; };
+template <> struct GramAcc<float> { using type = f32x4; };
+
+template <int NB, int WV, int Q, typename T>
+__device__ __forceinline__ void gram_block_step(const T (&x)[NB], typename GramAcc<T>::type (&acc)[GramBlocks<NB>::NQ]) {
   using B = GramBlocks<NB>;
   if constexpr (WV + 4 * Q < B::T) {
     constexpr int a = B::row_of(WV + 4 * Q), b = B::col_of(WV + 4 * Q);
-    acc[Q] = __builtin_amdgcn_mfma_f64_16x16x4f64(x[a], x[b], acc[Q], 0, 0, 0);
+    if constexpr (sizeof(T) == 8) acc[Q] = __builtin_amdgcn_mfma_f64_16x16x4f64(x[a], x[b], acc[Q], 0, 0, 0);
+    else acc[Q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[a], x[b], acc[Q], 0, 0, 0);
   }
 }
-template <int NB, int WV, int... Q>
-__device__ __forceinline__ void gram_k_step(const double (&x)[NB], f64x4 (&acc)[GramBlocks<NB>::NQ],
+template <int NB, int WV, typename T, int... Q>
+__device__ __forceinline__ void gram_k_step(const T (&x)[NB], typename GramAcc<T>::type (&acc)[GramBlocks<NB>::NQ],
                                             std::integer_sequence<int, Q...>) {
-  (gram_block_step<NB, WV, Q>(x, acc), ...);
+  (gram_block_step<NB, WV, Q, T>(x, acc), ...);
 }
 // One staged tile: kTileRows / 4 k-steps.  Lane (m, kq) holds element [16c + m][4kk + kq] of column block c,
 // which is its share of the block both as the left and as the right operand.
-template <int NB, int WV>
+template <int NB, int WV, typename T>
 __device__ __forceinline__ void gram_tile_products(const float* tile, int m, int kq,
-                                                   f64x4 (&acc)[GramBlocks<NB>::NQ]) {
+                                                   typename GramAcc<T>::type (&acc)[GramBlocks<NB>::NQ]) {
   constexpr int kSteps = NB == 8 ? 8 : 16;      // unrolled k-steps: the widest matrix has no registers for 16 steps' operands
 #pragma unroll kSteps
   for (int kk = 0; kk < kTileRows / 4; ++kk) {
-    double x[NB];
+    T x[NB];
 #pragma unroll
-    for (int c = 0; c < NB; ++c) x[c] = (double)tile[(16 * c + m) * kGramStride + 4 * kk + kq];
-    gram_k_step<NB, WV>(x, acc, std::make_integer_sequence<int, GramBlocks<NB>::NQ>{});
+    for (int c = 0; c < NB; ++c) x[c] = (T)tile[(16 * c + m) * kGramStride + 4 * kk + kq];
+    gram_k_step<NB, WV, T>(x, acc, std::make_integer_sequence<int, GramBlocks<NB>::NQ>{});
   }
 }
-template <int NB, int WV, int Q>
+template <int NB, int WV, int Q, bool F64>
 __device__ __forceinline__ void gram_block_out(const f64x4 (&acc)[GramBlocks<NB>::NQ], double* out, int NP, int lane) {
   using B = GramBlocks<NB>;
   if constexpr (WV + 4 * Q < B::T) {
     constexpr int a = B::row_of(WV + 4 * Q), b = B::col_of(WV + 4 * Q);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) out[(16 * a + mfma_row_f64(lane, r)) * NP + 16 * b + (lane & 15)] = acc[Q][r];
+    for (int r = 0; r < 4; ++r) {
+      const int row = F64 ? mfma_row_f64(lane, r) : mfma_row_f32(lane, r);   // the layout of the instruction used
+      out[(16 * a + row) * NP + 16 * b + (lane & 15)] = acc[Q][r];
+    }
   }
 }
-template <int NB, int WV, int... Q>
+template <int NB, int WV, bool F64, int... Q>
 __device__ __forceinline__ void gram_out(const f64x4 (&acc)[GramBlocks<NB>::NQ], double* out, int NP, int lane,
                                          std::integer_sequence<int, Q...>) {
-  (gram_block_out<NB, WV, Q>(acc, out, NP, lane), ...);
+  (gram_block_out<NB, WV, Q, F64>(acc, out, NP, lane), ...);
 }
 
-template <int NB>
+template <int NB, bool F64>
 __global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ W, int64_t D, int n, int64_t ldw,
                                                    double* __restrict__ partial) {
   using B = GramBlocks<NB>;
+  using T = typename std::conditional<F64, double, float>::type;
   constexpr int NP = 16 * NB;
   __shared__ float tile[NP * kGramStride];
   const int lane = threadIdx.x & (kWave - 1);
@@ -159,21 +174,37 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ 
     store_tile<kGramStride>(NP, pre, tile);
     __syncthreads();
     if (c + 1 < c1) fetch_tile(W, ldw, D, n, NP, (c + 1) * kTileRows, pre);     // in flight during the products
-    switch (wave) {                                                             // uniform per wave
-      case 0: gram_tile_products<NB, 0>(tile, m, kq, acc); break;
-      case 1: gram_tile_products<NB, 1>(tile, m, kq, acc); break;
-      case 2: gram_tile_products<NB, 2>(tile, m, kq, acc); break;
-      default: gram_tile_products<NB, 3>(tile, m, kq, acc); break;
+    if constexpr (F64) {
+      switch (wave) {                                                           // uniform per wave
+        case 0: gram_tile_products<NB, 0, double>(tile, m, kq, acc); break;
+        case 1: gram_tile_products<NB, 1, double>(tile, m, kq, acc); break;
+        case 2: gram_tile_products<NB, 2, double>(tile, m, kq, acc); break;
+        default: gram_tile_products<NB, 3, double>(tile, m, kq, acc); break;
+      }
+    } else {
+      f32x4 part[B::NQ];                                                        // this tile's sums
+#pragma unroll
+      for (int q = 0; q < B::NQ; ++q) part[q] = {0.f, 0.f, 0.f, 0.f};
+      switch (wave) {
+        case 0: gram_tile_products<NB, 0, float>(tile, m, kq, part); break;
+        case 1: gram_tile_products<NB, 1, float>(tile, m, kq, part); break;
+        case 2: gram_tile_products<NB, 2, float>(tile, m, kq, part); break;
+        default: gram_tile_products<NB, 3, float>(tile, m, kq, part); break;
+      }
+#pragma unroll
+      for (int q = 0; q < B::NQ; ++q)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[q][r] += (double)part[q][r];
     }
     __syncthreads();
   }
   double* out = partial + (int64_t)blockIdx.x * NP * NP;
   constexpr auto slots = std::make_integer_sequence<int, B::NQ>{};
   switch (wave) {
-    case 0: gram_out<NB, 0>(acc, out, NP, lane, slots); break;
-    case 1: gram_out<NB, 1>(acc, out, NP, lane, slots); break;
-    case 2: gram_out<NB, 2>(acc, out, NP, lane, slots); break;
-    default: gram_out<NB, 3>(acc, out, NP, lane, slots); break;
+    case 0: gram_out<NB, 0, F64>(acc, out, NP, lane, slots); break;
+    case 1: gram_out<NB, 1, F64>(acc, out, NP, lane, slots); break;
+    case 2: gram_out<NB, 2, F64>(acc, out, NP, lane, slots); break;
+    default: gram_out<NB, 3, F64>(acc, out, NP, lane, slots); break;
   }
 }
 
@@ -317,11 +348,18 @@ __global__ __launch_bounds__(256) void zero_padding_kernel(float* __restrict__ Q
   for (int64_t i = D + threadIdx.x; i < ld; i += blockDim.x) Q[(int64_t)j * ld + i] = 0.0f;
 }
 
+// `orthonormal_input`: W is orthonormal already to ~1e-4 (the second pass of CholeskyQR2): fp32 matrix instructions.
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram,
-                bool accumulate, hipStream_t st) {
+                bool accumulate, bool orthonormal_input, hipStream_t st) {
   const int NP = (n + 15) / 16 * 16;
   switch (NP / 16) {
-#define TWA_GRAM(NB_) case NB_: hipLaunchKernelGGL(gram_kernel<NB_>, dim3(grid), dim3(256), 0, st, W, D, n, ldw, partial); break
+#define TWA_GRAM(NB_)                                                                                          \
+  case NB_:                                                                                                    \
+    if (orthonormal_input)                                                                                     \
+      hipLaunchKernelGGL((gram_kernel<NB_, false>), dim3(grid), dim3(256), 0, st, W, D, n, ldw, partial);      \
+    else                                                                                                       \
+      hipLaunchKernelGGL((gram_kernel<NB_, true>), dim3(grid), dim3(256), 0, st, W, D, n, ldw, partial);       \
+    break
     TWA_GRAM(1); TWA_GRAM(2); TWA_GRAM(3); TWA_GRAM(4); TWA_GRAM(5); TWA_GRAM(6); TWA_GRAM(7); TWA_GRAM(8);
 #undef TWA_GRAM
     default: return TWA_ERR_SHAPE;

@@ -55,7 +55,7 @@ int launch_beta_optim(int kind, float* beta, const float* s, float* m, float* v,
 int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pmat& out, hipStream_t st);
 int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st);
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram,
-                bool accumulate, hipStream_t st);
+                bool accumulate, bool orthonormal_input, hipStream_t st);
 int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
                       int grid, bool zero_padding, hipStream_t st);
 
