@@ -161,7 +161,7 @@ int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P,
  * kept elsewhere piece by piece: the benchmark's largest configuration streams 16 M-row panels).  A panel
  * is rows [r0, r0 + rows) of all n vectors: pointer W + r0 with the matrix' stride.  One pass of
  * CholeskyQR is
- *     for every panel:  twa_gram_accumulate   G += W_panel^T W_panel   (fp64; accumulate = 0 on the first)
+ *     for every panel:  twa_gram_accumulate   G += W_panel^T W_panel   (fp64; `accumulate` bit 0 clear on the first)
  *     once:             twa_gram_factor       G = R^T R on the host, R^-1 to the device (synchronises)
  *     for every panel:  twa_apply_rinv        P_panel = W_panel R^-1   (may overwrite W_panel)
  * and twa_build_basis is two such passes (the second over P) with R = R_2 R_1 -- `compose` = 1 in the
@@ -170,8 +170,14 @@ int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P,
  *   W, P            fp32, 16-byte aligned, strides multiples of 4 elements and >= rows.  Elements outside
  *                   the panel are neither read nor written (padding of P is the caller's to zero).
  *   R_host          n*n doubles, row major, upper triangular; optional unless compose = 1.
+ *   accumulate      flags: TWA_GRAM_ADD (1) adds to what `gram` holds, else it is overwritten;
+ *                   TWA_GRAM_ORTHONORMAL_INPUT (2) says that the panel belongs to a matrix that is orthonormal
+ *                   to ~1e-4 already (the second pass): its products are then formed by fp32 matrix
+ *                   instructions per 64-row tile and the tiles summed in fp64, at twice the rate.
  * Errors as for twa_build_basis; on TWA_ERR_RANK R_host[0] holds the index of the dependent checkpoint.
  */
+#define TWA_GRAM_ADD 1
+#define TWA_GRAM_ORTHONORMAL_INPUT 2
 int twa_basis_state_bytes(int32_t n, size_t* gram_bytes, size_t* rinv_bytes, size_t* ws_bytes);
 int twa_gram_accumulate(const float* W, int64_t rows, int32_t n, int64_t ldw, double* gram, int32_t accumulate,
                         void* ws, size_t ws_bytes, void* stream);

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtwa.so")
 
 F32, BF16, I8, I4, U8MM, U4MM, U16MM, U2MM, U1MM, U3MM = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
+GRAM_ADD, GRAM_ORTHONORMAL_INPUT = 1, 2         # flags of twa_gram_accumulate
 MINMAX_TYPES = (U8MM, U4MM, U16MM, U2MM, U1MM, U3MM)
 BITS_OF = {F32: 32, BF16: 16, I8: 8, I4: 4, U8MM: 8, U4MM: 4, U16MM: 16, U2MM: 2, U1MM: 1, U3MM: 3}
 MAX_N, MAX_K, LD_MULTIPLE, SCALE_SPAN, MAX_LAYERS = 128, 8, 128, 2048, 65536
@@ -435,7 +436,8 @@ def build_basis_panels(W: torch.Tensor, D: int, panel_rows: int, out: Optional[t
     for p in range(2):
         for k, r0 in enumerate(range(0, D, panel_rows)):
             rows = min(panel_rows, D - r0)
-            _check(lib().twa_gram_accumulate(src.data_ptr() + 4 * r0, rows, n, lds, gram.ptr, 1 if k else 0, ws.ptr,
+            flags = (GRAM_ADD if k else 0) | (GRAM_ORTHONORMAL_INPUT if p else 0)     # second pass: fp32 products
+            _check(lib().twa_gram_accumulate(src.data_ptr() + 4 * r0, rows, n, lds, gram.ptr, flags, ws.ptr,
                                              ws.nbytes, _stream()), "twa_gram_accumulate")
         rc = lib().twa_gram_factor(gram.ptr, n, rinv.ptr, _ptr(R), p, _stream())
         if rc == ERR_RANK:

@@ -620,14 +620,15 @@ int twa_gram_accumulate(const float* W, int64_t rows, int32_t n, int64_t ldw, do
   int rc = check_panel(W, rows, n, ldw);
   if (rc != TWA_OK) return rc;
   if (!gram) return TWA_ERR_NULL;
+  if (accumulate & ~(TWA_GRAM_ADD | TWA_GRAM_ORTHONORMAL_INPUT)) return TWA_ERR_SHAPE;
   size_t gb = 0, rb = 0, wb = 0;
   twa_basis_state_bytes(n, &gb, &rb, &wb);
   if (!ws || ws_bytes < wb) return TWA_ERR_WORKSPACE;
   if (!aligned16(ws) || !aligned16(gram)) return TWA_ERR_ALIGN;
   const int grid = basis_grid(rows);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
-  return launch_gram(W, rows, n, ldw, static_cast<double*>(ws), grid, gram, accumulate != 0,
-                     /*orthonormal_input=*/false, static_cast<hipStream_t>(stream));
+  return launch_gram(W, rows, n, ldw, static_cast<double*>(ws), grid, gram, (accumulate & TWA_GRAM_ADD) != 0,
+                     (accumulate & TWA_GRAM_ORTHONORMAL_INPUT) != 0, static_cast<hipStream_t>(stream));
 }
 
 int twa_gram_factor(const double* gram, int32_t n, float* rinv, double* R_host, int32_t compose, void* stream) {

@@ -191,6 +191,7 @@ def test_panel_calls_argument_errors():
     assert L.twa_gram_accumulate(0x1000, 1000, 4, 1002, 0x2000, 0, 0x4000, big, None) == twa.ERR_ALIGN     # stride % 4
     assert L.twa_gram_accumulate(0x1004, 1000, 4, 1024, 0x2000, 0, 0x4000, big, None) == twa.ERR_ALIGN
     assert L.twa_gram_accumulate(0x1000, 1000, 4, 1024, 0x2000, 0, 0x4000, 64, None) == twa.ERR_WORKSPACE
+    assert L.twa_gram_accumulate(0x1000, 1000, 4, 1024, 0x2000, 4, 0x4000, big, None) == twa.ERR_SHAPE     # unknown flag
     assert L.twa_gram_factor(None, 4, 0x3000, None, 0, None) == twa.ERR_NULL
     assert L.twa_gram_factor(0x2000, 4, 0x3000, None, 1, None) == twa.ERR_NULL                            # compose needs R
     assert L.twa_gram_factor(0x2000, 0, 0x3000, None, 0, None) == twa.ERR_SHAPE
