@@ -307,6 +307,43 @@ def test_build_basis_from_panels_of_rows(name, D, n, panel):
         assert ei.value.code == twa.ERR_RANK and "checkpoint 4" in str(ei.value)
 
 
+@pytest.mark.parametrize("n", [10, 100, 128])
+def test_gram_of_an_orthonormal_matrix_in_fp32_products(n):
+    """The second pass's Gram matrix (TWA_GRAM_ORTHONORMAL_INPUT: fp32 products per 64-row tile, tiles summed in
+    fp64) against the fp64 one and against numpy, on a basis the library has just built; and the flag word is
+    checked."""
+    import ctypes as C
+    D = 300_011
+    W = synth.checkpoints(synth.WORKLOADS["cifar_resnet18"], seed=5, device="cuda", D=D, n=n)
+    P, _ = twa.build_basis(W, D)
+    L = twa.lib()
+    gb, rb, wb = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    assert L.twa_basis_state_bytes(n, C.byref(gb), C.byref(rb), C.byref(wb)) == twa.OK
+    NP = (n + 15) // 16 * 16
+    assert gb.value == NP * NP * 8
+    ws = twa.Workspace(wb.value)
+    grams = []
+    for flags in (0, twa.GRAM_ORTHONORMAL_INPUT):
+        g = torch.full((NP, NP), float("nan"), dtype=torch.float64, device="cuda")
+        st = torch.cuda.current_stream().cuda_stream
+        assert L.twa_gram_accumulate(P.data_ptr(), D, n, P.shape[1], g.data_ptr(), flags, ws.ptr, ws.nbytes, st) == twa.OK
+        torch.cuda.synchronize()
+        grams.append(np.triu(g.cpu().numpy()[:n, :n]))
+    Ph = P[:, :D].cpu().numpy().astype(np.float64)
+    ref = np.triu(Ph @ Ph.T)
+    say("gram fp64 vs numpy", np.max(np.abs(grams[0] - ref)), " fp32 products vs numpy", np.max(np.abs(grams[1] - ref)))
+    assert np.max(np.abs(grams[0] - ref)) <= 1e-12
+    assert np.max(np.abs(grams[1] - ref)) <= 2e-8           # fp32 products of numbers ~ D^-1/2, summed in fp64
+    # adding: twice the matrix
+    g2 = torch.from_numpy(np.zeros((NP, NP))).cuda()
+    for k in range(2):
+        flags = twa.GRAM_ORTHONORMAL_INPUT | (twa.GRAM_ADD if k else 0)
+        assert L.twa_gram_accumulate(P.data_ptr(), D, n, P.shape[1], g2.data_ptr(), flags, ws.ptr, ws.nbytes,
+                                     torch.cuda.current_stream().cuda_stream) == twa.OK
+    torch.cuda.synchronize()
+    assert np.max(np.abs(np.triu(g2.cpu().numpy()[:n, :n]) - 2.0 * grams[1])) <= 1e-15
+
+
 def test_build_basis_rank_deficient():
     D, n = 5000, 6
     W = random_basis_like(D, n, seed=8)
