@@ -271,8 +271,26 @@ def test_large_int4_int8_full_size():
         torch.cuda.empty_cache()
 
 
-def test_imagenet_resnet50_algorithm_1_minmax4_full_size():
-    """The paper's default configuration at the benchmark shape, as bench.py --mode layerwise --storage mm4 runs it:
+def _minmax_codes_at(pm, idx):
+    """Codes of all vectors at the elements `idx` (a device tensor of indices), read from the packed storage."""
+    if pm.dtype == twa.U4MM:
+        by = pm.data[:, idx // 2]
+        return ((by >> (4 * (idx & 1)).to(torch.uint8)) & 0xF).cpu().numpy().astype(np.uint16)
+    assert pm.dtype == twa.U3MM
+    # groups of 32 elements in three 32-bit words: element e = 16h + 4k + m has its low two bits in word h at
+    # bit 2(4k + m), its high bit in word 2 at bit 8k + m + 4h
+    words = pm.data.view(torch.int32)
+    g, e = idx // 32, idx % 32
+    h, f = e // 16, e % 16
+    low = (words[:, 3 * g + h] >> (2 * f).to(torch.int32)) & 3
+    high = (words[:, 3 * g + 2] >> (8 * (f // 4) + f % 4 + 4 * h).to(torch.int32)) & 1
+    return (low | (high << 2)).cpu().numpy().astype(np.uint16)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_imagenet_resnet50_algorithm_1_minmax_full_size(bits):
+    """The paper's default configuration at the benchmark shape, as bench.py --mode layerwise --storage mm4 runs it
+    (and the same with 3-bit codes, --storage mm3):
     layer-wise centre+normalise basis (Sec. 4.1, 4.5), 4-bit per-layer min-max codes (Sec. 4.6), coefficient step
     with weight decay and w = wbar + P beta (Alg. 1).  Sampled: wbar and E on blocks, codes and factors of whole
     layers through the oracle's quantiser, coefficient columns over all of D, w on blocks next to layer boundaries."""
@@ -281,7 +299,7 @@ def test_imagenet_resnet50_algorithm_1_minmax4_full_size():
     off_cpu = synth.workload_layers(wl.name)
     offs = off_cpu.numpy()
     L = len(offs) - 1
-    say("full size, Alg. 1, 4-bit min-max", wl.name, D, n, "L", L)
+    say("full size, Alg. 1, min-max codes of", bits, "bits", wl.name, D, n, "L", L)
     W = synth.checkpoints(wl, seed=0, device="cuda")
     plan = twa.LayerPlan(off_cpu, D)
     # ---- basis: mean bit-exact and centred/normalised vectors within the bar, on sampled layers (whole layers)
@@ -297,17 +315,15 @@ def test_imagenet_resnet50_algorithm_1_minmax4_full_size():
         Eo, wbo, _ = orc.centre_normalise_layers(W_host[l], np.array([0, b - a], dtype=np.int64))
         assert np.array_equal(wbar[a:b].cpu().numpy(), wbo.astype(np.float32)), l
         assert rel_l2(E[:, a:b].cpu().numpy(), Eo) <= REL_L2_TOL, l
-    # ---- 4-bit codes and factors of those layers, bit-exact
+    # ---- codes and factors of those layers, bit-exact
     E_host = {l: E[:, offs[l]:offs[l + 1]].cpu().numpy().astype(np.float64) for l in layers}
-    pm = twa.quantize_minmax(E, D, plan, bits=4)
+    pm = twa.quantize_minmax(E, D, plan, bits=bits)
     torch.cuda.synchronize()
     ab = pm.scales.cpu().numpy()
     for l in layers:
         a, b = int(offs[l]), int(offs[l + 1])
-        co, ao, bo = orc.quantize_minmax(E_host[l], 4, np.array([0, b - a], dtype=np.int64))
-        idx = torch.arange(a, b, device="cuda")
-        by = pm.data[:, idx // 2]
-        codes = ((by >> (4 * (idx & 1)).to(torch.uint8)) & 0xF).cpu().numpy().astype(np.uint16)
+        co, ao, bo = orc.quantize_minmax(E_host[l], bits, np.array([0, b - a], dtype=np.int64))
+        codes = _minmax_codes_at(pm, torch.arange(a, b, device="cuda"))
         assert np.array_equal(codes, co), l
         assert ab[l, 0] == np.float32(ao[0]) and ab[l, 1] == np.float32(bo[0]), l
     del W, E, W_host, E_host
@@ -335,8 +351,7 @@ def test_imagenet_resnet50_algorithm_1_minmax4_full_size():
     near = [int(o) // block for o in offs[1:-1]] + [max(0, int(o) // block - 1) for o in offs[1:-1]]
     ids = sorted(set([0, nb - 1] + r.integers(0, nb, size=48).tolist() + r.choice(near, size=40).tolist()))
     rows = torch.cat([torch.arange(b * block, (b + 1) * block) for b in ids]).cuda()
-    by = pm.data[:, rows // 2]
-    codes = ((by >> (4 * (rows & 1)).to(torch.uint8)) & 0xF).cpu().numpy().astype(np.uint16)
+    codes = _minmax_codes_at(pm, rows)
     rows_np = rows.cpu().numpy()
     off_sub = np.searchsorted(rows_np, offs, side="left").astype(np.int64)
     po = orc.Pmat(orc.MM, int(rows.numel()), np.ascontiguousarray(codes), np.ascontiguousarray(ab, dtype=np.float32), 0, 1.0,
