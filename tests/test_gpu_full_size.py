@@ -276,6 +276,13 @@ def _minmax_codes_at(pm, idx):
     if pm.dtype == twa.U4MM:
         by = pm.data[:, idx // 2]
         return ((by >> (4 * (idx & 1)).to(torch.uint8)) & 0xF).cpu().numpy().astype(np.uint16)
+    if pm.dtype in (twa.U2MM, twa.U1MM):                   # B-bit fields, low bits first
+        B = 2 if pm.dtype == twa.U2MM else 1
+        per = 8 // B
+        by = pm.data[:, idx // per]
+        return ((by >> (B * (idx % per)).to(torch.uint8)) & ((1 << B) - 1)).cpu().numpy().astype(np.uint16)
+    if pm.dtype in (twa.U8MM, twa.U16MM):                  # the container holds code - 2^(B-1)
+        return (pm.data[:, idx].to(torch.int32) + (1 << (pm.block - 1))).cpu().numpy().astype(np.uint16)
     assert pm.dtype == twa.U3MM
     # groups of 32 elements in three 32-bit words: element e = 16h + 4k + m has its low two bits in word h at
     # bit 2(4k + m), its high bit in word 2 at bit 8k + m + 4h
@@ -287,7 +294,7 @@ def _minmax_codes_at(pm, idx):
     return (low | (high << 2)).cpu().numpy().astype(np.uint16)
 
 
-@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("bits", [4, 3, 2, 1, 8, 16])
 def test_imagenet_resnet50_algorithm_1_minmax_full_size(bits):
     """The paper's default configuration at the benchmark shape, as bench.py --mode layerwise --storage mm4 runs it
     (and the same with 3-bit codes, --storage mm3):
