@@ -555,3 +555,133 @@ def test_quantize_rounds_the_product_to_binary32_before_the_integer_rounding():
     q = orc.quantize_i8(vec)
     assert q.scales[0, 0] == scale
     assert q.data[0, 1:1 + min(len(found), 100)].tolist() == [e for _, e in found[:100]]
+
+
+# --------------------------------------------------------------------------- int4: codes against the EFFECTIVE scale
+def _numpy_recipe_i4(p, gscale, block=64):
+    """The 4-bit recipe in numpy float32 / float16 operations, an independent evaluation of every step:
+    amax / 7 -> / gscale -> binary16 (nearest even) -> * gscale -> 1 / e -> rint(p * inv)."""
+    n, D = p.shape
+    nblk = (D + block - 1) // block
+    pp = np.zeros((n, nblk * block), dtype=np.float32)
+    pp[:, :D] = p
+    b3 = pp.reshape(n, nblk, block)
+    amax = np.abs(b3).max(axis=2)
+    scale = (amax / np.float32(7.0)).astype(np.float32)
+    h = (scale / np.float32(gscale)).astype(np.float32).astype(np.float16)
+    eff = (h.astype(np.float32) * np.float32(gscale)).astype(np.float32)
+    with np.errstate(divide="ignore"):
+        inv = np.where(eff != 0, np.float32(1.0) / eff, np.float32(0)).astype(np.float32)
+    t = (b3 * inv[:, :, None]).astype(np.float32)
+    q = np.clip(np.rint(t), -7, 7).astype(np.int64).reshape(n, -1)
+    packed = ((q[:, 0::2] + 8) | ((q[:, 1::2] + 8) << 4)).astype(np.uint8)
+    return packed, h.view(np.uint16), scale, eff
+
+
+@pytest.mark.parametrize("scale_mag", [1.0, 5.3e-5, 2.0e-4, 37.0, 3.1e-9])
+def test_quantize_i4_equals_float32_float16_evaluation(scale_mag):
+    r = rng(31)
+    p = (r.normal(size=(4, 64 * 41 + 9)) * scale_mag).astype(np.float32)
+    q = orc.quantize_i4(p)                                   # gscale chosen by the library's rule
+    assert q.gscale != 1.0
+    packed, hbits, scale, eff = _numpy_recipe_i4(p, q.gscale)
+    assert np.array_equal(q.scales, hbits)
+    assert np.array_equal(q.data, packed)
+    # the pin bites only if rounding the scale to binary16 matters: most blocks' effective scale differs
+    # from the binary32 scale, and forming the codes against the unrounded one changes some of them
+    assert np.mean(eff != scale) > 0.9
+    with np.errstate(divide="ignore"):
+        inv_unrounded = np.where(scale != 0, np.float32(1.0) / scale, np.float32(0)).astype(np.float32)
+    pp = np.zeros((4, eff.shape[1] * 64), dtype=np.float32)
+    pp[:, :p.shape[1]] = p
+    other = np.clip(np.rint((pp.reshape(4, -1, 64) * inv_unrounded[:, :, None]).astype(np.float32)), -7, 7)
+    mine = np.stack([(q.data & 0xF).astype(np.int64) - 8, (q.data >> 4).astype(np.int64) - 8], axis=2).reshape(4, -1)
+    assert np.count_nonzero(other.reshape(4, -1) != mine) > 0
+
+
+def test_quantize_i4_codes_are_formed_against_the_binary16_rounded_scale():
+    # One block by hand.  amax = 7.005: scale = 1.000714.., which binary16 (quantum 2^-10 above 1) rounds UP to
+    # e = 1 + 2^-10 = 1.0009765625.  Elements strictly between 2.5*scale and 2.5*e (4.5*scale and 4.5*e, ...)
+    # lie below the tie of the effective scale and above the tie of the unrounded one.
+    from fractions import Fraction
+    amax = np.float32(7.005)
+    scale = Fraction(float(amax)) / 7
+    eff = Fraction(1) + Fraction(1, 1024)
+    assert scale > 1 + Fraction(1, 2048)                     # above the binary16 tie: rounds up to 1 + 2^-10
+    vals = [2.5021, 4.5038, -2.5021, 6.5052, 0.5004, 1.5011]
+    want = []
+    for v in vals:
+        x = Fraction(float(np.float32(v))) / eff             # the quotient against the effective scale, exactly
+        y = Fraction(float(np.float32(v))) / scale           # ... against the unrounded scale
+        k = math.floor(abs(x))
+        assert abs(abs(x) - (k + Fraction(1, 2))) > Fraction(1, 100000)   # 20x the binary32 rounding of p*inv away from a tie
+        assert abs(x) < k + Fraction(1, 2) < abs(y)          # the two scales disagree about this element
+        want.append(int(math.copysign(k, v)))
+    p = np.zeros((1, 64), dtype=np.float32)
+    p[0, 0] = amax
+    p[0, 1:1 + len(vals)] = vals
+    q = orc.quantize_i4(p, gscale=1.0)
+    assert orc.f16_bits_to_f32(int(q.scales[0, 0])) == float(eff)
+    codes = np.stack([(q.data[0] & 0xF).astype(int) - 8, (q.data[0] >> 4).astype(int) - 8], axis=1).reshape(-1)
+    assert codes[0] == 7
+    assert codes[1:1 + len(vals)].tolist() == want           # [2, 4, -2, 6, 0, 1]: one less than against `scale`
+    assert q.dense()[0, 1] == 2 * float(eff)                 # and the stored value uses the effective scale too
+
+
+def test_quantize_i4_is_a_fixed_point_on_its_own_output():
+    r = rng(32)
+    D = 64 * 20 + 17
+    p = (r.normal(size=(5, D)) / math.sqrt(D)).astype(np.float32)
+    q = orc.quantize_i4(p)
+    dq = q.dense()
+    assert np.array_equal(dq.astype(np.float32).astype(np.float64), dq)       # e*q is a binary32 number
+    q2 = orc.quantize_i4(dq.astype(np.float32), gscale=q.gscale)
+    assert np.array_equal(q2.data, q.data) and np.array_equal(q2.scales, q.scales)
+
+
+# --------------------------------------------------------------------------- min-max quantiser: tie rule, a = 0, end points
+@pytest.mark.parametrize("B,top", [(1, 1.0), (2, 3.0), (3, 7.0), (4, 15.0), (4, 45.0), (8, 255.0), (8, 765.0),
+                                   (16, 65535.0)])
+def test_minmax_ties_go_to_the_even_code(B, top):
+    # min = 0 and max = top make the step a = top / (2^B - 1) exactly 1 or 3; (k + 1/2) * a is then exactly
+    # half way between the codes k and k + 1: the paper names no tie rule, the reading here is ties to even.
+    levels = (1 << B) - 1
+    a = top / levels
+    m = min(levels, 3000)
+    k = np.arange(m) if levels <= 3000 else np.concatenate([np.arange(1500), np.arange(levels - 1500, levels)])
+    P = np.zeros((3, k.size + 2))
+    P[0, 0], P[0, 1] = 0.0, top
+    P[0, 2:] = (k + 0.5) * a
+    P[1, 2:] = k * a
+    P[2, 2:] = (k + 0.25) * a
+    codes, ao, bo = orc.quantize_minmax(P, B, [0, P.shape[1]])
+    assert ao[0] == a and bo[0] == 0.0
+    assert codes[0, 0] == 0 and codes[0, 1] == levels        # the end points take the first and the last code
+    assert np.array_equal(codes[0, 2:].astype(np.int64), np.where(k % 2 == 0, k, k + 1))
+    assert np.array_equal(codes[1, 2:].astype(np.int64), k)
+    assert np.array_equal(codes[2, 2:].astype(np.int64), k)
+
+
+def test_minmax_constant_layer_and_sixteen_bit_end_points():
+    r = rng(33)
+    P = r.normal(size=(4, 900))
+    P[:, 300:500] = -0.375                                    # a constant layer: a = 0
+    off = [0, 300, 500, 900]
+    codes, a, b = orc.quantize_minmax(P, 16, off)
+    assert a[1] == 0.0 and b[1] == -0.375 and not codes[:, 300:500].any()
+    dense = orc.pmat_minmax(codes, a, b, off).dense()
+    assert np.all(dense[:, 300:500] == -0.375)
+    for l in (0, 2):
+        seg = P[:, off[l]:off[l + 1]]
+        c = codes[:, off[l]:off[l + 1]]
+        assert c[np.unravel_index(np.argmin(seg), seg.shape)] == 0
+        assert c[np.unravel_index(np.argmax(seg), seg.shape)] == 65535
+        assert a[l] == (seg.max() - seg.min()) / 65535.0 and b[l] == seg.min()
+        # every code is the nearest level, computed independently in exact rational arithmetic on a sample
+        from fractions import Fraction
+        fa, fb = Fraction(float(a[l])), Fraction(float(b[l]))
+        for (j, i) in [(0, 0), (1, 17), (3, seg.shape[1] - 1), (2, 123)]:
+            x = (Fraction(float(seg[j, i])) - fb) / fa
+            lo = math.floor(x)
+            near = lo if x - lo < Fraction(1, 2) else lo + 1
+            assert abs(int(c[j, i]) - near) <= (1 if abs((x - lo) - Fraction(1, 2)) < Fraction(1, 10 ** 9) else 0)
