@@ -50,7 +50,8 @@ typedef enum twa_status {
   TWA_ERR_WORKSPACE = -5, /* workspace missing or smaller than the query reports               */
   TWA_ERR_RANK = -6,      /* checkpoints numerically linearly dependent (build_basis)          */
   TWA_ERR_HIP = -7,       /* a HIP runtime call failed; see twa_last_hip_error()               */
-  TWA_ERR_NO_DEVICE = -8  /* no usable gfx950 device                                           */
+  TWA_ERR_NO_DEVICE = -8, /* no usable gfx950 device                                           */
+  TWA_ERR_LIMIT = -9      /* size beyond the fixed device array of twa_project_noalloc         */
 } twa_status;
 
 /* Storage type of a projection matrix. */
@@ -215,6 +216,23 @@ int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* ou
  */
 int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float* s, void* ws,
                 size_t ws_bytes, void* stream);
+
+/*
+ * twa_project for callers that cannot allocate: code under stream capture into a HIP graph, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, kernels, arithmetic and bits as twa_project, without
+ * the workspace: the per-workgroup partial sums go to a fixed array in device memory that belongs to the
+ * library (TWA_NOALLOC_SCRATCH_BYTES per GPU the entry point is used on, held until the process ends).  The
+ * call allocates and frees nothing (no hipMalloc, no hipFree, no allocating library routine).
+ *   Limit: n * k <= TWA_NOALLOC_MAX_NK, else TWA_ERR_LIMIT (checked on the host before anything is enqueued).
+ *   The array keeps the previous call's contents; nothing in it has to start at zero, because every slot the
+ *   final reduction reads is written by the same call first.
+ *   Every call on one GPU uses that GPU's one array: calls that overlap on a GPU (two streams, two threads)
+ *   race and give wrong sums; calls on one stream are ordered and safe.  The first call on a device looks the
+ *   array's address up (no allocation, but a runtime query: make it outside stream capture).
+ */
+#define TWA_NOALLOC_MAX_NK 512
+#define TWA_NOALLOC_SCRATCH_BYTES (2048u * TWA_NOALLOC_MAX_NK * 4u)   /* 4 MiB */
+int twa_project_noalloc(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float* s, void* stream);
 
 /*
  * g~ = P s ; w <- w - lr * g~   (Sec. 4.2, weight-space form of the update rule, lambda = 0;

@@ -24,7 +24,8 @@ MAX_N, MAX_K, LD_MULTIPLE, SCALE_SPAN, MAX_LAYERS = 128, 8, 128, 2048, 65536
 DEFAULT_BLOCK = {I8: 128, I4: 64}
 
 OK = 0
-ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_WORKSPACE, ERR_RANK, ERR_HIP, ERR_NO_DEVICE = range(-1, -9, -1)
+ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_WORKSPACE, ERR_RANK, ERR_HIP, ERR_NO_DEVICE, ERR_LIMIT = range(-1, -10, -1)
+NOALLOC_MAX_NK = 512
 
 
 class TwaError(RuntimeError):
@@ -78,6 +79,8 @@ def lib():
         L.twa_quantize.argtypes = [vp, i64, i32, i64, C.POINTER(_Pmat), vp]
         L.twa_project.argtypes = [C.POINTER(_Pmat), vp, i32, i64, vp, vp, C.c_size_t, vp]
         L.twa_expand_update.argtypes = [C.POINTER(_Pmat), vp, vp, f32, vp, vp]
+        L.twa_project_noalloc.argtypes = [C.POINTER(_Pmat), vp, i32, i64, vp, vp]
+        L.twa_project_noalloc.restype = C.c_int
         L.twa_project_layers_workspace_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
         L.twa_project_layers.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, vp, C.c_size_t, vp]
         L.twa_expand_update_layers.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, f32, vp, vp]
@@ -241,6 +244,17 @@ def project(P: Pmat, g: torch.Tensor, s: Optional[torch.Tensor] = None, ws: Opti
         ws = Workspace(project_workspace_bytes(P.n, k), device=g.device)
     st = P.c_struct()
     _check(lib().twa_project(C.byref(st), _ptr(g), k, ldg, _ptr(s), ws.ptr, ws.nbytes, _stream()), "twa_project")
+    return s
+
+
+def project_noalloc(P: Pmat, g: torch.Tensor, s: torch.Tensor) -> torch.Tensor:
+    """twa_project_noalloc: s = P^T g into the caller's `s`, partial sums in the library's fixed device array
+    (n * k <= NOALLOC_MAX_NK); neither this wrapper nor the call allocates."""
+    assert g.dtype == torch.float32 and g.is_contiguous() and s.dtype == torch.float32 and s.is_contiguous()
+    k, ldg = (1, 0) if g.dim() == 1 else (int(g.shape[0]), int(g.shape[1]))
+    assert s.numel() == k * P.n
+    st = P.c_struct()
+    _check(lib().twa_project_noalloc(C.byref(st), _ptr(g), k, ldg, _ptr(s), _stream()), "twa_project_noalloc")
     return s
 
 

@@ -191,6 +191,7 @@ const char* twa_strerror(int status) {
     case TWA_ERR_RANK: return "checkpoints are numerically linearly dependent";
     case TWA_ERR_HIP: return "a HIP runtime call failed";
     case TWA_ERR_NO_DEVICE: return "no usable GPU device";
+    case TWA_ERR_LIMIT: return "size beyond the fixed device array of an entry point that allocates nothing";
     default: return "unknown status";
   }
 }
@@ -249,6 +250,27 @@ int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float
   const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   float* partial = static_cast<float*>(ws);
+  if (k == 1) return launch_project(v, P->dtype, g, s, partial, grid, st);
+  return launch_project_batched(v, P->dtype, g, ldg, k, s, partial, grid, st);
+}
+
+int twa_project_noalloc(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float* s, void* stream) {
+  PView v;
+  int rc = view_of(P, &v);
+  if (rc != TWA_OK) return rc;
+  if (!g || !s) return TWA_ERR_NULL;
+  if (k <= 0 || k > TWA_MAX_K) return TWA_ERR_SHAPE;
+  if ((int64_t)v.n * k > TWA_NOALLOC_MAX_NK) return TWA_ERR_LIMIT;      // beyond the fixed array: said on the host
+  if (k > 1 && (ldg < v.D || (ldg & 3) != 0)) return TWA_ERR_SHAPE;
+  if (!aligned16(g) || (reinterpret_cast<uintptr_t>(s) & 3u)) return TWA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  float* partial = nullptr;
+  size_t floats = 0;
+  rc = noalloc_partials(&partial, &floats);
+  if (rc != TWA_OK) return rc;
+  if ((size_t)grid * (size_t)v.n * (size_t)k > floats) return TWA_ERR_LIMIT;
   if (k == 1) return launch_project(v, P->dtype, g, s, partial, grid, st);
   return launch_project_batched(v, P->dtype, g, ldg, k, s, partial, grid, st);
 }

@@ -30,6 +30,8 @@ int launch_project_batched(const PView& P, int dtype, const float* g, int64_t ld
                            int max_grid, hipStream_t st);
 int launch_expand_update(const PView& P, int dtype, const float* s, float* w, float lr, float* g_tilde, int max_grid,
                          hipStream_t st);
+// Device address and size of the library's own array of partial sums on the current device (no allocation).
+int noalloc_partials(float** out, size_t* floats);
 // Layer-wise step: the device plan (see twa_layers.hip) and the kernels that use it.
 struct LayerPlan;
 size_t layer_plan_bytes(int L);

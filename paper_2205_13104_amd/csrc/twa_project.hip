@@ -14,6 +14,8 @@
 //     read zeros without memory traffic and without branches in the steady state;
 //   * one cross-lane reduction per wave at the very end, per-workgroup partial sums in the
 //     workspace, and a second tiny kernel adds them in a fixed order (fp64) -> deterministic.
+#include <mutex>
+
 #include "twa_device.h"
 #include "twa_host.h"
 
@@ -687,6 +689,35 @@ static int launch_project_batched_dt(const PView& P, const float* g, int64_t ldg
     int rc = launch_project(P, DT, g + (int64_t)c * ldg, s + (int64_t)c * P.n, partial, max_grid, st);
     if (rc != TWA_OK) return rc;
   }
+  return TWA_OK;
+}
+
+// ---- partial sums for callers that cannot allocate ------------------------------------------------
+// The per-workgroup partial sums of a projection normally live in the caller's workspace.  For callers that
+// cannot allocate one (code under stream capture, serving loops, harnesses that forbid it) the library
+// keeps a fixed array in device memory: kNoAllocFloats floats per GPU, held until the process ends.  In host
+// code the array's name is only a handle; its device address is asked for once per device (with that device
+// current) and kept, and only that address is ever handed to a kernel.
+constexpr size_t kNoAllocFloats = (size_t)kMaxGrid * TWA_NOALLOC_MAX_NK;         // 4 MiB
+static __device__ __align__(256) float scratch[kNoAllocFloats];
+
+int noalloc_partials(float** out, size_t* floats) {
+  static std::mutex mu;
+  static float* ptr[64] = {nullptr};
+  int dev = 0;
+  int rc = hip_check(hipGetDevice(&dev));
+  if (rc != TWA_OK) return rc;
+  if (dev < 0 || dev >= 64) return TWA_ERR_NO_DEVICE;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    rc = hip_check(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (rc != TWA_OK) return rc;
+    if (!p) return TWA_ERR_HIP;
+    ptr[dev] = static_cast<float*>(p);
+  }
+  *out = ptr[dev];
+  *floats = kNoAllocFloats;
   return TWA_OK;
 }
 

@@ -206,3 +206,22 @@ def test_read_probe_argument_errors():
     assert L.twa_probe_read(0x1000, 1 << 20, None, None) == twa.ERR_NULL
     assert L.twa_probe_read(0x1000, 8, 0x2000, None) == twa.ERR_SHAPE
     assert L.twa_probe_read(0x1008, 1 << 20, 0x2000, None) == twa.ERR_ALIGN
+
+
+def test_project_noalloc_argument_errors():
+    """The entry point that allocates nothing: its size limit and the usual argument errors, all on the host."""
+    L = twa.lib()
+
+    def call(pm, g=0x2000, k=1, ldg=0, s=0x3000):
+        return L.twa_project_noalloc(C.byref(pm), g, k, ldg, s, None)
+
+    assert L.twa_project_noalloc(None, 0x2000, 1, 0, 0x3000, None) == twa.ERR_NULL
+    assert call(_pm(), g=0) == twa.ERR_NULL and call(_pm(), s=0) == twa.ERR_NULL
+    assert call(_pm(dtype=99)) == twa.ERR_DTYPE
+    assert call(_pm(), k=9) == twa.ERR_SHAPE
+    assert call(_pm(), g=0x2004) == twa.ERR_ALIGN
+    assert call(_pm(n=100), k=8, ldg=1024) == twa.ERR_LIMIT          # n * k = 800 > 512
+    assert call(_pm(n=128), k=5, ldg=1024) == twa.ERR_LIMIT
+    assert call(_pm(n=64), k=8, ldg=1024) in (twa.ERR_NO_DEVICE, twa.ERR_HIP)      # at the limit: goes on to the device
+    assert call(_pm(n=128), k=4, ldg=996) == twa.ERR_SHAPE           # inside the limit; ldg < D
+    assert "fixed device array" in twa.strerror(twa.ERR_LIMIT)
