@@ -685,3 +685,92 @@ def test_minmax_constant_layer_and_sixteen_bit_end_points():
             lo = math.floor(x)
             near = lo if x - lo < Fraction(1, 2) else lo + 1
             assert abs(int(c[j, i]) - near) <= (1 if abs((x - lo) - Fraction(1, 2)) < Fraction(1, 10 ** 9) else 0)
+
+
+# --------------------------------------------------------------------------- pins found by a mutation sweep of the oracle
+def test_stored_values_of_every_vector_are_read_from_its_own_run():
+    # the value of element (i, j) sits at j*ld + i, for every storage type (a column index that collapses
+    # to 0 would go unnoticed by checks that go through the oracle's own dequantiser twice)
+    r = rng(51)
+    n, D, ld = 5, 300, 384
+    a = np.zeros((n, ld), dtype=np.float32)
+    a[:, :D] = r.normal(size=(n, D)).astype(np.float32)
+    assert np.array_equal(orc.Pmat(orc.F32, D, a).dense(), a[:, :D].astype(np.float64))
+    a64 = a.astype(np.float64)
+    assert np.array_equal(orc.Pmat(orc.F64, D, a64).dense(), a64[:, :D])
+    b = orc.to_bf16(a, D=D, ld=ld)
+    want = torch.from_numpy(a[:, :D]).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(b.dense(), want)
+    assert not b.data[:, D:].any()                            # padding of every vector is zeroed
+    g = r.normal(size=D)
+    assert np.allclose(orc.project(orc.Pmat(orc.F32, D, a), g), a64[:, :D] @ g, rtol=1e-13, atol=1e-13)
+    assert np.allclose(orc.project(b, g), want @ g, rtol=1e-13, atol=1e-13)
+    q8 = orc.quantize_i8(a, D=D, ld=ld)
+    want8 = q8.data[:, :D].astype(np.float64) * np.repeat(q8.scales.astype(np.float64), 128, axis=1)[:, :D]
+    assert np.array_equal(q8.dense(), want8)
+    q4 = orc.quantize_i4(a, D=D, ld=ld)
+    c4 = np.stack([(q4.data & 0xF).astype(np.float64) - 8, (q4.data >> 4).astype(np.float64) - 8], axis=2).reshape(n, -1)
+    e4 = q4.scales.view(np.float16).astype(np.float64) * q4.gscale
+    assert np.array_equal(q4.dense(), (c4 * np.repeat(e4, 64, axis=1))[:, :D])
+
+
+def test_bfloat16_keeps_infinity_and_nan_apart():
+    assert orc.f32_to_bf16_bits(float("inf")) == 0x7F80 and orc.f32_to_bf16_bits(float("-inf")) == 0xFF80
+    assert (orc.f32_to_bf16_bits(float("nan")) & 0x7FFF) > 0x7F80
+    assert orc.f32_to_f16_bits(float("inf")) == 0x7C00 and orc.f32_to_f16_bits(1e6) == 0x7C00
+    assert (orc.f32_to_f16_bits(float("nan")) & 0x7FFF) > 0x7C00
+
+
+def test_rank_threshold_is_relative_to_the_largest_checkpoint_norm():
+    # |R_kk| <= rank_tol * max_j ||w_j|| is the error condition (rank_tol = 1e-6 by default)
+    big = np.array([1000.0, 0.0, 0.0, 0.0, 0.0, 0.0])
+    ok = np.array([0.0, 2e-3, 0.0, 0.0, 0.0, 0.0])            # 2e-3 > 1e-6 * 1000
+    P, R = orc.build_basis(np.stack([big, ok]))
+    assert R[1, 1] == pytest.approx(2e-3, rel=1e-12) and np.allclose(P[1], [0, 1, 0, 0, 0, 0], atol=1e-15)
+    small = np.array([0.0, 5e-4, 0.0, 0.0, 0.0, 0.0])         # 5e-4 <= 1e-6 * 1000
+    with pytest.raises(orc.OracleError) as ei:
+        orc.build_basis(np.stack([big, small]))
+    assert ei.value.code == orc.ERR_RANK and ei.value.column == 1
+    # the largest norm counts wherever it stands, also behind the failing column
+    with pytest.raises(orc.OracleError) as ei:
+        orc.build_basis(np.stack([small, big]))
+    assert ei.value.column == 0
+    P, _ = orc.build_basis(np.stack([small, big]), rank_tol=1e-7)
+    # norms below 1: the largest NORM decides (0.6), not a squared norm and not the first one seen
+    e = np.eye(6)
+    with pytest.raises(orc.OracleError) as ei:
+        orc.build_basis(np.stack([0.5 * e[0], 0.6 * e[1], 0.55e-6 * e[2]]))
+    assert ei.value.column == 2
+    orc.build_basis(np.stack([0.5 * e[0], 0.6 * e[1], 0.65e-6 * e[2]]))
+    assert np.allclose(np.abs(P), [[0, 1, 0, 0, 0, 0], [1, 0, 0, 0, 0, 0]], atol=1e-15)
+
+
+def test_a_checkpoint_equal_to_the_mean_gives_a_zero_vector():
+    # Sec. 4.1: e = (w - wbar)/||w - wbar||; a zero centred part has no direction: the vector is zero, not NaN
+    w = rng(52).normal(size=(1, 40))
+    E, wbar = orc.centre_normalise(w)
+    assert np.array_equal(wbar, w[0]) and not E.any()
+    W = np.stack([w[0], w[0] + 1.0, w[0] - 1.0])               # the first equals the mean of the three
+    E, wbar = orc.centre_normalise(W)
+    assert np.allclose(wbar, w[0], atol=1e-15) and np.all(np.isfinite(E))
+    assert np.max(np.abs(E[0])) <= 1e-12 or np.allclose(np.linalg.norm(E[0]), 1.0)   # rounding may leave a direction
+    E2, wb2, nr2 = orc.centre_normalise_layers(np.stack([w[0], w[0]]), [0, 10, 40])
+    assert not E2.any() and not nr2.any()
+
+
+def test_quantize_i4_ignores_what_stands_in_the_padding_of_its_input():
+    # elements [D, ld) are padding: they do not enter a block's absmax and their code is 0 (nibble 8),
+    # whatever the input holds there -- also when D is even and ends inside a byte pair's neighbour
+    r = rng(53)
+    for D in (70, 71):
+        p = np.full((2, 128), 5.0e3, dtype=np.float32)         # poison everywhere ...
+        p[:, :D] = r.normal(size=(2, D)).astype(np.float32)    # ... but in the D real elements
+        q = orc.quantize_i4(p, D=D, ld=128, gscale=2.0 ** -14)
+        codes = np.stack([(q.data & 0xF).astype(int) - 8, (q.data >> 4).astype(int) - 8], axis=2).reshape(2, -1)
+        assert not codes[:, D:].any()
+        clean = np.zeros_like(p)
+        clean[:, :D] = p[:, :D]
+        q0 = orc.quantize_i4(clean, D=D, ld=128, gscale=2.0 ** -14)
+        assert np.array_equal(q.data, q0.data) and np.array_equal(q.scales, q0.scales)
+        q8, q80 = orc.quantize_i8(p, D=D, ld=128), orc.quantize_i8(clean, D=D, ld=128)
+        assert np.array_equal(q8.data, q80.data) and np.array_equal(q8.scales, q80.scales) and not q8.data[:, D:].any()
