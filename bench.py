@@ -3,22 +3,32 @@
 
 One "step" is one pass of the whole hot path over one synthetic gradient:
     s = P^T g   (twa_project)      then      g~ = P s, w -= lr g~   (twa_expand_update)
-enqueued back to back on one stream, s staying on the device.  The workload is the
+enqueued back to back on one stream, s staying on the device.  The default workload is the
 ResNet-50-sized configuration the metric is quoted on: D = 25,557,032, n = 100, P stored as int8
 codes with one fp32 absmax scale per 128 elements.  P is produced by the library itself from a
 synthetic checkpoint trajectory (twa_build_basis, then twa_quantize); all inputs are resident in
 HBM before the timed region starts.
 
+Protocol: W untimed warm-up steps; K steps timed at once (the "cold" figure: what a short run sees
+while the device's clocks still settle); further untimed steps until the device has been under this
+load for --settle-seconds; then --reps repetitions of exactly K timed steps each, bracketed by
+synchronisations.  `ms_per_step` and `value` are the MEDIAN repetition; the line keeps every
+repetition and the cold figure.
+
 Prints ONE JSON line.  `value` = projected steps/s; `p_stream_GBps` = steps/s x 2 x (bytes of P);
 `roofline` = the slower of the two kernels against the 8 TB/s HBM peak, its duration measured here
 with device events on the stream the kernels run on; `cpu_baseline` = the fp64 oracle timed on the
-host cores on a bounded sample of the same stored P.
+host cores (all of them, and one) on a bounded sample of the same stored P.
+
+Other legs: --mode layerwise (Alg. 1 as written), --mode batched (s = P^T G for k gradients per call,
+the fine-tuning configuration's own metric: calls/s and GB/s over ALL bytes, P + G).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -26,17 +36,24 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
+# issue peak of the vector ALUs: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second
+VALU_PEAK_TLANE = 256 * 4 * 16 * 2.4e9 / 1e12
 METRIC = "projected steps/s and P-stream HBM GB/s (% of peak), D=25.6M n=100 int8"
-METRIC_LAYERWISE = "layer-wise coefficient-form steps/s (Alg. 1) and P-stream HBM GB/s (% of peak)"
+STORAGE_NAME = {"f32": "fp32", "bf16": "bf16", "i8": "int8", "i4": "int4", "mm16": "minmax16", "mm8": "minmax8",
+                "mm4": "minmax4", "mm3": "minmax3", "mm2": "minmax2", "mm1": "minmax1"}
+# vector-ALU lane-instructions per stored element of the step kernels, from rocprofv3 --pmc SQ_INSTS_VALU
+# (profiles/valu_utilisation.txt): the 4-bit and narrower kernels are co-limited by the vector ALUs
+VALU_INSTR_PER_ELEMENT = {"i8": 2.14, "mm8": 2.14, "i4": 2.56, "mm4": 2.56}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def read_traffic(kernel: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc (profiles/hbm_traffic_*.txt), or None."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_imagenet_resnet50_int8.txt")
+def read_traffic(tag: str, kernel: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc for THIS leg, workload and storage
+    (profiles/hbm_traffic_<tag>.txt), or None when no such measurement is committed."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{tag}.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -49,18 +66,25 @@ def read_traffic(kernel: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=1000,
-                    help="untimed steps; the device needs ~0.5 s of this load before the step time settles")
+    ap.add_argument("--steps", type=int, default=1000, help="K: steps per timed repetition")
+    ap.add_argument("--warmup", type=int, default=200, help="W: untimed steps before anything is timed")
+    ap.add_argument("--reps", type=int, default=5, help="timed repetitions of K steps; the median is reported")
+    ap.add_argument("--settle-seconds", type=float, default=1.0,
+                    help="the device runs this load for at least so long before the repetitions are timed "
+                         "(its step time settles after ~0.5 s of load)")
     ap.add_argument("--workload", default="imagenet_resnet50", help="name in synth.WORKLOADS")
-    ap.add_argument("--storage", default="i8", choices=["f32", "bf16", "i8", "i4", "mm16", "mm8", "mm4", "mm3", "mm2", "mm1"],
-                    help="mm16 .. mm1: the paper's per-layer min-max codes of that many bits (layer-wise mode only)")
-    ap.add_argument("--mode", default="whole", choices=["whole", "layerwise"],
+    ap.add_argument("--storage", default=None, choices=list(STORAGE_NAME),
+                    help="mm16 .. mm1: the paper's per-layer min-max codes of that many bits (layer-wise mode only); "
+                         "default: i8 (bf16 in batched mode)")
+    ap.add_argument("--mode", default="whole", choices=["whole", "layerwise", "batched"],
                     help="whole: the headline step (orthonormal basis, s = P^T g, w -= lr P s).  layerwise: Alg. 1 as "
-                         "written -- per-layer centre+normalise basis, coefficient step with weight decay, w = wbar + P beta")
+                         "written -- per-layer centre+normalise basis, coefficient step with weight decay, w = wbar + P beta.  "
+                         "batched: projection only, k gradients per call (S = P^T G)")
+    ap.add_argument("--batched", action="store_true", help="same as --mode batched")
+    ap.add_argument("--k", type=int, default=0, help="gradients per call in batched mode (default: the workload's, 8)")
     ap.add_argument("--D", type=int, default=0, help="override the parameter count (smoke runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of each oracle sample")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known 1 GiB read + 1 GiB write) so that a "
@@ -69,6 +93,10 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build is a single-GPU library (no collectives, no sharding); run with --gpus 1. "
                  "How the path would shard over GPUs is described in the repository's design notes.")
+    if args.batched:
+        args.mode = "batched"
+    if args.storage is None:
+        args.storage = "bf16" if args.mode == "batched" else "i8"
 
     import numpy as np
     import torch
@@ -86,8 +114,10 @@ def main():
     dtype = {"f32": twa.F32, "bf16": twa.BF16, "i8": twa.I8, "i4": twa.I4, "mm8": twa.U8MM, "mm4": twa.U4MM,
              "mm16": twa.U16MM, "mm3": twa.U3MM, "mm2": twa.U2MM, "mm1": twa.U1MM}[args.storage]
     layerwise = args.mode == "layerwise"
+    batched = args.mode == "batched"
     if dtype in twa.MINMAX_TYPES and not layerwise:
         sys.exit("bench.py: the min-max formats exist for the layer-wise calls only (use --mode layerwise)")
+    k = (args.k or max(wl.k, 2)) if batched else 1
 
     # ---- inputs: checkpoints -> orthonormal basis (in place) -> stored P ------------------------
     t0 = time.time()
@@ -121,7 +151,7 @@ def main():
     if dtype != twa.F32:
         del W, P32
         torch.cuda.empty_cache()
-    log(f"[bench] {wl.name}: D={D} n={n} storage={args.storage}; generate {t1 - t0:.2f}s, "
+    log(f"[bench] {wl.name}: D={D} n={n} storage={args.storage} mode={args.mode}; generate {t1 - t0:.2f}s, "
         f"build_basis {t2 - t1:.3f}s, quantize {t3 - t2:.3f}s")
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -131,10 +161,24 @@ def main():
         torch.cuda.synchronize()
         del a, b
         torch.cuda.empty_cache()
-    ring = [synth.gradient(D, wl.sigma_g, seed=args.seed, step=i, device=dev) for i in range(4)]
     lr = wl.lr
     lam = 1e-4                                  # weight decay of the coefficient form (layer-wise mode)
-    if layerwise:
+    p_bytes = pm.stream_bytes
+    if batched:
+        ldg = (D + 3) // 4 * 4
+        nring = 2                               # a batch of gradients is far larger than every cache of the device
+        ring = [synth.gradient(D, wl.sigma_g, seed=args.seed, step=i, device=dev, k=k, ldg=ldg) for i in range(nring)]
+        S = torch.empty((k, n), dtype=torch.float32, device=dev)
+        ws = twa.Workspace(twa.project_workspace_bytes(n, k), device=dev)
+
+        def step(i):
+            twa.project(pm, ring[i % nring], S, ws)
+
+        legs = {"twa_project": (lambda i: twa.project(pm, ring[i % nring], S, ws), p_bytes + 4 * D * k + 4 * n * k)}
+        pass_per_step, unit = 1, "calls/s"
+    elif layerwise:
+        nring = 4
+        ring = [synth.gradient(D, wl.sigma_g, seed=args.seed, step=i, device=dev) for i in range(nring)]
         L = plan.L
         beta = torch.zeros((L, n), dtype=torch.float32, device=dev)
         ws = twa.Workspace(twa.project_layers_workspace_bytes(n, L), device=dev)
@@ -142,7 +186,17 @@ def main():
         def step(i):
             twa.beta_step(pm, ring[i & 3], plan, beta, lr, lam, None, ws)
             twa.weights_from_beta(pm, beta, plan, wbar, w)
+
+        legs = {
+            # P once + g + beta read and written
+            "twa_beta_step": (lambda i: twa.beta_step(pm, ring[i & 3], plan, beta, lr, lam, None, ws), p_bytes + 4 * D + 8 * n * L),
+            # P once + wbar read + w written + beta
+            "twa_weights_from_beta": (lambda i: twa.weights_from_beta(pm, beta, plan, wbar, w), p_bytes + 8 * D + 4 * n * L),
+        }
+        pass_per_step, unit = 2, "steps/s"
     else:
+        nring = 4
+        ring = [synth.gradient(D, wl.sigma_g, seed=args.seed, step=i, device=dev) for i in range(nring)]
         s = torch.empty(n, dtype=torch.float32, device=dev)
         ws = twa.Workspace(twa.project_workspace_bytes(n), device=dev)
 
@@ -150,27 +204,47 @@ def main():
             twa.project(pm, ring[i & 3], s, ws)
             twa.expand_update(pm, s, w, lr)
 
-    # ---- the timed region: exactly K steps --------------------------------------------------------
+        legs = {
+            "twa_project": (lambda i: twa.project(pm, ring[i & 3], s, ws), p_bytes + 4 * D + 4 * n),            # P once + g + s
+            "twa_expand_update": (lambda i: twa.expand_update(pm, s, w, lr), p_bytes + 8 * D + 4 * n),        # P once + w read + w write + s
+        }
+        pass_per_step, unit = 2, "steps/s"
+
+    def timed_steps(count):
+        """`count` steps between two device events on the kernels' stream and two host clock readings, both
+        bracketed by synchronisations; the larger of the two times, in ms."""
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        wall0 = time.perf_counter()
+        e0.record()
+        for i in range(count):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - wall0
+        return max(e0.elapsed_time(e1), wall * 1e3)
+
+    # ---- warm-up, the cold figure, settling, then the timed repetitions of exactly K steps ----------
+    K = args.steps
+    load0 = time.perf_counter()
     for i in range(args.warmup):
         step(i)
-    torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    wall0 = time.perf_counter()
-    e0.record()
-    for i in range(args.steps):
-        step(i)
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - wall0
-    ms_total = e0.elapsed_time(e1)
-    ms_per_step = max(ms_total, wall * 1e3) / args.steps    # never report less than the host saw
+    cold_ms = timed_steps(K) / K                         # what a single short run would report
+    settle_steps = 0
+    while time.perf_counter() - load0 < args.settle_seconds:
+        for i in range(32):
+            step(i)
+        settle_steps += 32
+        torch.cuda.synchronize()
+    load_s = time.perf_counter() - load0
+    rep_ms = [timed_steps(K) / K for _ in range(max(1, args.reps))]
+    ms_per_step = statistics.median(rep_ms)
     steps_per_s = 1e3 / ms_per_step
-    p_bytes = pm.stream_bytes
-    p_stream_gbps = steps_per_s * 2 * p_bytes / 1e9
+    p_stream_gbps = steps_per_s * pass_per_step * p_bytes / 1e9
 
     # ---- per-kernel launch durations (device events around every launch, same stream) ----------
-    K2 = min(args.steps, 200)
+    K2 = max(20, min(K, 200))
 
     def timed_each(fn):
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K2)]
@@ -179,31 +253,31 @@ def main():
             fn(i)
             b.record()
         torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in evs) / K2
+        return statistics.median(a.elapsed_time(b) for a, b in evs)
 
-    if layerwise:
-        ms_project = timed_each(lambda i: twa.beta_step(pm, ring[i & 3], plan, beta, lr, lam, None, ws))
-        ms_expand = timed_each(lambda i: twa.weights_from_beta(pm, beta, plan, wbar, w))
-        alg = {
-            "twa_beta_step": p_bytes + 4 * D + 8 * n * L,           # P once + g + beta read and written
-            "twa_weights_from_beta": p_bytes + 8 * D + 4 * n * L,   # P once + wbar read + w written + beta
-        }
-        dur = {"twa_beta_step": ms_project, "twa_weights_from_beta": ms_expand}
-    else:
-        ms_project = timed_each(lambda i: twa.project(pm, ring[i & 3], s, ws))
-        ms_expand = timed_each(lambda i: twa.expand_update(pm, s, w, lr))
-        alg = {
-            "twa_project": p_bytes + 4 * D + 4 * n,                 # P once + g + s
-            "twa_expand_update": p_bytes + 8 * D + 4 * n,           # P once + w read + w write + s
-        }
-        dur = {"twa_project": ms_project, "twa_expand_update": ms_expand}
+    dur = {name: timed_each(fn) for name, (fn, _) in legs.items()}
+    alg = {name: nbytes for name, (_, nbytes) in legs.items()}
     dom = max(dur, key=dur.get)
     achieved = alg[dom] / (dur[dom] * 1e-3) / 1e9
+    tag = ("layerwise_" if layerwise else "batched_" if batched else "") + f"{wl.name}_{STORAGE_NAME[args.storage]}"
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(dom),
-                "algorithmic_bytes_per_launch": alg[dom], "avg_launch_ms": round(dur[dom], 5),
-                "other_kernel": {"kernel": min(dur, key=dur.get), "avg_launch_ms": round(min(dur.values()), 5),
-                                 "achieved": round(alg[min(dur, key=dur.get)] / (min(dur.values()) * 1e-3) / 1e9, 1)}}
+                "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": read_traffic(tag, dom) if D == wl.D else None,
+                "algorithmic_bytes_per_launch": alg[dom], "avg_launch_ms": round(dur[dom], 5)}
+    others = [nm for nm in dur if nm != dom]
+    if others:
+        o = others[0]
+        roofline["other_kernel"] = {"kernel": o, "avg_launch_ms": round(dur[o], 5),
+                                    "achieved": round(alg[o] / (dur[o] * 1e-3) / 1e9, 1)}
+    if args.storage in VALU_INSTR_PER_ELEMENT:
+        # the second bound of the integer-code kernels: vector-ALU issue (decode + FMA per stored element)
+        lane_instr = VALU_INSTR_PER_ELEMENT[args.storage] * n * D
+        tl = lane_instr / (dur[dom] * 1e-3) / 1e12
+        roofline["valu"] = {"lane_instr_per_element": VALU_INSTR_PER_ELEMENT[args.storage],
+                            "achieved_Tlane_instr_per_s": round(tl, 2), "peak": round(VALU_PEAK_TLANE, 2),
+                            "frac": round(tl / VALU_PEAK_TLANE, 4),
+                            "note": "co-limited: neither HBM nor the vector ALUs saturated" if tl / VALU_PEAK_TLANE > 0.5
+                            else "HBM bound; the vector ALUs are mostly idle"}
 
     # ---- the read ceiling of this device, measured: plain non-temporal reads over the stored codes ----
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -227,9 +301,11 @@ def main():
         from oracle import twa_oracle as orc
         from oracle.bridge import to_oracle
 
-        g_h = ring[0].cpu().numpy().astype(np.float64)
+        g_h = (ring[0][:, :D] if batched else ring[0]).cpu().numpy().astype(np.float64)
         w_h = w.cpu().numpy().astype(np.float64)
         off_h = plan.layer_off.cpu().numpy() if layerwise else None
+        what = ("coefficient step + weights from coefficients, layer-wise" if layerwise
+                else f"projection of {k} gradients" if batched else "project + expand_update")
 
         def oracle_step(cols):
             po = to_oracle(pm, cols=cols, layer_off=off_h)
@@ -239,36 +315,68 @@ def main():
                 bo = np.zeros_like(so)
                 orc.beta_step(bo, so, lr, lam)
                 orc.weights_from_beta(po, bo, off_h, w_h)
+            elif batched:
+                orc.project(po, g_h)
             else:
                 so = orc.project(po, g_h)
                 orc.expand_update(po, so, w_h.copy(), lr)
             return time.perf_counter() - t
 
-        t_one = oracle_step([0])
-        m = int(max(1, min(n, round(args.cpu_seconds / max(t_one, 1e-6)))))
-        reps, t_sum = 0, 0.0
-        while reps == 0 or (m == n and t_sum < args.cpu_seconds and reps < 50):
-            t_sum += oracle_step(list(range(m))) if m > 1 else oracle_step([0])
-            reps += 1
-        t_m = t_sum / reps
-        cpu = {"value": round(1.0 / (t_m * n / m), 5), "unit": "steps/s", "cores": orc.threads(), "kind": "oracle",
-               "sample": f"{reps} full step(s) ({'coefficient step + weights from coefficients, layer-wise' if layerwise else 'project + expand_update'}, fp64, on-the-fly dequantisation) over the "
-                         f"first {m} of {n} basis vectors at full D={D}: {t_m:.2f} s per step-sample, scaled by {n}/{m}"}
+        def sample(budget_s):
+            """Steps/s of the oracle from a sample of about `budget_s` seconds: whole steps if one fits the budget,
+            else one step over the first m basis vectors, scaled by n/m (both passes are linear in the vectors)."""
+            t_one = oracle_step([0])
+            m = int(max(1, min(n, round(budget_s / max(t_one, 1e-6)))))
+            reps, t_sum = 0, 0.0
+            while reps == 0 or (m == n and t_sum < budget_s and reps < 50):
+                t_sum += oracle_step(list(range(m)))
+                reps += 1
+            t_m = t_sum / reps
+            return 1.0 / (t_m * n / m), f"{reps} step(s) over the first {m} of {n} basis vectors at full D={D}: {t_m:.2f} s each, scaled by {n}/{m}"
 
+        all_cores = orc.threads()
+        v_all, how_all = sample(args.cpu_seconds)
+        orc.set_threads(1)
+        v_one, how_one = sample(args.cpu_seconds * 0.75)
+        orc.set_threads(all_cores)
+        cpu = {"value": round(v_all, 5), "unit": unit, "cores": all_cores, "kind": "oracle",
+               "sample": f"{what}, fp64, on-the-fly dequantisation; {how_all}",
+               "one_core": {"value": round(v_one, 5), "unit": unit, "cores": 1, "sample": how_one}}
+
+    store_txt = f"P stored as {args.storage}" + (f" (block {pm.block}, {'fp32' if dtype == twa.I8 else 'fp16'} scales)"
+                                                  if dtype in (twa.I8, twa.I4) else "")
+    headline = (args.mode == "whole" and wl.name == "imagenet_resnet50" and args.storage == "i8" and D == wl.D)
+    if headline:
+        metric = METRIC
+    elif batched:
+        metric = f"batched projections/s (k={k} gradients per call) and HBM GB/s over all bytes (% of peak), {wl.name} D={D} n={n} {args.storage}"
+    elif layerwise:
+        metric = f"layer-wise coefficient-form steps/s (Alg. 1) and P-stream HBM GB/s (% of peak), {wl.name} D={D} n={n} {args.storage}"
+    else:
+        metric = f"projected steps/s and P-stream HBM GB/s (% of peak), {wl.name} D={D} n={n} {args.storage}"
     out = {
-        "metric": METRIC if not layerwise else METRIC_LAYERWISE, "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "metric": metric, "value": round(steps_per_s, 2), "unit": unit, "n_gpus": 1, "steps": K,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: D={D}, n={n}, P stored as {args.storage}"
-                               + (f" (block {pm.block}, {'fp32' if dtype == twa.I8 else 'fp16'} scales)"
-                                  if dtype in (twa.I8, twa.I4) else "")
-                               + (f"; layer-wise, L={plan.L}, centre+normalise basis, coefficient form, lambda={lam}"
-                                  if layerwise else ""),
-                   "lr": lr, "sigma_g": wl.sigma_g, "gradient_ring": 4, "seed": args.seed},
+        "config": {"workload": f"{wl.name}: D={D}, n={n}, {store_txt}"
+                               + (f"; layer-wise, L={plan.L}, centre+normalise basis, coefficient form, lambda={lam}" if layerwise else "")
+                               + (f"; projection only, k={k} gradients per call" if batched else ""),
+                   "lr": lr, "sigma_g": wl.sigma_g, "gradient_ring": nring, "seed": args.seed},
+        "timing": {"protocol": f"median of {len(rep_ms)} repetitions of {K} steps after {args.warmup} warm-up steps and "
+                               f"{load_s:.2f} s of this load on the device",
+                   "rep_ms_per_step": [round(x, 5) for x in rep_ms], "min_ms_per_step": round(min(rep_ms), 5),
+                   "max_ms_per_step": round(max(rep_ms), 5), "cold_ms_per_step": round(cold_ms, 5),
+                   "cold_note": f"the {K} steps right after the {args.warmup} warm-up steps, before the device's step time has settled",
+                   "settle_steps": settle_steps, "device_load_s_before_timing": round(load_s, 3)},
         "p_stream_GBps": round(p_stream_gbps, 1), "p_stream_pct_of_peak": round(100 * p_stream_gbps / HBM_PEAK_GBPS, 2),
         "p_bytes_per_pass": p_bytes, "roofline": roofline, "cpu_baseline": cpu,
         "setup_s": {"generate": round(t1 - t0, 3), "build_basis": round(t2 - t1, 4), "quantize": round(t3 - t2, 4)},
     }
+    if batched:
+        tot = alg["twa_project"]
+        out["total_GBps"] = round(steps_per_s * tot / 1e9, 1)
+        out["total_pct_of_peak"] = round(100 * steps_per_s * tot / 1e9 / HBM_PEAK_GBPS, 2)
+        out["total_bytes_per_call"] = tot
     print(json.dumps(out), flush=True)
 
 
