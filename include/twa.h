@@ -123,6 +123,24 @@ const char* twa_strerror(int status);
 int twa_last_hip_error(void);
 
 /*
+ * Launch geometry, for tests and tuning runs only.  The library reads NO environment variable and keeps no
+ * other state between calls; these three process-wide integers are the one exception, and they change the
+ * launch geometry only -- never which operation is computed.  0 (the initial value) leaves the choice to the
+ * library.  The reduction order of twa_project[_layers] follows the grid, so the bits of its result are
+ * reproducible for a given knob value, not across values.  Set them while no call of the library is in flight.
+ *   TWA_KNOB_PROJECT_GRID      upper bound of the workgroups of the projection kernels (also the squares pass of
+ *                              twa_centre_normalise)             1 .. 2048
+ *   TWA_KNOB_EXPAND_GRID       upper bound of the workgroups of the expansion kernels          1 .. 2048
+ *   TWA_KNOB_BASIS_WGS_PER_CU  workgroups per compute unit of the Gram / apply kernels (default 2)
+ * Errors: TWA_ERR_DTYPE (unknown knob), TWA_ERR_SHAPE (value < 0 or > 2048).
+ */
+#define TWA_KNOB_PROJECT_GRID 0
+#define TWA_KNOB_EXPAND_GRID 1
+#define TWA_KNOB_BASIS_WGS_PER_CU 2
+#define TWA_KNOB_COUNT 3
+int twa_set_launch_knob(int32_t knob, int32_t value);
+
+/*
  * Sizes of the buffers that hold an n-vector matrix of logical length D in storage `dtype`.
  * Writes the smallest admissible ld, and the byte sizes of `data` and `scales` for that ld
  * (scale_bytes = 0 for F32/BF16).  Matches the paper's memory table (Sec. 4.6): 4nD bytes at
@@ -273,6 +291,12 @@ int twa_layer_plan_bytes(int32_t L, size_t* bytes);
  *                   intact as long as step calls use it, and is valid for any stored matrix with
  *                   the same D (every dtype).
  * 1 <= L <= TWA_MAX_LAYERS.  Asynchronous on `stream`.
+ * The plan carries the L and D it was built for.  The host cannot see into it, so a call that is handed a
+ * plan of another layer count or vector length still returns TWA_OK; on the device every kernel compares the
+ * plan's L and D with its own before it reads a table and, if they differ, touches nothing else and marks
+ * its result instead: twa_project_layers / twa_beta_step fill S (and beta) with NaN, twa_expand_update_layers /
+ * twa_weights_from_beta set w[0] (and g_tilde[0]) to NaN and leave the rest alone, twa_quantize_minmax writes
+ * NaN factors, twa_centre_normalise NaN norms and E[0] = NaN.
  */
 int twa_layer_plan(const int64_t* layer_off, int32_t L, int64_t D, void* plan, size_t plan_bytes, void* stream);
 
@@ -400,7 +424,7 @@ int twa_weights_from_beta(const twa_pmat* P, const float* beta, const void* plan
                           float* w, void* stream);
 
 /*
- * Measurement aid, no part of the method: one plain pass of non-temporal 128-bit reads over `bytes` bytes
+ * Measurement aid, NO part of the method and never called by any other entry point: one plain pass of non-temporal 128-bit reads over `bytes` bytes
  * (rounded down to 16) of `buf`, for callers that want the read ceiling of the device they run on next
  * to the rates of the step kernels (the benchmark reports both).
  *   buf  [in]  device, 16-byte aligned.     sink [out] device, 4 bytes; left alone in practice.

@@ -81,6 +81,8 @@ def lib():
         L.twa_expand_update.argtypes = [C.POINTER(_Pmat), vp, vp, f32, vp, vp]
         L.twa_project_noalloc.argtypes = [C.POINTER(_Pmat), vp, i32, i64, vp, vp]
         L.twa_project_noalloc.restype = C.c_int
+        L.twa_set_launch_knob.argtypes = [i32, i32]
+        L.twa_set_launch_knob.restype = C.c_int
         L.twa_project_layers_workspace_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
         L.twa_project_layers.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, vp, C.c_size_t, vp]
         L.twa_expand_update_layers.argtypes = [C.POINTER(_Pmat), vp, vp, i32, vp, f32, vp, vp]
@@ -108,6 +110,14 @@ def lib():
             f.restype = C.c_int
         _lib = L
     return _lib
+
+
+KNOB_PROJECT_GRID, KNOB_EXPAND_GRID, KNOB_BASIS_WGS_PER_CU = 0, 1, 2
+
+
+def set_launch_knob(knob: int, value: int) -> None:
+    """twa_set_launch_knob: launch geometry for tests and tuning runs (0 = the library's own choice)."""
+    _check(lib().twa_set_launch_knob(int(knob), int(value)), "twa_set_launch_knob")
 
 
 def strerror(code: int) -> str:
@@ -296,7 +306,7 @@ class LayerPlan:
 
     def tables(self):
         """(off, first2048, first1024) copied to the host, for inspection."""
-        raw = self.buf.cpu()
+        raw = self.buf.cpu()[2:]                       # behind the 16-byte header {magic, L, D}
         n = self.L + 1
         off = raw[:n].clone()
         rest = raw[n:].view(torch.int32)

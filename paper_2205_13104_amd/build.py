@@ -29,6 +29,10 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 5) -> str:
     os.makedirs(objdir, exist_ok=True)
     hdrs = [os.path.normpath(os.path.join(CSRC, h)) for h in HEADERS]
     procs, objs = [], []
+
+    def running():
+        return [p for _, p, _ in procs if p.poll() is None]
+
     for src in SOURCES:
         s = os.path.join(CSRC, src)
         o = os.path.join(objdir, src.replace(".hip", ".o"))
@@ -37,14 +41,16 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 5) -> str:
             cmd = [hipcc] + FLAGS + ["-c", s, "-o", o]
             if verbose:
                 print(" ".join(cmd), flush=True)
-            procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-            while len([p for _, p in procs if p.poll() is None]) >= jobs:
-                for _, p in procs:
-                    if p.poll() is None:
-                        p.wait()
-                        break
-    for src, p in procs:
-        out, _ = p.communicate()
+            # the compiler's output goes to a file: a pipe nobody reads while waiting can fill up and block it
+            log = open(o + ".log", "w+")
+            procs.append((src, subprocess.Popen(cmd, stdout=log, stderr=subprocess.STDOUT, text=True), log))
+            while len(running()) >= jobs:
+                running()[0].wait()
+    for src, p, log in procs:
+        p.wait()
+        log.seek(0)
+        out = log.read()
+        log.close()
         if p.returncode != 0:
             sys.stderr.write(out)
             raise RuntimeError(f"hipcc failed on {src}")

@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <initializer_list>
 #include <mutex>
 #include <vector>
@@ -35,13 +36,9 @@ int device_cus() {
   return cus[dev];
 }
 
-int env_int(const char* name, int fallback) {
-  const char* v = getenv(name);
-  if (!v || !*v) return fallback;
-  char* end = nullptr;
-  long x = strtol(v, &end, 10);
-  return (end && *end == 0 && x > 0 && x < (1 << 20)) ? (int)x : fallback;
-}
+// Launch-geometry knobs (twa_set_launch_knob): process-wide, 0 = the library's own choice.
+static std::atomic<int> g_knob[TWA_KNOB_COUNT];
+int launch_knob(int which) { return (which >= 0 && which < TWA_KNOB_COUNT) ? g_knob[which].load(std::memory_order_relaxed) : 0; }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
@@ -125,11 +122,11 @@ static int view_of(const twa_pmat* P, PView* v) {
 }
 
 // Upper bound of a persistent grid: `per_cu_x4`/4 workgroups per compute unit (a multiple of a
-// quarter), or the absolute value of the environment variable `env_name` when it is set.
-static int persistent_grid(const char* env_name, int per_cu_x4) {
+// quarter), or the caller's absolute value of the launch knob `knob` when one is set.
+static int persistent_grid(int knob, int per_cu_x4) {
   const int cus = device_cus();
   if (cus <= 0) return -1;
-  int64_t g = env_int(env_name, 0);
+  int64_t g = launch_knob(knob);
   if (g <= 0) g = (int64_t)cus * per_cu_x4 / 4;
   if (g > kMaxGrid) g = kMaxGrid;
   if (g < 1) g = 1;
@@ -198,6 +195,13 @@ const char* twa_strerror(int status) {
 
 int twa_last_hip_error(void) { return g_last_hip_error; }
 
+int twa_set_launch_knob(int32_t knob, int32_t value) {
+  if (knob < 0 || knob >= TWA_KNOB_COUNT) return TWA_ERR_DTYPE;
+  if (value < 0 || value > kMaxGrid) return TWA_ERR_SHAPE;
+  g_knob[knob].store(value, std::memory_order_relaxed);
+  return TWA_OK;
+}
+
 int twa_pmat_bytes(int32_t dtype, int64_t D, int32_t n, int32_t block, int64_t* ld, size_t* data_bytes,
                    size_t* scale_bytes) {
   if (!ld || !data_bytes || !scale_bytes) return TWA_ERR_NULL;
@@ -247,7 +251,7 @@ int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float
   if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
   if (!aligned16(ws)) return TWA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
+  const int grid = persistent_grid(TWA_KNOB_PROJECT_GRID, 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   float* partial = static_cast<float*>(ws);
   if (k == 1) return launch_project(v, P->dtype, g, s, partial, grid, st);
@@ -264,7 +268,7 @@ int twa_project_noalloc(const twa_pmat* P, const float* g, int32_t k, int64_t ld
   if (k > 1 && (ldg < v.D || (ldg & 3) != 0)) return TWA_ERR_SHAPE;
   if (!aligned16(g) || (reinterpret_cast<uintptr_t>(s) & 3u)) return TWA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
+  const int grid = persistent_grid(TWA_KNOB_PROJECT_GRID, 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   float* partial = nullptr;
   size_t floats = 0;
@@ -283,7 +287,7 @@ int twa_expand_update(const twa_pmat* P, const float* s, float* w, float lr, flo
   if (!aligned16(w) || (g_tilde && !aligned16(g_tilde)) || (reinterpret_cast<uintptr_t>(s) & 3u))
     return TWA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int grid = persistent_grid("TWA_EXPAND_GRID", 8);
+  const int grid = persistent_grid(TWA_KNOB_EXPAND_GRID, 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   return launch_expand_update(v, P->dtype, s, w, lr, g_tilde, grid, st);
 }
@@ -335,7 +339,7 @@ static int project_layers_common(const twa_pmat* P, const float* g, const void* 
   twa_project_layers_workspace_bytes(v.n, L, &need);
   if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
   if (!aligned16(ws)) return TWA_ERR_ALIGN;
-  const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
+  const int grid = persistent_grid(TWA_KNOB_PROJECT_GRID, 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   return launch_project_layers(v, P->dtype, g, plan, L, S, beta, lr, lambda, static_cast<float*>(ws), grid,
                                static_cast<hipStream_t>(stream));
@@ -363,7 +367,7 @@ int twa_expand_update_layers(const twa_pmat* P, const float* S, const void* plan
   if (rc != TWA_OK) return rc;
   if (!aligned16(w) || (g_tilde && !aligned16(g_tilde)) || (reinterpret_cast<uintptr_t>(S) & 3u))
     return TWA_ERR_ALIGN;
-  const int grid = persistent_grid("TWA_EXPAND_GRID", 8);
+  const int grid = persistent_grid(TWA_KNOB_EXPAND_GRID, 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   return launch_expand_update_layers(v, P->dtype, S, plan, L, w, w, lr, g_tilde, grid,
                                      static_cast<hipStream_t>(stream));
@@ -378,7 +382,7 @@ int twa_weights_from_beta(const twa_pmat* P, const float* beta, const void* plan
   rc = check_plan(plan, L);
   if (rc != TWA_OK) return rc;
   if (!aligned16(w) || !aligned16(wbar) || (reinterpret_cast<uintptr_t>(beta) & 3u)) return TWA_ERR_ALIGN;
-  const int grid = persistent_grid("TWA_EXPAND_GRID", 8);
+  const int grid = persistent_grid(TWA_KNOB_EXPAND_GRID, 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   // w = wbar - (-1) * (P beta): the expansion kernel with the mean as the weights it reads
   return launch_expand_update_layers(v, P->dtype, beta, plan, L, wbar, w, -1.0f, nullptr, grid,
@@ -469,7 +473,7 @@ int twa_centre_normalise(const float* W, int64_t D, int32_t n, int64_t ldw, cons
   }
   if (!ws || ws_bytes < centre_workspace_bytes(D, n, L)) return TWA_ERR_WORKSPACE;
   if (!aligned16(ws)) return TWA_ERR_ALIGN;
-  const int grid = persistent_grid("TWA_PROJECT_GRID", 8);
+  const int grid = persistent_grid(TWA_KNOB_PROJECT_GRID, 8);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   return launch_centre_normalise(W, D, n, ldw, plan, L, wbar, E, lde, norms, ws, grid, static_cast<hipStream_t>(stream));
 }
@@ -524,7 +528,8 @@ static int basis_grid(int64_t rows) {
   const int cus = device_cus();
   if (cus <= 0) return -1;
   const int64_t nchunks = (rows + 63) / 64;
-  int grid = cus * env_int("TWA_BASIS_WGS_PER_CU", 2);
+  const int per_cu = launch_knob(TWA_KNOB_BASIS_WGS_PER_CU);
+  int grid = cus * (per_cu > 0 ? per_cu : 2);
   if (grid > kGramMaxGrid) grid = kGramMaxGrid;
   if (grid > nchunks) grid = (int)nchunks;
   return grid;

@@ -332,6 +332,18 @@ struct LayerPlan {
   const int32_t* first;    // L+1 tile indices for the tile size of the kernel at hand
   int32_t L;
 };
+// The plan buffer starts with a 16-byte header {magic, L, D (64 bit)} written by the kernel that builds the
+// plan; off[] follows it directly.  A caller may hand a step call a plan that was built for another layer
+// count or vector length (the host cannot see into device memory): every kernel that reads plan tables
+// compares the header with its own L and D FIRST and, on a mismatch, reads no table at all and poisons its
+// output with NaN instead (the tables would be read at the wrong places, and tile counts taken from there
+// could carry stores out of the workspace).
+constexpr uint32_t kPlanMagic = 0x50415754u;
+constexpr int kPlanHeaderBytes = 16;
+__device__ __forceinline__ bool plan_header_ok(const int64_t* off, int L, int64_t D) {
+  const int32_t* h = reinterpret_cast<const int32_t*>(off) - kPlanHeaderBytes / 4;
+  return (uint32_t)h[0] == kPlanMagic && h[1] == L && *reinterpret_cast<const int64_t*>(h + 2) == D;
+}
 // Largest l in [0, L-1] with first[l] <= t: the layer that owns tile t (empty layers own none).
 __device__ __forceinline__ int layer_of_tile(const LayerPlan& plan, int64_t t) {
   int a = 0, b = plan.L - 1;

@@ -295,6 +295,15 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t D = P.D;
+  if constexpr (LAYERED) {
+    if (!plan_header_ok(plan.off, plan.L, D)) {           // not this call's plan: no table is read, nothing is expanded,
+      if (blockIdx.x == 0 && threadIdx.x == 0 && chunk == 0) {      // and the first weight says so
+        w[0] = __builtin_nanf("");
+        if (g_tilde) g_tilde[0] = __builtin_nanf("");
+      }
+      return;
+    }
+  }
   const int64_t ntiles_all = LAYERED ? (int64_t)plan.first[LAYERED ? plan.L : 0] : (D + X::TILE - 1) / X::TILE;
   // the run of tiles of this launch, and the tiles per wave (set here, because the number of
   // per-layer tiles is known on the device only)

@@ -18,8 +18,8 @@ int device_cus();
 // Upper bound of any persistent grid the library launches (sizes the workspaces).
 constexpr int kMaxGrid = 2048;
 
-// Integer tuning knob from the environment (read once per name), e.g. TWA_PROJECT_WGS_PER_CU.
-int env_int(const char* name, int fallback);
+// Current value of a launch knob (TWA_KNOB_*, set with twa_set_launch_knob); 0 = the library's own choice.
+int launch_knob(int which);
 
 // Kernel launchers (defined next to their kernels).
 // `max_grid`: upper bound of the persistent grid; the launchers pick the largest grid below it

@@ -2,6 +2,7 @@
 // coefficients per layer).  The step kernels cut their tiles per layer, so that a tile never meets
 // two layers and the stream over P stays the branch-free one of the whole-model step; this file
 // turns the caller's table of layer offsets into what those kernels need:
+//   header          {magic, L, D}: 16 bytes the step kernels compare with their own arguments
 //   off[L+1]        the offsets, clamped into a non-decreasing table with off[0] = 0, off[L] = D
 //   first2048[L+1]  index of the first tile of every layer for tiles of 2048 elements
 //   first1024[L+1]  the same for tiles of 1024 elements
@@ -27,6 +28,12 @@ __global__ __launch_bounds__(kPlanThreads) void layer_plan_kernel(const int64_t*
   __shared__ int64_t s_max[kPlanThreads];
   __shared__ int32_t s_a[kPlanThreads], s_b[kPlanThreads];
   const int i = threadIdx.x;
+  if (i == 0) {                                        // the header the step kernels check (see plan_header_ok)
+    int32_t* h = reinterpret_cast<int32_t*>(off) - kPlanHeaderBytes / 4;
+    h[0] = (int32_t)kPlanMagic;
+    h[1] = L;
+    *reinterpret_cast<int64_t*>(h + 2) = D;
+  }
   const int chunk = (L + 1 + kPlanThreads - 1) / kPlanThreads;
   const int q0 = i * chunk;
   const int q1 = q0 + chunk < L + 1 ? q0 + chunk : L + 1;
@@ -73,17 +80,17 @@ __global__ __launch_bounds__(kPlanThreads) void layer_plan_kernel(const int64_t*
   }
 }
 
-size_t layer_plan_bytes(int L) { return (size_t)(L + 1) * (sizeof(int64_t) + 2 * sizeof(int32_t)); }
+size_t layer_plan_bytes(int L) { return kPlanHeaderBytes + (size_t)(L + 1) * (sizeof(int64_t) + 2 * sizeof(int32_t)); }
 
 LayerPlan plan_view(const void* plan_dev, int L, int tile) {
-  const int64_t* off = static_cast<const int64_t*>(plan_dev);
+  const int64_t* off = reinterpret_cast<const int64_t*>(static_cast<const uint8_t*>(plan_dev) + kPlanHeaderBytes);
   const int32_t* f2048 = reinterpret_cast<const int32_t*>(off + L + 1);
   const int32_t* f1024 = f2048 + L + 1;
   return LayerPlan{off, tile == 2048 ? f2048 : f1024, L};
 }
 
 int launch_layer_plan(const int64_t* layer_off, int L, int64_t D, void* plan_dev, hipStream_t st) {
-  int64_t* off = static_cast<int64_t*>(plan_dev);
+  int64_t* off = reinterpret_cast<int64_t*>(static_cast<uint8_t*>(plan_dev) + kPlanHeaderBytes);
   int32_t* f2048 = reinterpret_cast<int32_t*>(off + L + 1);
   int32_t* f1024 = f2048 + L + 1;
   hipLaunchKernelGGL(layer_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, layer_off, L, D, off, f2048, f1024);

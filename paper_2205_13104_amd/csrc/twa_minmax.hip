@@ -37,6 +37,7 @@ __global__ __launch_bounds__(256) void minmax_init_kernel(uint32_t* __restrict__
 __global__ __launch_bounds__(256) void layer_minmax_kernel(const float* __restrict__ P, int64_t D, int n, int64_t ldp,
                                                            LayerPlan plan, uint32_t* __restrict__ keys) {
   constexpr int TILE = 2048;
+  if (!plan_header_ok(plan.off, plan.L, D)) return;      // not this call's plan: layer_factors_kernel answers with NaN
   const int ntiles = plan.first[plan.L];
   const int per = (ntiles + gridDim.x - 1) / gridDim.x;
   const int t0 = blockIdx.x * per;
@@ -86,9 +87,15 @@ __global__ __launch_bounds__(256) void layer_minmax_kernel(const float* __restri
 // layer gets (0, 0).
 __global__ __launch_bounds__(256) void layer_factors_kernel(const uint32_t* __restrict__ keys, int L, double levels,
                                                             float* __restrict__ ab, double* __restrict__ a64,
-                                                            double* __restrict__ ra64) {
+                                                            double* __restrict__ ra64, const int64_t* __restrict__ off,
+                                                            int64_t D) {
   const int l = blockIdx.x * 256 + threadIdx.x;
   if (l >= L) return;
+  if (!plan_header_ok(off, L, D)) {                      // a plan of another layer table: every factor says so
+    ab[2 * l] = ab[2 * l + 1] = __builtin_nanf("");
+    a64[l] = ra64[l] = __builtin_nan("");
+    return;
+  }
   const uint32_t kmin = keys[2 * l], kmax = keys[2 * l + 1];
   double a = 0.0;
   float b = 0.0f;
@@ -118,6 +125,7 @@ __global__ __launch_bounds__(256) void minmax_codes_kernel(const float* __restri
                                                            uint32_t half) {
   constexpr int BITS = Store<DT>::kBitsPerElem;
   constexpr int EL = 32 / BITS;                 // elements per dword
+  if (!plan_header_ok(off, L, D)) return;       // (the factors are NaN already; no table is read)
   const int j = blockIdx.y;
   const int64_t nquad = ld / (WPT * EL);        // groups of WPT dwords per vector (ld is a multiple of 2048)
   const float* p = P + (int64_t)j * ldp;
@@ -209,6 +217,7 @@ __global__ __launch_bounds__(256) void minmax_codes3_kernel(const float* __restr
                                                             const float* __restrict__ ab,
                                                             const double* __restrict__ a64,
                                                             const double* __restrict__ ra64, double levels) {
+  if (!plan_header_ok(off, L, D)) return;       // (the factors are NaN already; no table is read)
   const int j = blockIdx.y;
   const int64_t ngroups = ld / 32;
   const float* p = P + (int64_t)j * ldp;
@@ -282,7 +291,7 @@ int launch_quantize_minmax(const float* P, int64_t D, int n, int64_t ldp, const 
   hipLaunchKernelGGL(minmax_init_kernel, dim3(lgrid), dim3(256), 0, st, keys, L);
   const int cus = device_cus();
   hipLaunchKernelGGL(layer_minmax_kernel, dim3(cus * 4), dim3(256), 0, st, P, D, n, ldp, plan, keys);
-  hipLaunchKernelGGL(layer_factors_kernel, dim3(lgrid), dim3(256), 0, st, keys, L, levels, ab, a64, ra64);
+  hipLaunchKernelGGL(layer_factors_kernel, dim3(lgrid), dim3(256), 0, st, keys, L, levels, ab, a64, ra64, plan.off, D);
   const int el = dtype == TWA_U16MM ? 2 : dtype == TWA_U8MM ? 4 : dtype == TWA_U4MM ? 8 : dtype == TWA_U2MM ? 16 : 32;
   // dwords of codes a thread writes per trip, per container: measured at the ResNet-50 shape (code pass in ms
   // for 1 / 2 / 4 dwords: 16 bits 11.2 / 7.7 / 6.8, 8 bits 5.9 / 3.9 / 3.3, 4 bits 3.7 / 3.1 / 4.5,

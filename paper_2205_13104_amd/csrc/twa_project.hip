@@ -50,6 +50,9 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
   const int64_t D = P.D;
+  if constexpr (LAYERED) {
+    if (!plan_header_ok(plan.off, plan.L, D)) return;      // not this call's plan: the reduction kernel answers with NaN
+  }
   const int64_t ntiles = LAYERED ? (int64_t)plan.first[LAYERED ? plan.L : 0] : (D + TILE - 1) / TILE;
   // every workgroup owns the same number of consecutive tiles (the last ones may own fewer); the
   // number of per-layer tiles is known on the device only, so there the split is made here
@@ -573,13 +576,17 @@ struct BetaStep {
 constexpr int kRedWays = 8;
 template <bool MINMAX>
 __global__ __launch_bounds__(TWA_MAX_N* kRedWays) void project_layers_reduce_kernel(
-    const float* __restrict__ partial, const float* __restrict__ partial_g, int n, LayerPlan plan, int grid,
+    const float* __restrict__ partial, const float* __restrict__ partial_g, int n, LayerPlan plan, int64_t D, int grid,
     const float* __restrict__ ab, float bias, float* __restrict__ S, BetaStep bs) {
   __shared__ double red[kRedWays][TWA_MAX_N];
   __shared__ double redg[kRedWays];
   const int l = blockIdx.x;
   const int j = threadIdx.x % TWA_MAX_N;
   const int q = threadIdx.x / TWA_MAX_N;
+  if (!plan_header_ok(plan.off, plan.L, D)) {             // a plan of another layer table: no table is read
+    if (q == 0 && j < n) bs.finish(S, (int64_t)l * n + j, __builtin_nanf(""));
+    return;
+  }
   const int ntiles = plan.first[plan.L];
   const int tiles_per_wg = ntiles > 0 ? (ntiles + grid - 1) / grid : 1;      // as in project_kernel
   const int32_t ta = plan.first[l], tb = plan.first[l + 1];                  // tiles [ta, tb)
@@ -618,7 +625,7 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   int rc = launch_project_dt<DT, 1, VPL, true>(P, g, 0, 1, partial, max_grid, &grid, st, plan, partial_g);
   if (rc != TWA_OK) return rc;
   hipLaunchKernelGGL(project_layers_reduce_kernel<kMinMax<DT>>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial,
-                     partial_g, P.n, plan, grid, reinterpret_cast<const float*>(P.scales),
+                     partial_g, P.n, plan, P.D, grid, reinterpret_cast<const float*>(P.scales),
                      kNibbles<DT> ? 8.0f : P.code_bias,   // (nibbles are decoded as code + 8 - 8)
                     
                      S, bs);
@@ -635,7 +642,7 @@ int launch_layer_squares(const PView& P, const float* mean_hi, float* mean_lo, c
   int rc = launch_project_dt<TWA_F32, 1, 4, true, true>(P, mean_hi, 0, 1, partial, max_grid, &grid, st, plan, mean_lo);
   if (rc != TWA_OK) return rc;
   hipLaunchKernelGGL(project_layers_reduce_kernel<false>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial, nullptr,
-                     P.n, plan, grid, nullptr, 0.0f, Q, BetaStep{nullptr, 0.0f, 0.0f});
+                     P.n, plan, P.D, grid, nullptr, 0.0f, Q, BetaStep{nullptr, 0.0f, 0.0f});
   return hip_check(hipGetLastError());
 }
 

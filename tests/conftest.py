@@ -27,3 +27,19 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture
+def launch_knobs():
+    """Setter for the library's launch-geometry knobs that puts every knob back to 0 (the library's own choice)
+    when the test ends."""
+    from paper_2205_13104_amd import binding as twa
+    touched = set()
+
+    def set_knob(knob, value):
+        touched.add(knob)
+        twa.set_launch_knob(knob, value)
+
+    yield set_knob
+    for knob in touched:
+        twa.set_launch_knob(knob, 0)

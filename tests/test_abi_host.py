@@ -114,7 +114,7 @@ def test_other_entry_points_argument_errors():
 def test_layerwise_entry_points_argument_errors():
     L = twa.lib()
     nb = C.c_size_t()
-    assert L.twa_layer_plan_bytes(161, C.byref(nb)) == twa.OK and nb.value == 162 * 16
+    assert L.twa_layer_plan_bytes(161, C.byref(nb)) == twa.OK and nb.value == 16 + 162 * 16      # header {magic, L, D} + three tables
     assert L.twa_layer_plan_bytes(0, C.byref(nb)) == twa.ERR_SHAPE
     assert L.twa_layer_plan_bytes(twa.MAX_LAYERS + 1, C.byref(nb)) == twa.ERR_SHAPE
     assert L.twa_layer_plan(None, 3, 1000, 0x9000, 1 << 20, None) == twa.ERR_NULL
@@ -225,3 +225,18 @@ def test_project_noalloc_argument_errors():
     assert call(_pm(n=64), k=8, ldg=1024) in (twa.ERR_NO_DEVICE, twa.ERR_HIP)      # at the limit: goes on to the device
     assert call(_pm(n=128), k=4, ldg=996) == twa.ERR_SHAPE           # inside the limit; ldg < D
     assert "fixed device array" in twa.strerror(twa.ERR_LIMIT)
+
+
+def test_launch_knobs_are_explicit_and_bounded():
+    """The library reads no environment variable; its launch geometry changes only through this call."""
+    L = twa.lib()
+    assert L.twa_set_launch_knob(twa.KNOB_PROJECT_GRID, 7) == twa.OK
+    assert L.twa_set_launch_knob(twa.KNOB_PROJECT_GRID, 0) == twa.OK
+    assert L.twa_set_launch_knob(twa.KNOB_EXPAND_GRID, 2048) == twa.OK
+    assert L.twa_set_launch_knob(twa.KNOB_EXPAND_GRID, 0) == twa.OK
+    assert L.twa_set_launch_knob(twa.KNOB_EXPAND_GRID, 2049) == twa.ERR_SHAPE
+    assert L.twa_set_launch_knob(twa.KNOB_BASIS_WGS_PER_CU, -1) == twa.ERR_SHAPE
+    assert L.twa_set_launch_knob(3, 1) == twa.ERR_DTYPE and L.twa_set_launch_knob(-1, 1) == twa.ERR_DTYPE
+    src = "".join(open(os.path.join(ROOT, "paper_2205_13104_amd", "csrc", f)).read()
+                  for f in os.listdir(os.path.join(ROOT, "paper_2205_13104_amd", "csrc")))
+    assert "getenv" not in src

@@ -265,3 +265,64 @@ def test_layer_argument_errors():
                                       None) == twa.ERR_ALIGN
     assert L.twa_layer_plan(plan.layer_off.data_ptr(), 2, D, plan.ptr, 8, None) == twa.ERR_WORKSPACE
     assert L.twa_layer_plan(None, 2, D, plan.ptr, 1 << 20, None) == twa.ERR_NULL
+
+
+def test_a_plan_of_another_layer_table_poisons_the_result_and_touches_nothing_else():
+    """A plan carries the L and D it was built for.  Handed to a call with another L or another D (the host cannot
+    see into device memory, the status is TWA_OK) every kernel refuses to read its tables: the coefficients come
+    back as NaN, the expansion marks w[0] and leaves everything else as it was, the quantiser's factors are NaN."""
+    import ctypes as C
+    D, n = 70_001, 5
+    P32 = random_basis_like(D, n, seed=3, ld=(D + 2047) // 2048 * 2048)
+    pm = store_as(P32, D, twa.I8)
+    g = synth.gradient(D, 1e-2, seed=3, device="cuda")
+    good = twa.LayerPlan([0, 100, 5000, D], D)                        # L = 3
+    other_L = twa.LayerPlan([0, 100, D], D)                           # L = 2, same D
+    other_D = twa.LayerPlan([0, 100, 5000, D - 2048], D - 2048)       # L = 3, another D
+    lib, st = twa.lib(), pm.c_struct()
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ws = twa.Workspace(twa.project_layers_workspace_bytes(n, 3))
+    S_good = twa.project_layers(pm, g, good)
+    assert torch.isfinite(S_good).all()
+    for bad in (other_L, other_D):
+        S = torch.zeros((3, n), device="cuda")
+        guard = torch.full((64,), 7.0, device="cuda")                 # right behind S in no particular place: canaries
+        assert lib.twa_project_layers(C.byref(st), C.c_void_p(g.data_ptr()), C.c_void_p(bad.ptr), 3,
+                                      C.c_void_p(S.data_ptr()), C.c_void_p(ws.ptr), ws.nbytes, stream) == twa.OK
+        w = torch.full((D,), 0.25, device="cuda")
+        gt = torch.full((D,), 0.5, device="cuda")
+        assert lib.twa_expand_update_layers(C.byref(st), C.c_void_p(S_good.data_ptr()), C.c_void_p(bad.ptr), 3,
+                                            C.c_void_p(w.data_ptr()), C.c_float(0.1), C.c_void_p(gt.data_ptr()),
+                                            stream) == twa.OK
+        beta = torch.zeros((3, n), device="cuda")
+        assert lib.twa_beta_step(C.byref(st), C.c_void_p(g.data_ptr()), C.c_void_p(bad.ptr), 3,
+                                 C.c_void_p(beta.data_ptr()), C.c_float(0.1), C.c_float(0.0), None, C.c_void_p(ws.ptr),
+                                 ws.nbytes, stream) == twa.OK
+        torch.cuda.synchronize()
+        assert torch.isnan(S).all() and torch.isnan(beta).all() and torch.all(guard == 7.0)
+        assert torch.isnan(w[0]) and torch.all(w[1:] == 0.25)
+        assert torch.isnan(gt[0]) and torch.all(gt[1:] == 0.5)
+    # the one-time producers say so as well
+    E = P32.clone()
+    out = twa.alloc_pmat(twa.U8MM, D, n)
+    ab = torch.zeros((3, 2), device="cuda")
+    st_mm = twa._Pmat(twa.U8MM, n, D, out.ld, out.data.data_ptr(), ab.data_ptr(), 8, 1.0)
+    nb = C.c_size_t()
+    assert lib.twa_quantize_minmax_workspace_bytes(3, C.byref(nb)) == twa.OK
+    wsq = twa.Workspace(nb.value + 8)
+    assert lib.twa_quantize_minmax(C.c_void_p(E.data_ptr()), D, n, E.shape[1], C.c_void_p(other_L.ptr), 3, 8, C.byref(st_mm),
+                                   C.c_void_p(wsq.ptr), wsq.nbytes, stream) == twa.OK
+    nbc = C.c_size_t()
+    assert lib.twa_centre_normalise_workspace_bytes(D, n, 3, C.byref(nbc)) == twa.OK
+    wsc = twa.Workspace(nbc.value)
+    wbar = torch.zeros(D, device="cuda")
+    norms = torch.zeros((3, n), device="cuda")
+    E2 = torch.full_like(P32, 3.0)
+    assert lib.twa_centre_normalise(C.c_void_p(P32.data_ptr()), D, n, P32.shape[1], C.c_void_p(other_L.ptr), 3,
+                                    C.c_void_p(wbar.data_ptr()), C.c_void_p(E2.data_ptr()), E2.shape[1],
+                                    C.c_void_p(norms.data_ptr()), C.c_void_p(wsc.ptr), wsc.nbytes, stream) == twa.OK
+    torch.cuda.synchronize()
+    assert torch.isnan(ab).all() and torch.isnan(norms).all()
+    assert torch.isnan(E2[0, 0]) and torch.all(E2.flatten()[1:] == 3.0)
+    # and the good plan still works afterwards
+    assert torch.equal(twa.project_layers(pm, g, good), S_good)

@@ -467,14 +467,14 @@ def test_expand_in_several_launches(dtype, D):
 
 
 @pytest.mark.parametrize("dtype", [twa.F32, twa.I8, twa.I4], ids=["f32", "i8", "i4"])
-def test_expand_launch_partition_on_a_small_grid(dtype, monkeypatch):
+def test_expand_launch_partition_on_a_small_grid(dtype, launch_knobs):
     """The cut of a vector into launches and of a launch into rounds, exercised with a grid of a few workgroups
     so that short vectors already need several launches: every tile count around the capacity of one launch
     (4 waves x 7 rounds x grid), remainders of every size, whole-model and layer-wise."""
     n = 3
     s = torch.tensor([0.7, -1.3, 0.2], device="cuda")
     for grid in (1, 3):
-        monkeypatch.setenv("TWA_EXPAND_GRID", str(grid))
+        launch_knobs(twa.KNOB_EXPAND_GRID, grid)
         cap = 4 * 7 * grid                                    # tiles of 2048 elements one launch holds
         for tiles in sorted({1, 2, 5, cap - 1, cap, cap + 1, cap + 4, 2 * cap - 3, 2 * cap, 2 * cap + 1, 3 * cap + 9}):
             D = tiles * 2048 - 5
@@ -504,12 +504,12 @@ def test_expand_launch_partition_on_a_small_grid(dtype, monkeypatch):
 
 
 @pytest.mark.parametrize("dtype", [twa.F32, twa.I8, twa.I4], ids=["f32", "i8", "i4"])
-def test_project_tile_division_on_a_small_grid(dtype, monkeypatch):
+def test_project_tile_division_on_a_small_grid(dtype, launch_knobs):
     """The division of the tiles over the workgroups of the projection (and the per-layer slots of its partial
     sums), exercised with a grid of a few workgroups: many tiles per workgroup, workgroups without tiles."""
     n = 5
     for grid in (1, 3, 7):
-        monkeypatch.setenv("TWA_PROJECT_GRID", str(grid))
+        launch_knobs(twa.KNOB_PROJECT_GRID, grid)
         for tiles in (1, 2, grid, grid + 1, 5 * grid - 1, 11 * grid + 2):
             D = tiles * 2048 - 3
             print("division", dtype, "grid", grid, "tiles", tiles, flush=True)
