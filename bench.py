@@ -121,38 +121,59 @@ def main():
 
     # ---- inputs: checkpoints -> orthonormal basis (in place) -> stored P ------------------------
     t0 = time.time()
-    W = synth.checkpoints(wl, seed=args.seed, device=dev, D=D)
-    w = W[:, :D].mean(dim=0).contiguous()                  # the plain average: starting point of TWA
-    torch.cuda.synchronize()
-    t1 = time.time()
     plan = None
-    if layerwise:
-        sizes = synth.workload_layers(wl.name) if D == wl.D else synth.layer_offsets(synth.random_layer_sizes(D, 12, 11))
-        plan = twa.LayerPlan(sizes, D)
-        P32, w, _ = twa.centre_normalise(W, D, plan, out=W, want_norms=False)     # w = wbar: Alg. 1 starts at the mean
-        wbar = w.clone()
+    from_panels = wl.name == "large" and not layerwise and dtype in (twa.I8, twa.I4, twa.BF16) and D % 4 == 0
+    if from_panels:
+        # this configuration's checkpoints (179 GB in fp32) and its fp32 basis are never held: rows are produced in
+        # panels of 2^24 into one staging buffer, three sweeps, the second pass fused with the quantiser
+        from paper_2205_13104_amd.panels import stored_basis_from_panels
+        w = torch.empty(D, dtype=torch.float32, device=dev)
+
+        def make_panel(r0, rows, stage):
+            synth.trajectory_panel(rows, n, wl.decay, wl.drift, args.seed, r0, stage)
+
+        def mean_of(r0, rows, stage):                       # the plain average: starting point of TWA
+            w[r0:r0 + rows] = stage[:, :rows].mean(dim=0)
+
+        t1 = time.time()
+        outs, _, _, stage, _ = stored_basis_from_panels(make_panel, D, n, 1 << 24, [dtype], device=dev, on_first_sweep=mean_of)
+        pm = outs[dtype]
+        torch.cuda.synchronize()
+        t2 = t3 = time.time()
+        del stage, outs
+        torch.cuda.empty_cache()
+        log(f"[bench] {wl.name}: D={D} n={n} storage={args.storage} mode={args.mode}; basis and stored matrix from "
+            f"panels of 2^24 rows in {t2 - t1:.2f}s (generation included); peak device memory "
+            f"{torch.cuda.max_memory_allocated() / 2**30:.1f} GiB")
     else:
-        if wl.name == "large":
-            # this configuration's basis is built from 16 M-row panels (the calls a caller uses whose checkpoints
-            # do not sit in memory at once; here they do, so the panels are views)
-            P32, _ = twa.build_basis_panels(W, D, 1 << 24, out=W)
+        W = synth.checkpoints(wl, seed=args.seed, device=dev, D=D)
+        w = W[:, :D].mean(dim=0).contiguous()                  # the plain average: starting point of TWA
+        torch.cuda.synchronize()
+        t1 = time.time()
+        if layerwise:
+            sizes = synth.workload_layers(wl.name) if D == wl.D else synth.layer_offsets(synth.random_layer_sizes(D, 12, 11))
+            plan = twa.LayerPlan(sizes, D)
+            P32, w, _ = twa.centre_normalise(W, D, plan, out=W, want_norms=False)     # w = wbar: Alg. 1 starts at the mean
+            wbar = w.clone()
+        elif wl.name == "large":
+            P32, _ = twa.build_basis_panels(W, D, 1 << 24, out=W)      # (fp32 storage: the panels are views of W)
         else:
             P32, _ = twa.build_basis(W, D, out=W, want_R=False)
-    torch.cuda.synchronize()
-    t2 = time.time()
-    if dtype == twa.F32:
-        pm = twa.wrap_f32(P32, D)
-    elif dtype in twa.MINMAX_TYPES:
-        pm = twa.quantize_minmax(P32, D, plan, bits=twa.BITS_OF[dtype])
-    else:
-        pm = twa.quantize(P32, D, dtype)
-    torch.cuda.synchronize()
-    t3 = time.time()
-    if dtype != twa.F32:
-        del W, P32
-        torch.cuda.empty_cache()
-    log(f"[bench] {wl.name}: D={D} n={n} storage={args.storage} mode={args.mode}; generate {t1 - t0:.2f}s, "
-        f"build_basis {t2 - t1:.3f}s, quantize {t3 - t2:.3f}s")
+        torch.cuda.synchronize()
+        t2 = time.time()
+        if dtype == twa.F32:
+            pm = twa.wrap_f32(P32, D)
+        elif dtype in twa.MINMAX_TYPES:
+            pm = twa.quantize_minmax(P32, D, plan, bits=twa.BITS_OF[dtype])
+        else:
+            pm = twa.quantize(P32, D, dtype)
+        torch.cuda.synchronize()
+        t3 = time.time()
+        if dtype != twa.F32:
+            del W, P32
+            torch.cuda.empty_cache()
+        log(f"[bench] {wl.name}: D={D} n={n} storage={args.storage} mode={args.mode}; generate {t1 - t0:.2f}s, "
+            f"build_basis {t2 - t1:.3f}s, quantize {t3 - t2:.3f}s")
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         b = torch.empty_like(a)

@@ -205,6 +205,37 @@ int twa_apply_rinv(const float* W, int64_t rows, int32_t n, int64_t ldw, const f
                    void* stream);
 
 /*
+ * twa_apply_rinv with the result stored straight in the form `out` describes -- the second pass of the construction
+ * fused with twa_quantize (Sec. 4.1 and Sec. 4.6: the fp32 projection matrix is the memory burden; this way it is
+ * never written, the checkpoints' rows may be produced panel by panel into a small staging buffer and only the
+ * low-bit matrix is kept).  Values and codes are those of twa_apply_rinv followed by twa_quantize, bit for bit.
+ *   W    [in]  panel of the matrix after the FIRST pass: rows [row0, row0 + rows) of all n vectors (pointer to the
+ *              panel's first row, stride ldw).
+ *   rinv [in]  R^-1 of the second pass, from twa_gram_factor.
+ *   out  [in]  descriptor of the WHOLE stored matrix (D, n, ld, data, scales, block, gscale), dtype TWA_F32,
+ *              TWA_BF16, TWA_I8 or TWA_I4; block <= 128.  TWA_I4 needs out->gscale > 0 (a power of two): the
+ *              largest scale of the whole matrix cannot be known from one panel.  Any value that keeps the binary16
+ *              scales normal will do; twa_gscale_for_absmax(largest |entry| after the first pass, found with
+ *              twa_absmax_accumulate) is the value twa_quantize itself would choose up to the 1e-4 by which the
+ *              second pass moves the entries.
+ *   row0       first row of the panel in the whole matrix, a multiple of TWA_SCALE_SPAN; rows must be one too except
+ *              in the last panel (row0 + rows == out->D), whose call also writes the padding [D, ld): zeros, code 0,
+ *              scale 0.
+ * The stored matrix must not overlap W (except TWA_F32 exactly in place).  Asynchronous on `stream`.
+ */
+int twa_apply_rinv_quantize(const float* W, int64_t rows, int32_t n, int64_t ldw, const float* rinv, const twa_pmat* out,
+                            int64_t row0, void* stream);
+
+/* amax[0] = max(|X_ij|) over a panel (combined with what amax[0] holds when accumulate != 0; the value is a
+ * non-negative binary32 number).  amax: device, 4 bytes.  Asynchronous on `stream`. */
+int twa_absmax_accumulate(const float* X, int64_t rows, int32_t n, int64_t ld, float* amax, int32_t accumulate,
+                          void* stream);
+
+/* The power of two twa_quantize chooses for the binary16 scales of a TWA_I4 matrix whose largest |entry| is amax:
+ * 2^(floor(log2(amax / 7)) - 14), 1 for amax == 0.  Host arithmetic. */
+float twa_gscale_for_absmax(float amax);
+
+/*
  * Store an fp32 matrix in the form described by `out`  (Sec. 4.6: P as B-bit integers plus
  * scaling factors).  `out->dtype, n, D, ld, data, scales, block` are preset by the caller;
  * buffers sized per twa_pmat_bytes.  Exact recipe (each step ONE correctly rounded binary32

@@ -2,7 +2,8 @@
 
 The work is done by hand-written HIP kernels for gfx950 behind a C-ABI shared library
 (``include/twa.h``); :mod:`.binding` marshals torch device pointers into it and
-:mod:`.synth` draws the seeded synthetic inputs.  Importing the package loads nothing;
+:mod:`.synth` draws the seeded synthetic inputs, :mod:`.panels` sequences the calls of a
+basis construction whose checkpoints arrive in panels of rows.  Importing the package loads nothing;
 the library is loaded on first use of a binding call and a missing library is an error.
 """
-__all__ = ["binding", "synth", "build"]
+__all__ = ["binding", "synth", "build", "panels"]

@@ -81,6 +81,12 @@ def lib():
         L.twa_expand_update.argtypes = [C.POINTER(_Pmat), vp, vp, f32, vp, vp]
         L.twa_project_noalloc.argtypes = [C.POINTER(_Pmat), vp, i32, i64, vp, vp]
         L.twa_project_noalloc.restype = C.c_int
+        L.twa_apply_rinv_quantize.argtypes = [vp, i64, i32, i64, vp, C.POINTER(_Pmat), i64, vp]
+        L.twa_apply_rinv_quantize.restype = C.c_int
+        L.twa_absmax_accumulate.argtypes = [vp, i64, i32, i64, vp, i32, vp]
+        L.twa_absmax_accumulate.restype = C.c_int
+        L.twa_gscale_for_absmax.argtypes = [f32]
+        L.twa_gscale_for_absmax.restype = C.c_float
         L.twa_set_launch_knob.argtypes = [i32, i32]
         L.twa_set_launch_knob.restype = C.c_int
         L.twa_project_layers_workspace_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
@@ -473,6 +479,56 @@ def build_basis_panels(W: torch.Tensor, D: int, panel_rows: int, out: Optional[t
                                         _stream()), "twa_apply_rinv")
         src, lds = P, ldp
     return P, R
+
+
+class BasisState:
+    """The device buffers of a panel-wise CholeskyQR pass (twa_basis_state_bytes): Gram matrix, R^-1, workspace."""
+
+    def __init__(self, n: int, device="cuda"):
+        gb, rb, wb = C.c_size_t(), C.c_size_t(), C.c_size_t()
+        _check(lib().twa_basis_state_bytes(n, C.byref(gb), C.byref(rb), C.byref(wb)), "twa_basis_state_bytes")
+        self.n = n
+        self.gram, self.rinv, self.ws = Workspace(gb.value, device), Workspace(rb.value, device), Workspace(wb.value, device)
+
+
+def gram_accumulate(panel: torch.Tensor, rows: int, st: BasisState, first: bool, orthonormal_input: bool = False) -> None:
+    """twa_gram_accumulate on a panel ((n, ld) float32 device tensor or view whose row j starts ld elements after row j-1)."""
+    n, ld = panel.shape[0], panel.stride(0)
+    flags = (0 if first else GRAM_ADD) | (GRAM_ORTHONORMAL_INPUT if orthonormal_input else 0)
+    _check(lib().twa_gram_accumulate(panel.data_ptr(), rows, n, ld, st.gram.ptr, flags, st.ws.ptr, st.ws.nbytes, _stream()),
+           "twa_gram_accumulate")
+
+
+def gram_factor(st: BasisState, R: Optional[torch.Tensor] = None, compose: bool = False) -> None:
+    """twa_gram_factor: R^-1 of the accumulated Gram matrix to the device (synchronises); R (n, n) float64 CPU optional."""
+    rc = lib().twa_gram_factor(st.gram.ptr, st.n, st.rinv.ptr, _ptr(R), 1 if compose else 0, _stream())
+    if rc == ERR_RANK and R is not None:
+        raise TwaError(rc, "twa_gram_factor", f"(checkpoint {int(R[0, 0].item())})")
+    _check(rc, "twa_gram_factor")
+
+
+def apply_rinv(panel: torch.Tensor, rows: int, st: BasisState, out: Optional[torch.Tensor] = None) -> None:
+    """twa_apply_rinv on a panel (in place by default)."""
+    dst = panel if out is None else out
+    _check(lib().twa_apply_rinv(panel.data_ptr(), rows, panel.shape[0], panel.stride(0), st.rinv.ptr, dst.data_ptr(),
+                                dst.stride(0), _stream()), "twa_apply_rinv")
+
+
+def apply_rinv_quantize(panel: torch.Tensor, rows: int, st: BasisState, out: Pmat, row0: int) -> None:
+    """twa_apply_rinv_quantize: rows [row0, row0 + rows) of the stored matrix `out` from a panel of the first pass."""
+    c = out.c_struct()
+    _check(lib().twa_apply_rinv_quantize(panel.data_ptr(), rows, panel.shape[0], panel.stride(0), st.rinv.ptr, C.byref(c),
+                                         row0, _stream()), "twa_apply_rinv_quantize")
+
+
+def absmax_accumulate(panel: torch.Tensor, rows: int, amax: torch.Tensor, first: bool) -> None:
+    """twa_absmax_accumulate: amax (1 float32 on the device) = largest |entry| seen so far."""
+    _check(lib().twa_absmax_accumulate(panel.data_ptr(), rows, panel.shape[0], panel.stride(0), amax.data_ptr(),
+                                       0 if first else 1, _stream()), "twa_absmax_accumulate")
+
+
+def gscale_for_absmax(amax: float) -> float:
+    return float(lib().twa_gscale_for_absmax(C.c_float(amax)))
 
 
 def probe_read(buf: torch.Tensor, sink: torch.Tensor) -> None:

@@ -169,6 +169,17 @@ static void invert_upper(const std::vector<double>& R, int n, std::vector<double
   }
 }
 
+
+// One power of two for all binary16 scales of a matrix whose largest entry is amax: the largest scale, amax / 7,
+// lands in [2^14, 2^15).
+float gscale_of(float amax) {
+  const float smax = amax / 7.0f;
+  if (!(smax > 0.0f) || !isfinite(smax)) return 1.0f;
+  int ex = 0;
+  (void)frexpf(smax, &ex);                    // smax = m * 2^ex, m in [0.5, 1)
+  return ldexpf(1.0f, ex - 1 - 14);
+}
+
 }  // namespace twa
 
 using namespace twa;
@@ -500,21 +511,14 @@ int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* ou
       // largest block scale = (largest |p|) / 7: find it, then pick the power of two that puts
       // the largest binary16 scale in [2^14, 2^15).  The first word of the code buffer is scratch.
       float* tmp = static_cast<float*>(out->data);
-      rc = launch_absmax(P, D, n, ldp, tmp, st);
+      rc = launch_absmax(P, D, n, ldp, tmp, false, st);
       if (rc != TWA_OK) return rc;
       float amax = 0.0f;
       rc = hip_check(hipMemcpyAsync(&amax, tmp, sizeof(float), hipMemcpyDeviceToHost, st));
       if (rc != TWA_OK) return rc;
       rc = hip_check(hipStreamSynchronize(st));
       if (rc != TWA_OK) return rc;
-      const float smax = amax / 7.0f;
-      if (smax > 0.0f && isfinite(smax)) {
-        int ex = 0;
-        (void)frexpf(smax, &ex);                    // smax = m * 2^ex, m in [0.5, 1)
-        out->gscale = ldexpf(1.0f, ex - 1 - 14);
-      } else {
-        out->gscale = 1.0f;
-      }
+      out->gscale = gscale_of(amax);
     } else {
       int ex = 0;
       if (!(out->gscale > 0.0f) || !isfinite(out->gscale) || frexpf(out->gscale, &ex) != 0.5f) return TWA_ERR_SHAPE;
@@ -692,6 +696,54 @@ int twa_apply_rinv(const float* W, int64_t rows, int32_t n, int64_t ldw, const f
   const int grid = basis_grid(rows);
   if (grid <= 0) return TWA_ERR_NO_DEVICE;
   return launch_apply_rinv(W, ldw, P, ldp, rows, n, rinv, grid, false, static_cast<hipStream_t>(stream));
+}
+
+float twa_gscale_for_absmax(float amax) { return gscale_of(amax); }
+
+int twa_absmax_accumulate(const float* X, int64_t rows, int32_t n, int64_t ld, float* amax, int32_t accumulate,
+                          void* stream) {
+  int rc = check_panel(X, rows, n, ld);
+  if (rc != TWA_OK) return rc;
+  if (!amax) return TWA_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(amax) & 3u) return TWA_ERR_ALIGN;
+  if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_absmax(X, rows, n, ld, amax, accumulate != 0, static_cast<hipStream_t>(stream));
+}
+
+int twa_apply_rinv_quantize(const float* W, int64_t rows, int32_t n, int64_t ldw, const float* rinv, const twa_pmat* out,
+                            int64_t row0, void* stream) {
+  int rc = check_panel(W, rows, n, ldw);
+  if (rc != TWA_OK) return rc;
+  if (!rinv || !out || !out->data) return TWA_ERR_NULL;
+  const int dt = out->dtype;
+  if (dt != TWA_F32 && dt != TWA_BF16 && dt != TWA_I8 && dt != TWA_I4) return TWA_ERR_DTYPE;
+  if (out->n != n) return TWA_ERR_SHAPE;
+  rc = check_dims(out->D, n, out->ld, dt);
+  if (rc != TWA_OK) return rc;
+  if (row0 < 0 || row0 + rows > out->D) return TWA_ERR_SHAPE;
+  const bool last = row0 + rows == out->D;
+  // panels meet on the grid of the scale spans, so that no quantisation block straddles two panels
+  if (row0 % TWA_SCALE_SPAN != 0 || (!last && rows % TWA_SCALE_SPAN != 0)) return TWA_ERR_ALIGN;
+  if (!aligned16(rinv) || !aligned16(out->data)) return TWA_ERR_ALIGN;
+  if (scaled(dt)) {
+    if (!out->scales) return TWA_ERR_NULL;
+    if (!aligned16(out->scales)) return TWA_ERR_ALIGN;
+    if (!pow2(out->block) || out->block < 32 || out->block > 128) return TWA_ERR_SHAPE;    // a block spans two tiles at most
+    if (dt == TWA_I4) {
+      int ex = 0;
+      if (!(out->gscale > 0.0f) || !isfinite(out->gscale) || frexpf(out->gscale, &ex) != 0.5f) return TWA_ERR_SHAPE;
+    }
+  }
+  {  // the stored matrix must not overlap the panel it is made from
+    const char* a = reinterpret_cast<const char*>(W);
+    const char* b = reinterpret_cast<const char*>(out->data);
+    const size_t wa = ((size_t)(n - 1) * ldw + rows) * 4, ob = (size_t)n * out->ld * bits_of(dt) / 8;
+    const bool same_f32 = dt == TWA_F32 && static_cast<const void*>(W) == static_cast<const void*>(static_cast<const float*>(out->data) + row0) && ldw == out->ld;
+    if (!same_f32 && a < b + ob && b < a + wa) return TWA_ERR_SHAPE;
+  }
+  const int grid = basis_grid(rows);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_apply_rinv_store(W, ldw, rows, n, rinv, *out, row0, last, grid, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -281,13 +281,131 @@ __device__ __forceinline__ void apply_tile_products(const float* tile, const flo
   }
 }
 
-template <int NB>
-__global__ __launch_bounds__(256, 2) void apply_rinv_kernel(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D,
-                                                            int n, const float* __restrict__ rinv) {
+// What apply_rinv_kernel does with a finished tile of Q.  The sums of a tile leave the matrix instruction as
+// 16-lane runs of 64 bytes per column; written to memory like that the kernel reached 4.0 TB/s (the plain copy
+// of this device: 5.3).  They are therefore first written to LDS as out[col][row] (the staged input tile is
+// dead by then and gives its place), and leave in the shape the destination wants:
+//   EMIT_F32   Q as fp32: 16 lanes store the 64 rows of a column as one run of 256 bytes
+//   EMIT_BF16  the same rounded to bfloat16 (nearest even)
+//   EMIT_I8 / EMIT_I4  the block-absmax integer codes of twa_quantize, bit for bit the recipe of that call (every
+//              step one correctly rounded binary32 operation): Q in fp32 is then never written at all.  A
+//              quantisation block of 128 rows spans two tiles: the first one waits in a second LDS buffer.
+enum { EMIT_F32 = 0, EMIT_BF16 = 1, EMIT_I8 = 2, EMIT_I4 = 3 };
+constexpr int kOutStride = kTileRows + 4;     // floats; 4 columns apart = 16 banks apart: the 16-lane runs of two
+                                              // column quads of a matrix-instruction result land on disjoint banks
+
+struct EmitTarget {
+  float* q;             // EMIT_F32: Q, stride ldq                 (may be W itself)
+  uint8_t* codes;       // other modes: values / codes of the whole matrix, vector stride `ld` elements
+  uint8_t* scales;      // EMIT_I8 / EMIT_I4: span-interleaved scales of the whole matrix
+  int64_t ld;           // elements between vectors in q / codes
+  int64_t row0;         // first row of this panel in the whole matrix (a multiple of kScaleSpan for the integer modes)
+  int64_t rows_out;     // rows to produce, >= the panel's rows: those behind the panel's end are padding (zeros)
+  int block_shift;      // log2(quantisation block)
+  float gscale, inv_gscale;
+};
+
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+  const uint32_t u = as_u32(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  const uint32_t keep = u >> 16, rem = u & 0xffffu;
+  return keep + ((rem > 0x8000u || (rem == 0x8000u && (keep & 1u))) ? 1u : 0u);
+}
+
+// `nt` tiles of kTileRows rows (tile 0 in buf0, tile 1 in buf1, laid out [col][row] with stride kOutStride) starting at panel
+// row i0 leave for memory.  EL rows per thread: 4, or 8 for the 4-bit codes (one dword of codes either way).
+template <int EMIT>
+__device__ __forceinline__ void emit_rows(const EmitTarget& T, int n, int NP, int64_t i0, int nt, const float* buf0,
+                                          const float* buf1) {
+  constexpr int EL = EMIT == EMIT_I4 ? 8 : 4;
+  constexpr int PER_TILE = kTileRows / EL;                       // threads per column and tile
+  const int per_col = PER_TILE * nt;
+  const int total = NP * per_col;
+  for (int idx = threadIdx.x; idx < (total + 255) / 256 * 256; idx += 256) {
+    const int col = idx / per_col;
+    const int rr = idx - col * per_col;                          // run of EL rows inside the group of tiles
+    const int t = rr / PER_TILE;
+    const int r = rr - t * PER_TILE;
+    const bool inside = idx < total && col < n;
+    float x[EL];
+#pragma unroll
+    for (int e = 0; e < EL; e += 4) {
+      const float4 v = inside ? *reinterpret_cast<const float4*>((t ? buf1 : buf0) + col * kOutStride + EL * r + e)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+      x[e] = v.x; x[e + 1] = v.y; x[e + 2] = v.z; x[e + 3] = v.w;
+    }
+    const int64_t row = i0 + (int64_t)t * kTileRows + EL * r;    // first of this thread's rows, inside the panel
+    const int64_t grow = T.row0 + row;                           // ... and in the whole matrix
+    const bool live = inside && row < T.rows_out;
+    if constexpr (EMIT == EMIT_F32) {
+      if (live) {
+        float* dst = T.q + (int64_t)col * T.ld + row;
+        if (row + 4 <= T.rows_out) {
+          *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) if (row + e < T.rows_out) dst[e] = x[e];
+        }
+      }
+    } else if constexpr (EMIT == EMIT_BF16) {
+      if (live) {                                                // rows_out is a multiple of 4 here (ld is)
+        const uint2 v = {bf16_rne(x[0]) | (bf16_rne(x[1]) << 16), bf16_rne(x[2]) | (bf16_rne(x[3]) << 16)};
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(T.codes) + (int64_t)col * T.ld + grow) = v;
+      }
+    } else {
+      // the recipe of twa_quantize; the block's absmax over the block / EL consecutive threads that hold it
+      constexpr float QMAX = EMIT == EMIT_I8 ? 127.0f : 7.0f;
+      const int lanes_per_block = (1 << T.block_shift) / EL;
+      float amax = 0.0f;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) amax = fmaxf(amax, fabsf(x[e]));
+#pragma unroll
+      for (int m = 1; m < 32; m <<= 1)
+        if (m < lanes_per_block) amax = fmaxf(amax, __shfl_xor(amax, m, kWave));
+      const float scale = amax / QMAX;
+      float eff = scale;
+      uint16_t hbits = 0;
+      if constexpr (EMIT == EMIT_I4) {
+        const _Float16 h = (_Float16)(scale * T.inv_gscale);
+        hbits = __builtin_bit_cast(uint16_t, h);
+        eff = (float)h * T.gscale;
+      }
+      const bool nonzero = eff != 0.0f;
+      const float inv = nonzero ? 1.0f / eff : 0.0f;
+      uint32_t word = 0;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) {
+        float c = __builtin_rintf(x[e] * inv);
+        c = fminf(fmaxf(c, -QMAX), QMAX);
+        const int q = nonzero ? (int)c : 0;
+        if constexpr (EMIT == EMIT_I8) word |= ((uint32_t)q & 0xffu) << (8 * e);
+        else word |= ((uint32_t)(q + 8) & 0xfu) << (4 * e);
+      }
+      if (live) {
+        constexpr int BITS = EMIT == EMIT_I8 ? 8 : 4;
+        *reinterpret_cast<uint32_t*>(T.codes + ((((int64_t)col * T.ld + grow) * BITS) >> 3)) = word;
+        if ((rr & (lanes_per_block - 1)) == 0) {
+          const int gshift = kScaleSpanShift - T.block_shift;
+          const int64_t b = grow >> T.block_shift;
+          const int64_t at = ((((b >> gshift) * n + col)) << gshift) + (b & (((int64_t)1 << gshift) - 1));
+          if constexpr (EMIT == EMIT_I8) reinterpret_cast<float*>(T.scales)[at] = scale;
+          else reinterpret_cast<uint16_t*>(T.scales)[at] = hbits;
+        }
+      }
+    }
+  }
+}
+
+// GROUP = tiles that are emitted together: 2 where a quantisation block of 128 rows spans two tiles, else 1.
+template <int NB, int EMIT, int GROUP>
+__global__ __launch_bounds__(256, 2) void apply_rinv_kernel(const float* W, int64_t ldw, int64_t D, int n,
+                                                            const float* __restrict__ rinv, EmitTarget T) {
   constexpr int NP = 16 * NB;
   constexpr int KK = 4 * NB;                    // k-steps of the widest block
   constexpr int RG = kApplyRowGroups;           // row groups per tile
+  static_assert(kOutStride <= kApplyStride, "a finished tile takes the place of the staged one");
   __shared__ float tile[NP * kApplyStride];
+  __shared__ float first[GROUP == 2 ? NP * kOutStride : 1];      // the first tile of a pair waits here
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 15, kq = lane >> 4;
@@ -303,13 +421,14 @@ __global__ __launch_bounds__(256, 2) void apply_rinv_kernel(const float* W, int6
     }
   }
 
-  const int64_t nchunks = (D + kTileRows - 1) / kTileRows;
-  int64_t c0, c1;
-  split_range(nchunks, (int)gridDim.x, (int)blockIdx.x, c0, c1);
+  // groups of GROUP tiles are dealt to the workgroups; rows behind the panel's end (up to rows_out) are zeros
+  const int64_t ngroups = (T.rows_out + GROUP * kTileRows - 1) / (GROUP * kTileRows);
+  int64_t g0, g1;
+  split_range(ngroups, (int)gridDim.x, (int)blockIdx.x, g0, g1);
+  const int64_t c0 = g0 * GROUP, c1 = g1 * GROUP;
   float4 pre[kTileQuads];
   if (c0 < c1) fetch_tile(W, ldw, D, n, NP, c0 * kTileRows, pre);
   for (int64_t c = c0; c < c1; ++c) {
-    const int64_t i0 = c * kTileRows;
     store_tile<kApplyStride>(NP, pre, tile);
     __syncthreads();
     // the next tile's rows are other rows than this tile's, which are the only ones written below:
@@ -326,22 +445,24 @@ __global__ __launch_bounds__(256, 2) void apply_rinv_kernel(const float* W, int6
       case 2: apply_tile_products<NB, 2>(tile, afrag, m, kq, acc); break;
       default: apply_tile_products<NB, 3>(tile, afrag, m, kq, acc); break;
     }
-    __syncthreads();      // every wave has read the tile in LDS; the next one may replace it
+    __syncthreads();      // every wave has read the staged tile: the finished one may take its place
+    const bool waits = GROUP == 2 && ((c - c0) & 1) == 0;          // first tile of a pair
+    float* out = waits ? first : tile;
 #pragma unroll
     for (int jbi = 0; jbi < 2; ++jbi) {
       const int jb = jbs[jbi];
       if (jb >= 0) {
 #pragma unroll
-        for (int rg = 0; rg < RG; ++rg) {
-          const int64_t row = i0 + 16 * rg + m;
+        for (int rg = 0; rg < RG; ++rg)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int col = 16 * jb + mfma_row_f32(lane, r);
-            if (col < n && row < D) Q[(int64_t)col * ldq + row] = acc[jbi][rg][r];
-          }
-        }
+          for (int r = 0; r < 4; ++r)
+            out[(16 * jb + mfma_row_f32(lane, r)) * kOutStride + 16 * rg + m] = acc[jbi][rg][r];
       }
     }
+    if (waits) continue;                                           // (the next store_tile only touches `tile`)
+    __syncthreads();
+    emit_rows<EMIT>(T, n, NP, (c + 1 - GROUP) * kTileRows, GROUP, GROUP == 2 ? first : tile, tile);
+    __syncthreads();      // the staged tile's place is free again
   }
 }
 
@@ -373,17 +494,53 @@ int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, 
   return hip_check(hipGetLastError());
 }
 
-int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
-                      int grid, bool zero_padding, hipStream_t st) {
+template <int EMIT, int GROUP>
+static int launch_apply_emit(const float* W, int64_t ldw, int64_t rows, int n, const float* rinv_dev, const EmitTarget& T,
+                             int grid, hipStream_t st) {
   const int NP = (n + 15) / 16 * 16;
   switch (NP / 16) {
-#define TWA_APPLY(NB_) case NB_: hipLaunchKernelGGL(apply_rinv_kernel<NB_>, dim3(grid), dim3(256), 0, st, W, ldw, Q, ldq, D, n, rinv_dev); break
+#define TWA_APPLY(NB_) case NB_: hipLaunchKernelGGL((apply_rinv_kernel<NB_, EMIT, GROUP>), dim3(grid), dim3(256), 0, st, W, ldw, rows, n, rinv_dev, T); break
     TWA_APPLY(1); TWA_APPLY(2); TWA_APPLY(3); TWA_APPLY(4); TWA_APPLY(5); TWA_APPLY(6); TWA_APPLY(7); TWA_APPLY(8);
 #undef TWA_APPLY
     default: return TWA_ERR_SHAPE;
   }
+  return hip_check(hipGetLastError());
+}
+
+int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
+                      int grid, bool zero_padding, hipStream_t st) {
+  const EmitTarget T{Q, nullptr, nullptr, ldq, 0, D, 0, 1.0f, 1.0f};
+  int rc = launch_apply_emit<EMIT_F32, 1>(W, ldw, D, n, rinv_dev, T, grid, st);
+  if (rc != TWA_OK) return rc;
   if (zero_padding && ldq > D) hipLaunchKernelGGL(zero_padding_kernel, dim3(1, n), dim3(256), 0, st, Q, D, ldq);
   return hip_check(hipGetLastError());
+}
+
+// Q = W R^-1 stored straight in the form `out` describes (rows [row0, row0 + rows) of the whole matrix; with
+// `last` the padding behind them, up to out.ld, is produced too: zeros, code 0, scale 0).
+int launch_apply_rinv_store(const float* W, int64_t ldw, int64_t rows, int n, const float* rinv_dev, const twa_pmat& out,
+                            int64_t row0, bool last, int grid, hipStream_t st) {
+  int shift = 0;
+  while ((1 << shift) < out.block) ++shift;
+  const int64_t rows_out = last ? out.ld - row0 : rows;
+  const float gs = out.dtype == TWA_I4 ? out.gscale : 1.0f;
+  const EmitTarget T{static_cast<float*>(out.data), static_cast<uint8_t*>(out.data), static_cast<uint8_t*>(out.scales),
+                     out.ld, row0, rows_out, shift, gs, 1.0f / gs};
+  switch (out.dtype) {
+    case TWA_F32: {
+      EmitTarget F = T;
+      F.q = static_cast<float*>(out.data) + row0;              // (EMIT_F32 addresses rows inside the panel)
+      return launch_apply_emit<EMIT_F32, 1>(W, ldw, rows, n, rinv_dev, F, grid, st);
+    }
+    case TWA_BF16: return launch_apply_emit<EMIT_BF16, 1>(W, ldw, rows, n, rinv_dev, T, grid, st);
+    case TWA_I8:
+      return out.block == 128 ? launch_apply_emit<EMIT_I8, 2>(W, ldw, rows, n, rinv_dev, T, grid, st)
+                              : launch_apply_emit<EMIT_I8, 1>(W, ldw, rows, n, rinv_dev, T, grid, st);
+    case TWA_I4:
+      return out.block == 128 ? launch_apply_emit<EMIT_I4, 2>(W, ldw, rows, n, rinv_dev, T, grid, st)
+                              : launch_apply_emit<EMIT_I4, 1>(W, ldw, rows, n, rinv_dev, T, grid, st);
+    default: return TWA_ERR_DTYPE;
+  }
 }
 
 }  // namespace twa

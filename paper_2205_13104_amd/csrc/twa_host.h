@@ -55,11 +55,14 @@ int launch_beta_update(float* beta, const float* s, int64_t count, float lr, flo
 int launch_beta_optim(int kind, float* beta, const float* s, float* m, float* v, int64_t count, float lr, float lambda,
                       float mu, float beta2, float eps, float bias1, float bias2, hipStream_t st);
 int launch_quantize(const float* P, int64_t D, int n, int64_t ldp, const twa_pmat& out, hipStream_t st);
-int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st);
+int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, bool accumulate, hipStream_t st);
 int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, int grid, double* gram,
                 bool accumulate, bool orthonormal_input, hipStream_t st);
 int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
                       int grid, bool zero_padding, hipStream_t st);
+
+int launch_apply_rinv_store(const float* W, int64_t ldw, int64_t rows, int n, const float* rinv_dev, const twa_pmat& out,
+                            int64_t row0, bool last, int grid, hipStream_t st);
 
 int launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st);
 

@@ -157,8 +157,9 @@ static int grid_x_for(int64_t work_items, int n) {
   return (int)gx;
 }
 
-int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, hipStream_t st) {
-  hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, st, reinterpret_cast<unsigned int*>(out_dev));
+int launch_absmax(const float* P, int64_t D, int n, int64_t ldp, float* out_dev, bool accumulate, hipStream_t st) {
+  if (!accumulate)
+    hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, st, reinterpret_cast<unsigned int*>(out_dev));
   hipLaunchKernelGGL(absmax_kernel, dim3(grid_x_for(D, n), n), dim3(256), 0, st, P, D, ldp,
                      reinterpret_cast<unsigned int*>(out_dev));
   return hip_check(hipGetLastError());

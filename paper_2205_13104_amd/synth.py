@@ -80,6 +80,25 @@ def trajectory(D: int, n: int, decay: float, drift: float, seed: int = 0, device
     return W
 
 
+def trajectory_panel(rows: int, n: int, decay: float, drift: float, seed: int, r0: int, out: torch.Tensor,
+                     w0_std: float = 0.05, step_std: float = 1e-3) -> torch.Tensor:
+    """Rows [r0, r0 + rows) of all n checkpoints of a synthetic trajectory, written to out[:, :rows] (fp32, on out's
+    device): the recipe of `trajectory`, with every panel drawn from a generator of its own seeded by (seed, r0), so that
+    a panel can be produced again at any time without the rest of the matrix -- what a caller does whose checkpoints
+    are too large to sit in memory at once (D = 350 M, n = 128 is 179 GB in fp32)."""
+    assert out.dtype == torch.float32 and out.shape[0] == n and out.shape[1] >= rows
+    gen = _gen(seed * 2_000_003 + 104_729 * (r0 // 2048 + 1), out.device)
+    dev = out.device
+    out[0, :rows] = torch.randn(rows, generator=gen, device=dev, dtype=torch.float32) * w0_std
+    c = torch.randn(rows, generator=gen, device=dev, dtype=torch.float32) * step_std
+    for i in range(1, n):
+        noise = torch.randn(rows, generator=gen, device=dev, dtype=torch.float32)
+        noise *= step_std * (decay ** i)
+        noise.add_(c, alpha=drift)
+        torch.add(out[i - 1, :rows], noise, out=out[i, :rows])
+    return out
+
+
 def finetune_offsets(D: int, n: int, seed: int = 0, device="cpu", ld: Optional[int] = None,
                      base_std: float = 0.02, offset_std: float = 2e-3,
                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
