@@ -176,6 +176,20 @@ int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P,
                     double* R_host, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * twa_build_basis that never synchronises: the two n x n Cholesky factorisations, the triangular inverses and the
+ * product R = R_2 R_1 run on the device (one workgroup, fp64, the operations of the host routines in their order:
+ * P and R come out bit for bit as from twa_build_basis).  The call only enqueues on `stream`, so it can be captured
+ * into a HIP graph together with what follows it (twa_quantize, the step calls).
+ *   R      [out, optional, DEVICE] n*n doubles, row major, zero below the diagonal.
+ *   status [out, DEVICE] one int32: 0 when the stream reaches the end of the call's work, or 1 + the 0-based index
+ *          of the checkpoint at which a Cholesky pivot was <= 1e-12 * the largest diagonal entry (the condition of
+ *          TWA_ERR_RANK); in that case P and the upper triangle of R are filled with NaN.  The library sets it to 0 first.
+ * Other arguments, workspace and argument errors as for twa_build_basis.
+ */
+int twa_build_basis_async(const float* W, int64_t D, int32_t n, int64_t ldw, float* P, int64_t ldp, double* R,
+                          int32_t* status, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * The same construction for checkpoints whose rows arrive in panels (a matrix that is generated, read or
  * kept elsewhere piece by piece: the benchmark's largest configuration streams 16 M-row panels).  A panel
  * is rows [r0, r0 + rows) of all n vectors: pointer W + r0 with the matrix' stride.  One pass of
@@ -203,6 +217,11 @@ int twa_gram_accumulate(const float* W, int64_t rows, int32_t n, int64_t ldw, do
 int twa_gram_factor(const double* gram, int32_t n, float* rinv, double* R_host, int32_t compose, void* stream);
 int twa_apply_rinv(const float* W, int64_t rows, int32_t n, int64_t ldw, const float* rinv, float* P, int64_t ldp,
                    void* stream);
+/* twa_gram_factor on the device, without synchronising: rinv <- R^-1 of the accumulated Gram matrix, R [optional,
+ * DEVICE, n*n doubles] <- R of THIS pass (the caller multiplies the passes' factors if it wants their product).
+ * status [DEVICE, int32]: left alone on success, set to 1 + the index of the dependent checkpoint (and rinv, R to
+ * NaN) if it still holds 0 and a pivot fails: zero it before the first pass. */
+int twa_gram_factor_async(const double* gram, int32_t n, float* rinv, double* R, int32_t* status, void* stream);
 
 /*
  * twa_apply_rinv with the result stored straight in the form `out` describes -- the second pass of the construction

@@ -87,6 +87,10 @@ def lib():
         L.twa_absmax_accumulate.restype = C.c_int
         L.twa_gscale_for_absmax.argtypes = [f32]
         L.twa_gscale_for_absmax.restype = C.c_float
+        L.twa_build_basis_async.argtypes = [vp, i64, i32, i64, vp, i64, vp, vp, vp, C.c_size_t, vp]
+        L.twa_build_basis_async.restype = C.c_int
+        L.twa_gram_factor_async.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.twa_gram_factor_async.restype = C.c_int
         L.twa_set_launch_knob.argtypes = [i32, i32]
         L.twa_set_launch_knob.restype = C.c_int
         L.twa_project_layers_workspace_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
@@ -447,6 +451,22 @@ def build_basis(W: torch.Tensor, D: int, out: Optional[torch.Tensor] = None, wan
         raise TwaError(rc, "twa_build_basis", f"(checkpoint {int(R[0, 0].item())})")
     _check(rc, "twa_build_basis")
     return P, R
+
+
+def build_basis_async(W: torch.Tensor, D: int, out: Optional[torch.Tensor] = None, R: Optional[torch.Tensor] = None,
+                      status: Optional[torch.Tensor] = None, ws: Optional[Workspace] = None):
+    """twa_build_basis_async: as build_basis, without any synchronisation.  R: optional (n, n) float64 DEVICE tensor;
+    status: one int32 on the device (0, or 1 + the index of a dependent checkpoint).  Returns (P, R, status)."""
+    assert W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous()
+    n, ldw = W.shape
+    P = torch.empty_like(W) if out is None else out
+    if status is None:
+        status = torch.empty(1, dtype=torch.int32, device=W.device)
+    if ws is None:
+        ws = Workspace(build_basis_workspace_bytes(n), device=W.device)
+    _check(lib().twa_build_basis_async(_ptr(W), D, n, ldw, _ptr(P), int(P.shape[1]), _ptr(R), _ptr(status), ws.ptr,
+                                       ws.nbytes, _stream()), "twa_build_basis_async")
+    return P, R, status
 
 
 def build_basis_panels(W: torch.Tensor, D: int, panel_rows: int, out: Optional[torch.Tensor] = None):

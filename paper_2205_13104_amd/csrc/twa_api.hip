@@ -619,6 +619,61 @@ int twa_build_basis(const float* W, int64_t D, int32_t n, int64_t ldw, float* P,
   return TWA_OK;
 }
 
+int twa_build_basis_async(const float* W, int64_t D, int32_t n, int64_t ldw, float* P, int64_t ldp, double* R,
+                          int32_t* status, void* ws, size_t ws_bytes, void* stream) {
+  if (!W || !P || !status) return TWA_ERR_NULL;
+  int rc = check_dims(D, n, ldw, TWA_F32);
+  if (rc != TWA_OK) return rc;
+  rc = check_dims(D, n, ldp, TWA_F32);
+  if (rc != TWA_OK) return rc;
+  if (n > D) return TWA_ERR_SHAPE;
+  if (!aligned16(W) || !aligned16(P) || (reinterpret_cast<uintptr_t>(R) & 7u) || (reinterpret_cast<uintptr_t>(status) & 3u))
+    return TWA_ERR_ALIGN;
+  if (static_cast<const void*>(W) == static_cast<const void*>(P) && ldw != ldp) return TWA_ERR_SHAPE;
+  size_t need = 0;
+  twa_build_basis_workspace_bytes(n, &need);
+  if (!ws || ws_bytes < need) return TWA_ERR_WORKSPACE;
+  if (!aligned16(ws)) return TWA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int NP = (n + 15) / 16 * 16;
+  const int grid = basis_grid(D);
+  if (grid <= 0) return TWA_ERR_NO_DEVICE;
+  double* partial = static_cast<double*>(ws);
+  double* gram_dev = partial + (size_t)kGramMaxGrid * NP * NP;
+  float* rinv_dev = reinterpret_cast<float*>(gram_dev + (size_t)NP * NP);
+  // between a pass's reduction and the next pass's Gram kernel the partial sums are dead: room for two n x n matrices
+  double* r_pass = partial;
+  double* scratch = partial + (size_t)n * n;
+  rc = launch_zero_status(status, st);
+  if (rc != TWA_OK) return rc;
+  const float* src = W;
+  int64_t lds = ldw;
+  for (int pass = 0; pass < 2; ++pass) {
+    rc = launch_gram(src, D, n, lds, partial, grid, gram_dev, false, /*orthonormal_input=*/pass == 1, st);
+    if (rc != TWA_OK) return rc;
+    rc = launch_gram_factor(gram_dev, n, rinv_dev, R ? (pass == 0 ? R : r_pass) : nullptr, status, st);
+    if (rc != TWA_OK) return rc;
+    if (R && pass == 1) {
+      rc = launch_compose_upper(r_pass, R, scratch, n, st);
+      if (rc != TWA_OK) return rc;
+    }
+    rc = launch_apply_rinv(src, lds, P, ldp, D, n, rinv_dev, grid, true, st);
+    if (rc != TWA_OK) return rc;
+    src = P;
+    lds = ldp;
+  }
+  return TWA_OK;
+}
+
+int twa_gram_factor_async(const double* gram, int32_t n, float* rinv, double* R, int32_t* status, void* stream) {
+  if (!gram || !rinv || !status) return TWA_ERR_NULL;
+  if (n <= 0 || n > TWA_MAX_N) return TWA_ERR_SHAPE;
+  if (!aligned16(gram) || !aligned16(rinv) || (reinterpret_cast<uintptr_t>(R) & 7u) || (reinterpret_cast<uintptr_t>(status) & 3u))
+    return TWA_ERR_ALIGN;
+  if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
+  return launch_gram_factor(gram, n, rinv, R, status, static_cast<hipStream_t>(stream));
+}
+
 // ---- the same construction for checkpoints whose rows arrive in panels -------------------------
 
 int twa_probe_read(const void* buf, size_t bytes, uint32_t* sink, void* stream) {

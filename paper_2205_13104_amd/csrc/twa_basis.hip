@@ -466,6 +466,122 @@ __global__ __launch_bounds__(256, 2) void apply_rinv_kernel(const float* W, int6
   }
 }
 
+// ---- the n x n algebra of a pass on the device (n <= 128): no host round trip, nothing synchronises --------
+// G = R^T R (R upper triangular, positive diagonal), X = R^-1, in fp64 by ONE workgroup with the whole matrix in
+// LDS (129 x 128 doubles = 132 KB: gfx950 gives a workgroup up to 160 KB).  The operations and their order are
+// those of the host routines of the synchronous path (right-looking elimination visits the terms of every entry
+// in the same order k = 0, 1, .. as the host's dot products; products and sums are rounded separately, as the host
+// compiler does without fused multiply-add), so both paths give the same bits.
+//   upper triangle of A: G, then R in place          lower triangle: X^T (X[i][j], i < j, at A[j][i])
+//   xd: the diagonal of X
+// A pivot d <= tol * max diag(G) stops the factorisation: *status (if still 0) becomes 1 + the index of that
+// checkpoint, and rinv is filled with NaN so that everything computed from it says so.
+constexpr int kFactorStride = TWA_MAX_N + 1;
+__global__ __launch_bounds__(256) void gram_factor_kernel(const double* __restrict__ gram, int n, int NP,
+                                                          float* __restrict__ rinv, double* __restrict__ Rout,
+                                                          int* __restrict__ status, double tol) {
+#pragma clang fp contract(off)            // products and sums rounded separately, as in the host routines
+  __shared__ double A[TWA_MAX_N * kFactorStride];
+  __shared__ double xd[TWA_MAX_N];
+  const int tid = threadIdx.x;
+  for (int idx = tid; idx < n * n; idx += 256) {
+    const int r = idx / n, c = idx - r * n;
+    if (r <= c) A[r * kFactorStride + c] = gram[r * NP + c];
+  }
+  __syncthreads();
+  double dmax = 0.0;
+  for (int i = 0; i < n; ++i) dmax = fmax(dmax, A[i * kFactorStride + i]);
+  int bad = 0;
+  for (int j = 0; j < n; ++j) {
+    const double d = A[j * kFactorStride + j];                 // every thread reads the same value: uniform branch
+    if (!(d > tol * dmax)) { bad = j + 1; break; }
+    const double rjj = sqrt(d);
+    for (int i = j + 1 + tid; i < n; i += 256) A[j * kFactorStride + i] = A[j * kFactorStride + i] / rjj;
+    __syncthreads();
+    if (tid == 0) A[j * kFactorStride + j] = rjj;
+    const int b = tid & (TWA_MAX_N - 1);                       // column of the trailing matrix, two threads per column
+    if (b > j && b < n) {
+      const double rjb = A[j * kFactorStride + b];
+      for (int a = j + 1 + (tid >> 7); a <= b; a += 2)
+        A[a * kFactorStride + b] = A[a * kFactorStride + b] - A[j * kFactorStride + a] * rjb;
+    }
+    __syncthreads();
+  }
+  if (bad) {
+    if (tid == 0 && *status == 0) *status = bad;
+    const float nan = __builtin_nanf("");
+    for (int idx = tid; idx < NP * NP; idx += 256) rinv[idx] = nan;
+    if (Rout)
+      for (int idx = tid; idx < n * n; idx += 256) Rout[idx] = __builtin_nan("");
+    return;
+  }
+  // X = R^-1, row by row from the bottom; thread j owns column j and reads only what it wrote itself
+  if (tid < n) xd[tid] = 1.0 / A[tid * kFactorStride + tid];
+  __syncthreads();
+  if (tid < n) {
+    const int j = tid;
+    for (int i = j - 1; i >= 0; --i) {
+      double v = 0.0;
+      for (int k = i + 1; k <= j; ++k) {
+        const double xkj = k == j ? xd[j] : A[j * kFactorStride + k];
+        v = v + A[i * kFactorStride + k] * xkj;
+      }
+      A[j * kFactorStride + i] = -v / A[i * kFactorStride + i];
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < NP * NP; idx += 256) {
+    const int r = idx / NP, c = idx - r * NP;
+    double x = 0.0;
+    if (r < n && c < n && r <= c) x = r == c ? xd[r] : A[c * kFactorStride + r];
+    rinv[idx] = (float)x;
+  }
+  if (Rout)
+    for (int idx = tid; idx < n * n; idx += 256) {
+      const int r = idx / n, c = idx - r * n;
+      Rout[idx] = r <= c ? A[r * kFactorStride + c] : 0.0;
+    }
+}
+
+// T = R * Rtot (both n x n upper triangular, row major): W = Q1 Rtot and Q1 = P R give W = P (R Rtot).  One
+// thread per entry, the terms added in the order of the host routine.
+__global__ __launch_bounds__(256) void compose_upper_kernel(const double* __restrict__ R, const double* __restrict__ Rtot,
+                                                            double* __restrict__ T, int n) {
+#pragma clang fp contract(off)
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n * n) return;
+  const int i = idx / n, j = idx - i * n;
+  double v = 0.0;
+  if (i <= j)
+    for (int k = i; k <= j; ++k) v = v + R[i * n + k] * Rtot[k * n + j];
+  T[idx] = v;
+}
+__global__ __launch_bounds__(256) void copy_doubles_kernel(const double* __restrict__ src, double* __restrict__ dst, int count) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx < count) dst[idx] = src[idx];
+}
+__global__ void zero_status_kernel(int* p) { *p = 0; }
+
+int launch_zero_status(int* status, hipStream_t st) {
+  hipLaunchKernelGGL(zero_status_kernel, dim3(1), dim3(1), 0, st, status);
+  return hip_check(hipGetLastError());
+}
+
+// Factor the reduced Gram matrix on the device: rinv <- R^-1 (NP x NP floats), Rout <- R (n x n doubles) if wanted.
+int launch_gram_factor(const double* gram, int n, float* rinv, double* Rout, int* status, hipStream_t st) {
+  const int NP = (n + 15) / 16 * 16;
+  hipLaunchKernelGGL(gram_factor_kernel, dim3(1), dim3(256), 0, st, gram, n, NP, rinv, Rout, status, 1e-12);
+  return hip_check(hipGetLastError());
+}
+
+// Rtot <- R * Rtot through the scratch T (n x n doubles).
+int launch_compose_upper(const double* R, double* Rtot, double* T, int n, hipStream_t st) {
+  const int blocks = (n * n + 255) / 256;
+  hipLaunchKernelGGL(compose_upper_kernel, dim3(blocks), dim3(256), 0, st, R, Rtot, T, n);
+  hipLaunchKernelGGL(copy_doubles_kernel, dim3(blocks), dim3(256), 0, st, T, Rtot, n * n);
+  return hip_check(hipGetLastError());
+}
+
 // Zero the padding [D, ld) of every vector.
 __global__ __launch_bounds__(256) void zero_padding_kernel(float* __restrict__ Q, int64_t D, int64_t ld) {
   const int j = blockIdx.y;

@@ -61,6 +61,9 @@ int launch_gram(const float* W, int64_t D, int n, int64_t ldw, double* partial, 
 int launch_apply_rinv(const float* W, int64_t ldw, float* Q, int64_t ldq, int64_t D, int n, const float* rinv_dev,
                       int grid, bool zero_padding, hipStream_t st);
 
+int launch_zero_status(int* status, hipStream_t st);
+int launch_gram_factor(const double* gram, int n, float* rinv, double* Rout, int* status, hipStream_t st);
+int launch_compose_upper(const double* R, double* Rtot, double* T, int n, hipStream_t st);
 int launch_apply_rinv_store(const float* W, int64_t ldw, int64_t rows, int n, const float* rinv_dev, const twa_pmat& out,
                             int64_t row0, bool last, int grid, hipStream_t st);
 

@@ -240,3 +240,56 @@ def test_launch_knobs_are_explicit_and_bounded():
     src = "".join(open(os.path.join(ROOT, "paper_2205_13104_amd", "csrc", f)).read()
                   for f in os.listdir(os.path.join(ROOT, "paper_2205_13104_amd", "csrc")))
     assert "getenv" not in src
+
+
+def test_fused_second_pass_and_absmax_argument_errors():
+    L = twa.lib()
+    out = _pm(dtype=twa.I8, n=4, D=5000, ld=6144, data=0x100000, scales=0x200000, block=128)
+
+    def call(W=0x6000, rows=5000, n=4, ldw=6144, rinv=0x7000, desc=out, row0=0):
+        return L.twa_apply_rinv_quantize(W, rows, n, ldw, rinv, C.byref(desc), row0, None)
+
+    assert call(W=None) == twa.ERR_NULL and call(rinv=None) == twa.ERR_NULL
+    assert L.twa_apply_rinv_quantize(0x6000, 5000, 4, 6144, 0x7000, None, 0, None) == twa.ERR_NULL
+    assert call(n=5) == twa.ERR_SHAPE                                   # the descriptor says 4 vectors
+    assert call(rows=2048, row0=1024) == twa.ERR_ALIGN                  # panels start on multiples of 2048 rows ...
+    assert call(rows=1000) == twa.ERR_ALIGN                             # ... and end there unless they end the matrix
+    assert call(rows=4096, row0=2048) == twa.ERR_SHAPE                  # past the end of the matrix
+    assert call(desc=_pm(dtype=twa.I8, n=4, D=5000, ld=6144, data=0x100000, scales=0, block=128)) == twa.ERR_NULL
+    assert call(desc=_pm(dtype=twa.I8, n=4, D=5000, ld=6144, data=0x100000, scales=0x200000, block=256)) == twa.ERR_SHAPE
+    assert call(desc=_pm(dtype=twa.I4, n=4, D=5000, ld=6144, data=0x100000, scales=0x200000, block=64, gscale=0.0)) == twa.ERR_SHAPE
+    assert call(desc=_pm(dtype=twa.U4MM, n=4, D=5000, ld=6144, data=0x100000, scales=0x200000)) == twa.ERR_DTYPE
+    assert call(desc=_pm(dtype=twa.I8, n=4, D=5000, ld=6144, data=0x6000 + 64, scales=0x200000, block=128)) == twa.ERR_SHAPE  # overlap
+    assert call() == twa.ERR_NO_DEVICE                                  # a valid call goes on to the device
+    assert L.twa_absmax_accumulate(None, 100, 4, 128, 0x9000, 0, None) == twa.ERR_NULL
+    assert L.twa_absmax_accumulate(0x6000, 100, 4, 128, None, 0, None) == twa.ERR_NULL
+    assert L.twa_absmax_accumulate(0x6000, 100, 4, 64, 0x9000, 0, None) == twa.ERR_SHAPE      # ld < rows
+    assert L.twa_absmax_accumulate(0x6000, 100, 4, 128, 0x9002, 0, None) == twa.ERR_ALIGN
+
+
+def test_gscale_for_absmax_is_the_rule_of_the_four_bit_format():
+    # 2^(floor(log2(amax / 7)) - 14); the oracle states the same rule from its own code
+    import numpy as np
+    from oracle import twa_oracle as orc
+    assert twa.gscale_for_absmax(0.0) == 1.0
+    assert twa.gscale_for_absmax(7.0) == 2.0 ** -14 and twa.gscale_for_absmax(13.99) == 2.0 ** -14
+    assert twa.gscale_for_absmax(14.0) == 2.0 ** -13
+    for amax in (3.1e-4, 5.5e-5, 0.02, 1.0, 6.9999, 123.0):
+        p = np.zeros((1, 64), dtype=np.float32)
+        p[0, 3] = -amax
+        assert twa.gscale_for_absmax(float(np.float32(amax))) == orc.gscale_i4(p)
+
+
+def test_async_basis_argument_errors():
+    L = twa.lib()
+    wsb = twa.build_basis_workspace_bytes(4)
+    assert L.twa_build_basis_async(None, 1000, 4, 1024, 0x7000, 1024, None, 0x9000, 0x8000, wsb, None) == twa.ERR_NULL
+    assert L.twa_build_basis_async(0x6000, 1000, 4, 1024, 0x7000, 1024, None, None, 0x8000, wsb, None) == twa.ERR_NULL   # status
+    assert L.twa_build_basis_async(0x6000, 3, 4, 128, 0x7000, 128, None, 0x9000, 0x8000, wsb, None) == twa.ERR_SHAPE    # n > D
+    assert L.twa_build_basis_async(0x6000, 1000, 4, 1024, 0x7000, 1024, 0xA004, 0x9000, 0x8000, wsb, None) == twa.ERR_ALIGN
+    assert L.twa_build_basis_async(0x6000, 1000, 4, 1024, 0x7000, 1024, None, 0x9000, 0x8000, 8, None) == twa.ERR_WORKSPACE
+    assert L.twa_build_basis_async(0x6000, 1000, 4, 1024, 0x7000, 1024, None, 0x9000, 0x8000, wsb, None) == twa.ERR_NO_DEVICE
+    assert L.twa_gram_factor_async(None, 4, 0x7000, None, 0x9000, None) == twa.ERR_NULL
+    assert L.twa_gram_factor_async(0x6000, 4, 0x7000, None, None, None) == twa.ERR_NULL
+    assert L.twa_gram_factor_async(0x6000, 129, 0x7000, None, 0x9000, None) == twa.ERR_SHAPE
+    assert L.twa_gram_factor_async(0x6000, 4, 0x7000, None, 0x9000, None) == twa.ERR_NO_DEVICE
