@@ -285,7 +285,7 @@ __device__ __forceinline__ void apply_tile_products(const float* tile, const flo
 // 16-lane runs of 64 bytes per column; written to memory like that the kernel reached 4.0 TB/s (the plain copy
 // of this device: 5.3).  They are therefore first written to LDS as out[col][row] (the staged input tile is
 // dead by then and gives its place), and leave in the shape the destination wants:
-//   EMIT_F32   Q as fp32: 16 lanes store the 64 rows of a column as one run of 256 bytes
+//   EMIT_F32   Q as fp32 (this one leaves straight from the registers: see the kernel)
 //   EMIT_BF16  the same rounded to bfloat16 (nearest even)
 //   EMIT_I8 / EMIT_I4  the block-absmax integer codes of twa_quantize, bit for bit the recipe of that call (every
 //              step one correctly rounded binary32 operation): Q in fp32 is then never written at all.  A
@@ -446,6 +446,27 @@ __global__ __launch_bounds__(256, 2) void apply_rinv_kernel(const float* W, int6
       default: apply_tile_products<NB, 3>(tile, afrag, m, kq, acc); break;
     }
     __syncthreads();      // every wave has read the staged tile: the finished one may take its place
+    if constexpr (EMIT == EMIT_F32) {
+      // fp32 leaves straight from the registers, 64 bytes per column and 16-lane run: taking it through LDS for
+      // runs of 256 bytes was measured and is 5 % SLOWER (two more barriers per tile; 5.4 against 5.1 ms)
+      const int64_t i0 = c * kTileRows;
+#pragma unroll
+      for (int jbi = 0; jbi < 2; ++jbi) {
+        const int jb = jbs[jbi];
+        if (jb >= 0) {
+#pragma unroll
+          for (int rg = 0; rg < RG; ++rg) {
+            const int64_t row = i0 + 16 * rg + m;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int col = 16 * jb + mfma_row_f32(lane, r);
+              if (col < n && row < T.rows_out) T.q[(int64_t)col * T.ld + row] = acc[jbi][rg][r];
+            }
+          }
+        }
+      }
+      continue;
+    }
     const bool waits = GROUP == 2 && ((c - c0) & 1) == 0;          // first tile of a pair
     float* out = waits ? first : tile;
 #pragma unroll
