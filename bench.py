@@ -41,10 +41,10 @@ VALU_PEAK_TLANE = 256 * 4 * 16 * 2.4e9 / 1e12
 METRIC = "projected steps/s and P-stream HBM GB/s (% of peak), D=25.6M n=100 int8"
 STORAGE_NAME = {"f32": "fp32", "bf16": "bf16", "i8": "int8", "i4": "int4", "mm16": "minmax16", "mm8": "minmax8",
                 "mm4": "minmax4", "mm3": "minmax3", "mm2": "minmax2", "mm1": "minmax1"}
-# vector-ALU lane-instructions per stored element of the step kernels, from rocprofv3 --pmc SQ_INSTS_VALU
-# (profiles/valu_utilisation.txt): the 4-bit and narrower kernels are co-limited by the vector ALUs
-VALU_INSTR_PER_ELEMENT = {"i8": 2.14, "mm8": 2.14, "i4": 2.56, "mm4": 2.56}
-
+# vector-ALU lane-instructions per stored element of the step kernels (projection-like, expansion-like), from
+# rocprofv3 --pmc SQ_INSTS_VALU (profiles/sq_counters_imagenet_resnet50_int4_int8.txt, profiles/valu_utilisation.txt):
+# the 4-bit and narrower kernels are co-limited by the vector ALUs
+VALU_INSTR_PER_ELEMENT = {"i8": (2.14, 2.28), "mm8": (2.14, 2.28), "i4": (2.47, 2.64), "mm4": (2.56, 2.52)}
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -318,9 +318,10 @@ def main():
                                     "achieved": round(alg[o] / (dur[o] * 1e-3) / 1e9, 1)}
     if args.storage in VALU_INSTR_PER_ELEMENT:
         # the second bound of the integer-code kernels: vector-ALU issue (decode + FMA per stored element)
-        lane_instr = VALU_INSTR_PER_ELEMENT[args.storage] * n * D
+        per_elem = VALU_INSTR_PER_ELEMENT[args.storage][0 if ("project" in dom or "beta_step" in dom) else 1]
+        lane_instr = per_elem * n * D
         tl = lane_instr / (dur[dom] * 1e-3) / 1e12
-        roofline["valu"] = {"lane_instr_per_element": VALU_INSTR_PER_ELEMENT[args.storage],
+        roofline["valu"] = {"lane_instr_per_element": per_elem,
                             "achieved_Tlane_instr_per_s": round(tl, 2), "peak": round(VALU_PEAK_TLANE, 2),
                             "frac": round(tl / VALU_PEAK_TLANE, 4),
                             "note": "co-limited: neither HBM nor the vector ALUs saturated" if tl / VALU_PEAK_TLANE > 0.5
