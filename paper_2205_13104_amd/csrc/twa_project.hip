@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256, 2) void project_layers_kernel(PView P, const f
   project_body<DT, 1, U, NCH, VPL, true, SQUARES>(P, g, 0, 1, partial, cpw, 0, plan, aux);
 }
 
-// S = P^T G for up to TWA_MAX_K gradients in ONE pass over P (n <= 32 basis vectors; not int4).
+// S = P^T G for up to TWA_MAX_K gradients in ONE pass over P (up to 32 basis vectors per launch; not int4).
 // The gradients are 44 % of the bytes at k = 8, n = 20, so they must not be fetched once per wave:
 // the workgroup loads each tile of G once, coalesced, into a double-buffered LDS tile (the loads of
 // tile t+1 are issued before tile t is consumed), and every wave reads its k slices from there.
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(256, 2) void project_layers_kernel(PView P, const f
 template <int DT, int U, int NCH>
 __global__ __launch_bounds__(256) void project_batched_kernel(PView P, const float* __restrict__ G, int64_t ldg,
                                                               int kvalid, float* __restrict__ partial, int cpw,
-                                                              int tiles_per_wg) {
+                                                              int tiles_per_wg, int col_begin, int col_end) {
   using S = Store<DT>;
   constexpr int KB = TWA_MAX_K;
   constexpr int EPV = S::kEPV;
@@ -334,8 +334,9 @@ __global__ __launch_bounds__(256) void project_batched_kernel(PView P, const flo
   int64_t t1 = t0 + tiles_per_wg;
   if (t1 > ntiles) t1 = ntiles;
 
-  const int c0 = wave * cpw;
-  int ncol = P.n - c0;
+  // this launch serves the basis vectors [col_begin, col_end) (at most 32 of them: 4 waves x 8 slots)
+  const int c0 = col_begin + wave * cpw;
+  int ncol = col_end - c0;
   ncol = ncol < 0 ? 0 : (ncol > cpw ? cpw : ncol);
   const uint32_t col_bytes = stored_bytes<DT>(D);
   const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
@@ -669,17 +670,25 @@ int launch_project_layers(const PView& P, int dtype, const float* g, const void*
 // k > 1 gradients.  Up to 32 basis vectors (and not int4, whose 32-element vectors leave no
 // registers for k gradient slices): one pass over P serves all k gradients (project_batched_kernel).
 // Otherwise the gradients are projected one launch at a time.
+// k > 1 gradients: one pass over P serves all k gradients (project_batched_kernel).  A launch takes up to 32
+// basis vectors (4 waves x 8 column slots, k running sums each); a wider matrix is served in groups of 32 vectors,
+// one launch each -- P is still read once in total, only the gradients are read once per group (n = 100, k = 8:
+// 2.6 GB + 4 x 0.8 GB instead of the 8 x 2.7 GB of one launch per gradient).  The 4-bit codes keep the
+// one-launch-per-gradient path: their 32-element lane vectors leave no registers for k gradient slices.
 template <int DT>
 static int launch_project_batched_dt(const PView& P, const float* g, int64_t ldg, int k, float* s, float* partial,
                                      int max_grid, hipStream_t st) {
   if constexpr (DT != TWA_I4) {
-    if (P.n <= 32) {
-      const int cpw = (P.n + 3) / 4;
-      int grid, tiles_per_wg;
-      divide_tiles(P.D, kWave * Store<DT>::kEPV, max_grid, &grid, &tiles_per_wg);
+    int grid, tiles_per_wg;
+    divide_tiles(P.D, kWave * Store<DT>::kEPV, max_grid, &grid, &tiles_per_wg);
+    const int groups = (P.n + 31) / 32;
+    const int per_group = (P.n + groups - 1) / groups;            // balanced: 100 vectors -> 4 x 25
+    for (int col = 0; col < P.n; col += per_group) {
+      const int col_end = col + per_group < P.n ? col + per_group : P.n;
+      const int cpw = (col_end - col + 3) / 4;
 #define TWA_LAUNCH_B(U_, NCH_)                                                                              \
   hipLaunchKernelGGL((project_batched_kernel<DT, U_, NCH_>), dim3(grid), dim3(256), 0, st, P, g, ldg, k, partial, \
-                     cpw, tiles_per_wg)
+                     cpw, tiles_per_wg, col, col_end)
       if (cpw <= 3) TWA_LAUNCH_B(3, 1);
       else if (cpw == 4) TWA_LAUNCH_B(4, 1);
       else if (cpw == 5) TWA_LAUNCH_B(5, 1);
@@ -688,9 +697,9 @@ static int launch_project_batched_dt(const PView& P, const float* g, int64_t ldg
 #undef TWA_LAUNCH_B
       int rc = hip_check(hipGetLastError());
       if (rc != TWA_OK) return rc;
-      hipLaunchKernelGGL(project_reduce_kernel, dim3(P.n * k), dim3(kWave), 0, st, partial, grid, P.n * k, s);
-      return hip_check(hipGetLastError());
     }
+    hipLaunchKernelGGL(project_reduce_kernel, dim3(P.n * k), dim3(kWave), 0, st, partial, grid, P.n * k, s);
+    return hip_check(hipGetLastError());
   }
   for (int c = 0; c < k; ++c) {
     int rc = launch_project(P, DT, g + (int64_t)c * ldg, s + (int64_t)c * P.n, partial, max_grid, st);
