@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--D", type=int, default=0, help="override the parameter count (smoke runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of each oracle sample")
+    ap.add_argument("--basis-baseline", action="store_true",
+                    help="also time the one-time basis construction: twa_build_basis on the device against the oracle's "
+                         "Householder factorisation on the host cores, the latter on a slice of D rows and scaled (its cost is linear in D)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known 1 GiB read + 1 GiB write) so that a "
@@ -391,6 +394,31 @@ def main():
                "sample": f"{what}, fp64, on-the-fly dequantisation; {how_all}",
                "one_core": {"value": round(v_one, 5), "unit": unit, "cores": 1, "sample": how_one}}
 
+    # ---- the one-time basis construction against the oracle's (optional leg) ---------------------------
+    basis = None
+    if args.basis_baseline and not from_panels:
+        from oracle import twa_oracle as orc
+        Wb = synth.checkpoints(wl, seed=args.seed, device=dev, D=D)
+        Pb = torch.empty_like(Wb)
+        wsb = twa.Workspace(twa.build_basis_workspace_bytes(n), device=dev)
+        twa.build_basis(Wb, D, out=Pb, want_R=False, ws=wsb)
+        torch.cuda.synchronize()
+        tb = []
+        for _ in range(5):
+            t = time.perf_counter()
+            twa.build_basis(Wb, D, out=Pb, want_R=False, ws=wsb)
+            torch.cuda.synchronize()
+            tb.append(time.perf_counter() - t)
+        Ds = max(4 * n, min(D, 1_000_000))
+        Wh = Wb[:, :Ds].cpu().numpy().astype(np.float64)
+        del Wb, Pb
+        t = time.perf_counter()
+        orc.build_basis(Wh)
+        t_or = time.perf_counter() - t
+        basis = {"twa_build_basis_ms": round(1e3 * statistics.median(tb), 3),
+                 "oracle_s": round(t_or * D / Ds, 2), "cores": orc.threads(),
+                 "sample": f"Householder QR in fp64 of the first {Ds} of {D} rows of the same {n} checkpoints: {t_or:.2f} s, scaled by {D}/{Ds}"}
+
     store_txt = f"P stored as {args.storage}" + (f" (block {pm.block}, {'fp32' if dtype == twa.I8 else 'fp16'} scales)"
                                                   if dtype in (twa.I8, twa.I4) else "")
     headline = (args.mode == "whole" and wl.name == "imagenet_resnet50" and args.storage == "i8" and D == wl.D)
@@ -420,6 +448,8 @@ def main():
         "p_bytes_per_pass": p_bytes, "roofline": roofline, "cpu_baseline": cpu,
         "setup_s": {"generate": round(t1 - t0, 3), "build_basis": round(t2 - t1, 4), "quantize": round(t3 - t2, 4)},
     }
+    if basis is not None:
+        out["basis_construction"] = basis
     if graph_ms is not None:
         out["hip_graph"] = {"ms_per_step": round(graph_ms, 5), "steps_per_s": round(1e3 / graph_ms, 1),
                             "note": f"the same {K} steps captured once in a HIP graph and replayed (median of {max(1, args.reps)}): "
