@@ -95,7 +95,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a single-GPU library (no collectives, no sharding); run with --gpus 1. "
-                 "How the path would shard over GPUs is described in the repository's design notes.")
+                 "(It would shard by rows of P: every GPU holds a slice of all n vectors and of w, and one all-reduce of n floats per step joins the partial coefficients.)")
     if args.batched:
         args.mode = "batched"
     if args.storage is None:

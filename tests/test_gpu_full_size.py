@@ -2,8 +2,8 @@
 
 Up to the ResNet-50 shape the fp64 oracle evaluates a WHOLE step in about a second on the machine's host cores, so
 there the comparison is exhaustive: every coefficient of s and every element of g~ and w, against the oracle on
-the stored P the GPU used, by relative L2 AND per element (max-abs bars, derived from the arithmetic in the
-repository's design notes).  Only the largest configuration (D = 350 M, n = 128: 45 G products per pass) is
+the stored P the GPU used, by relative L2 AND per element (max-abs bars, derived from the arithmetic in
+check_step_whole).  Only the largest configuration (D = 350 M, n = 128: 45 G products per pass) is
 sampled: a few coefficients over the whole of D, and g~ / w on sampled blocks.  Orthonormality of the full-size
 bases is checked with an fp64 library matmul over row chunks."""
 import numpy as np
