@@ -674,7 +674,7 @@ int twa_gram_factor_async(const double* gram, int32_t n, float* rinv, double* R,
   return launch_gram_factor(gram, n, rinv, R, status, static_cast<hipStream_t>(stream));
 }
 
-// ---- the same construction for checkpoints whose rows arrive in panels -------------------------
+// ---- measurement aid: a plain non-temporal read pass (no other entry point calls it) ------------
 
 int twa_probe_read(const void* buf, size_t bytes, uint32_t* sink, void* stream) {
   if (!buf || !sink) return TWA_ERR_NULL;
@@ -683,6 +683,8 @@ int twa_probe_read(const void* buf, size_t bytes, uint32_t* sink, void* stream) 
   if (device_cus() <= 0) return TWA_ERR_NO_DEVICE;
   return launch_read_probe(buf, bytes, sink, static_cast<hipStream_t>(stream));
 }
+
+// ---- the same construction for checkpoints whose rows arrive in panels -------------------------
 
 int twa_basis_state_bytes(int32_t n, size_t* gram_bytes, size_t* rinv_bytes, size_t* ws_bytes) {
   if (!gram_bytes || !rinv_bytes || !ws_bytes) return TWA_ERR_NULL;

@@ -21,6 +21,90 @@
 
 namespace twa {
 
+// ---- the 4-bit block codes in integers ---------------------------------------------------------------------
+// Decoding a 4-bit code to a float and multiplying costs two vector instructions per element, and at 32 elements
+// per 128-bit load the vector ALUs, not the memory stream, bound the kernel.  The integer dot product of eight
+// 4-bit pairs (v_dot8_i32_i4) takes a dword of codes as it is stored (after one XOR that turns code + 8 into the
+// two's complement nibble), so the gradient comes to it instead: each lane turns its 32-element slice of g into a
+// fixed-point number per element, x_i = round_to_nearest_even(g_i / unit), unit = 2^(e-22) with 2^e the smallest
+// power of two above the slice's largest |g_i| (|x_i| <= 2^22), written as six signed hexadecimal digits
+// x_i = sum_k d_ik 16^k, d_ik in [-8, 7].  Then sum_i q_i x_i = sum_k 16^k sum_i q_i d_ik exactly, in 32-bit
+// integers, and one conversion and two multiplications per (lane, basis vector) bring it back to a float.
+// Error model: g is rounded to multiples of `unit` <= 2^-21 max|g_slice| (error <= unit / 2); products and sums
+// of a slice are exact; the running sums over tiles are fp32 as for every other storage type.
+// A slice that holds an infinity or a NaN gets unit = NaN, which every sum it enters inherits.
+constexpr bool kI4IntegerDots = true;
+constexpr int kFixDigits = 6;
+
+// out[k] = nibble k of y[0..7] gathered into one dword (nibble r of out[k] = nibble k of y[r]), k < 6:
+// 16-bit halves, bytes, then nibbles change places.
+__device__ __forceinline__ void gather_digits(const uint32_t (&y)[8], uint32_t (&out)[kFixDigits]) {
+  uint32_t a[8], b[8];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    a[r] = __builtin_amdgcn_perm(y[r + 4], y[r], 0x05040100u);
+    a[r + 4] = __builtin_amdgcn_perm(y[r + 4], y[r], 0x07060302u);
+  }
+#pragma unroll
+  for (int h = 0; h < 8; h += 4) {
+#pragma unroll
+    for (int r = h; r < h + 2; ++r) {
+      b[r] = __builtin_amdgcn_perm(a[r], a[r + 2], 0x02060004u);
+      b[r + 2] = __builtin_amdgcn_perm(a[r], a[r + 2], 0x03070105u);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < kFixDigits; r += 2) {
+    out[r] = (b[r] & 0x0f0f0f0fu) | ((b[r + 1] << 4) & 0xf0f0f0f0u);
+    out[r + 1] = ((b[r] >> 4) & 0x0f0f0f0fu) | (b[r + 1] & 0xf0f0f0f0u);
+  }
+}
+
+// The fixed-point digits of a lane's 32 gradient elements, in the nibble order of the stored codes (element
+// 8m + r in nibble r of dg[m][k]); returns `unit`.
+__device__ __forceinline__ float fixed_point_digits(const float (&g)[32], uint32_t (&dg)[4][kFixDigits]) {
+  uint32_t amax = 0;                               // largest |g| as a bit pattern: NaN sorts above infinity
+#pragma unroll
+  for (int e = 0; e < 32; ++e) {
+    const uint32_t ab = as_u32(g[e]) & 0x7fffffffu;
+    amax = ab > amax ? ab : amax;
+  }
+  const uint32_t eb = amax >> 23;                  // biased exponent: max|g| < 2^(eb - 126)
+  const uint32_t ex = eb < 22u ? 22u : eb;         // (below 2^-104 the unit stays 2^-126)
+  const float up = as_f32((275u - ex) << 23);      // 2^(148 - ex) = 1 / unit
+  const float unit = eb == 255u ? __builtin_nanf("") : as_f32((ex - 21u) << 23);
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    uint32_t y[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      // 1.5 * 2^23 + x: the low mantissa bits hold x (two's complement), rounded to nearest even by the FMA
+      const uint32_t bits = as_u32(__builtin_fmaf(g[8 * m + r], up, 12582912.0f));
+      // x + 0x888888 has the digits d_k + 8 in its nibbles; XOR 8 makes each the two's complement nibble of d_k
+      y[r] = (bits + (0x00888888u - 0x4B400000u)) ^ 0x00888888u;
+    }
+    gather_digits(y, dg[m]);
+  }
+  return unit;
+}
+
+// sum_i q_i x_i for the 32 codes of one 128-bit load against the digits of the lane's slice.
+__device__ __forceinline__ int dot_codes_fixed(const u32x4& codes, const uint32_t (&dg)[4][kFixDigits]) {
+  int q[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) q[m] = (int)(codes[m] ^ 0x88888888u);   // stored nibble = code + 8
+  // Horner over the digits, most significant first, in ONE accumulator (wrap-around in between is harmless:
+  // the final value is below 2^31 in magnitude and the arithmetic is modulo 2^32)
+  int v = 0;
+#pragma unroll
+  for (int k = kFixDigits - 1; k >= 0; --k) {
+    if (k != kFixDigits - 1) v = (int)((uint32_t)v << 4);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) v = __builtin_amdgcn_sdot8(q[m], (int)dg[m][k], v, false);
+  }
+  return v;
+}
+
 // KB = gradients handled together (1 or TWA_MAX_K slots), U = column slots per chunk,
 // NCH = chunks, so a wave owns up to U*NCH basis vectors; VPL = 128-bit vectors per lane per
 // basis vector and tile.
@@ -45,6 +129,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
   constexpr int SLOTS = U * NCH;
+  constexpr bool DOT8 = DT == TWA_I4 && kI4IntegerDots;     // the 4-bit block codes: integer dot products
   static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -140,6 +225,8 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
     //      the layer), and the range check is per dword, so elements past that end arrive as 0 --
     float gs[KB][VPL][EPV];
     float gcorr[KB][VPL];
+    uint32_t gdig[DOT8 ? KB : 1][DOT8 ? VPL : 1][4][kFixDigits];     // DOT8: the slice as fixed-point digits,
+    float gunit[DOT8 ? KB : 1][DOT8 ? VPL : 1];                      // and what one unit of it is worth
     float mean_hi[SQUARES ? VPL : 1][EPV], mean_lo[SQUARES ? VPL : 1][EPV];     // SQUARES: this lane's slice of the mean
 #pragma unroll
     for (int c = 0; c < KB; ++c) {
@@ -176,7 +263,11 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
             for (int e = 0; e < EPV; ++e) gs[c][v][e] = rel + e >= head ? gs[c][v][e] : 0.0f;
           }
         }
-        if constexpr (kNibbles<DT> || kMinMax<DT>) {
+        if constexpr (DOT8) {
+          static_assert(!DOT8 || EPV == 32, "a lane's slice is one 128-bit load of codes");
+          gunit[c][v] = fixed_point_digits(gs[c][v], gdig[c][v]);
+          gcorr[c][v] = 0.0f;
+        } else if constexpr (kNibbles<DT> || kMinMax<DT>) {
           float sum = 0.0f;
 #pragma unroll
           for (int e = 0; e < EPV; ++e) sum += gs[c][v][e];
@@ -220,7 +311,8 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
                 valid ? ((((pos >> kScaleSpanShift) * (uint32_t)P.n + (uint32_t)col) << gshift) +
                          ((pos & (uint32_t)(kScaleSpan - 1)) >> P.block_shift)) * (uint32_t)S::kScaleBytes
                       : 0x7fffff00u;
-            sc[u][v] = load_scale<DT>(rs, soff, P.gscale);
+            if constexpr (DOT8) sc[u][v] = as_f32(ld16(rs, soff));      // the binary16 bits: widened when consumed
+            else sc[u][v] = load_scale<DT>(rs, soff, P.gscale);
           } else {
             sc[u][v] = 1.0f;
           }
@@ -234,6 +326,15 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
         const int slot = ch * U + u;
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
+          if constexpr (DOT8) {
+#pragma unroll
+            for (int c = 0; c < KB; ++c) {
+              const float d = (float)dot_codes_fixed(raw[u][v], gdig[c][v]) * gunit[c][v];
+              const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)as_u32(sc[u][v])) * P.gscale;
+              acc[slot][c] = __builtin_fmaf(d, scale, acc[slot][c]);
+            }
+            continue;
+          }
           float x[EPV];
           decode<DT>(raw[u][v], x);
           if constexpr (SQUARES) {
@@ -260,13 +361,21 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
     // double buffered: the loads of chunk ch+1 are issued before chunk ch is consumed
     u32x4 rawA[U][VPL], rawB[U][VPL];
     float scA[U][VPL], scB[U][VPL];
+    // (DOT8: what consumes a load is a single XOR, which the scheduler would otherwise put, with its wait, right
+    //  behind the load -- one load in flight per wave.  Nothing may cross the fences.)
+    auto fence = [] { if constexpr (DOT8) __builtin_amdgcn_sched_barrier(0); };
     load_chunk(0, rawA, scA);
+    fence();
 #pragma unroll
     for (int ch = 0; ch < NCH; ch += 2) {
       if (ch + 1 < NCH) load_chunk(ch + 1, rawB, scB);
+      fence();
       compute_chunk(ch, rawA, scA);
+      fence();
       if (ch + 2 < NCH) load_chunk(ch + 2, rawA, scA);
+      fence();
       if (ch + 1 < NCH) compute_chunk(ch + 1, rawB, scB);
+      fence();
     }
   }
 
@@ -304,6 +413,120 @@ __global__ __launch_bounds__(256, 2) void project_layers_kernel(PView P, const f
                                                                 float* __restrict__ partial, int cpw, LayerPlan plan,
                                                                 float* __restrict__ aux) {
   project_body<DT, 1, U, NCH, VPL, true, SQUARES>(P, g, 0, 1, partial, cpw, 0, plan, aux);
+}
+
+// The whole-model projection on 4-bit block codes (k = 1): the body above with the integer dot products, and the
+// stream pipelined ACROSS tiles.  With 32 elements per 128-bit load a tile is only 1 KB per basis vector, so the
+// start of a tile -- fetch the slice of g, turn it into digits, fetch the first chunk of codes -- is a large part
+// of the tile's time, and a wave that has nothing in flight meanwhile costs bandwidth (a pure-read kernel with
+// this access pattern falls from 6.3 to 3.9 TB/s when its loads are not kept in flight).  Here the next tile's
+// slice of g is fetched as soon as this tile's digits are formed (its registers are free then), and the next
+// tile's first chunk of codes while this tile's last chunk is consumed.  Sums, reduction and partial-sum layout
+// as in project_body.
+template <int U, int NCH>
+__global__ __launch_bounds__(256, 2) void project_i4_kernel(PView P, const float* __restrict__ g,
+                                                         float* __restrict__ partial, int cpw, int tiles_per_wg) {
+  using S = Store<TWA_I4>;
+  constexpr int EPV = S::kEPV;                                     // 32 codes per lane and basis vector
+  constexpr int TILE = kWave * EPV;                                // = one scale span
+  constexpr int SLOTS = U * NCH;
+  static_assert(TILE == kScaleSpan, "a tile is one span of scales");
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t D = P.D;
+  const int64_t ntiles = (D + TILE - 1) / TILE;
+  const int64_t t0 = (int64_t)blockIdx.x * tiles_per_wg;
+  int64_t t1 = t0 + tiles_per_wg;
+  if (t1 > ntiles) t1 = ntiles;
+  const int c0 = wave * cpw;
+  int ncol = P.n - c0;
+  ncol = ncol < 0 ? 0 : (ncol > cpw ? cpw : ncol);
+  const uint32_t col_bytes = stored_bytes<TWA_I4>(D);
+  const int64_t ld_bytes = P.ld >> 1;
+  const int gshift = kScaleSpanShift - P.block_shift;              // log2(scales per span and vector)
+  const uint32_t span_scale_bytes = ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes;
+  const rsrc_t rg = make_rsrc(g, (uint32_t)(D * 4));               // elements past D arrive as 0
+  const uint32_t loc = (uint32_t)lane * EPV;                       // this lane's first element inside a tile
+
+  float acc[SLOTS];
+#pragma unroll
+  for (int sl = 0; sl < SLOTS; ++sl) acc[sl] = 0.0f;
+
+  float gs[EPV];                                                   // slice of g of the tile whose digits are formed next
+  uint32_t gdig[4][kFixDigits];
+  float gunit = 0.0f;
+  // (`dead` = 0x80000000 puts every offset of a fetch outside its descriptor: a prefetch past the workgroup's last
+  //  tile is issued like any other, returns zeros and moves no memory -- no branch in the pipeline)
+  auto load_g = [&](int64_t t, uint32_t dead) {
+    const uint32_t elem = (uint32_t)(t * TILE) + loc;
+#pragma unroll
+    for (int q = 0; q < EPV / 4; ++q) {
+      const u32x4 x = ld128(rg, ((elem + 4u * q) * 4u) | dead);    // shared by the 4 waves: keep it cacheable
+#pragma unroll
+      for (int r = 0; r < 4; ++r) gs[4 * q + r] = as_f32(x[r]);
+    }
+  };
+  // chunk ch of tile t: codes and binary16 scale bits of column slots [ch*U, (ch+1)*U)
+  auto load_chunk = [&](int64_t t, int ch, uint32_t dead, u32x4 (&raw)[U], uint32_t (&sc)[U]) {
+    const uint32_t voff = (uint32_t)(((uint64_t)t * TILE + loc) >> 1) | dead;
+    const rsrc_t rs = make_rsrc(P.scales + t * (int64_t)span_scale_bytes, span_scale_bytes);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int slot = ch * U + u;
+      const bool valid = slot < ncol;
+      const int col = valid ? c0 + slot : 0;
+      const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
+      raw[u] = load_codes<TWA_I4>(rc, voff);
+      // [vector][block in span]; an unused column slot reads far outside the range and gets 0
+      const uint32_t soff = valid ? ((((uint32_t)col) << gshift) + (loc >> P.block_shift)) * (uint32_t)S::kScaleBytes : 0x7fffff00u;
+      sc[u] = ld16(rs, soff | dead);
+    }
+  };
+  auto compute_chunk = [&](int ch, const u32x4 (&raw)[U], const uint32_t (&sc)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float d = (float)dot_codes_fixed(raw[u], gdig) * gunit;
+      const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)sc[u]) * P.gscale;
+      acc[ch * U + u] = __builtin_fmaf(d, scale, acc[ch * U + u]);
+    }
+  };
+  // nothing may cross a fence: what consumes a load is a single XOR, which the scheduler would otherwise put,
+  // with its wait, right behind the load
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+  // Three code buffers: chunk 0 of a tile always sits in Z, chunks 1, 3, .. in X, chunks 2, 4, .. in Y, so that every
+  // tile runs the same code (two buffers would change roles from tile to tile when NCH is odd, and the second copy
+  // of the loop body costs the kernel its registers).  Z is free once chunk 0 is consumed: the next tile's chunk 0
+  // is fetched into it while this tile's last chunk is consumed.
+  static_assert(NCH >= 2, "chunk 0 of the next tile is fetched while another chunk is consumed");
+  u32x4 rawX[U], rawY[U], rawZ[U];
+  uint32_t scX[U], scY[U], scZ[U];
+  load_g(t0, 0u);                                                   // (every workgroup of the grid owns a tile)
+  load_chunk(t0, 0, 0u, rawZ, scZ);
+  fence();
+  for (int64_t t = t0; t < t1; ++t) {
+    gunit = fixed_point_digits(gs, gdig);
+    fence();
+    const uint32_t dead = t + 1 < t1 ? 0u : 0x80000000u;
+    load_g(t + 1, dead);                                            // gs is free: the digits are formed
+    fence();
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      if (ch + 1 == NCH) load_chunk(t + 1, 0, dead, rawZ, scZ);
+      else if ((ch + 1) % 2 == 1) load_chunk(t, ch + 1, 0u, rawX, scX);
+      else load_chunk(t, ch + 1, 0u, rawY, scY);
+      fence();
+      if (ch == 0) compute_chunk(ch, rawZ, scZ);
+      else if (ch % 2 == 1) compute_chunk(ch, rawX, scX);
+      else compute_chunk(ch, rawY, scY);
+      fence();
+    }
+  }
+
+#pragma unroll
+  for (int sl = 0; sl < SLOTS; ++sl) {
+    const float tot = wave_sum_to_last_lane(acc[sl]);
+    if (lane == kSumLane && sl < ncol) partial[(int64_t)blockIdx.x * P.n + c0 + sl] = tot;
+  }
 }
 
 // S = P^T G for up to TWA_MAX_K gradients in ONE pass over P (up to 32 basis vectors per launch; not int4).
@@ -495,7 +718,10 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
 #define TWA_LAUNCH(U_, NCH_)                                                                                  \
   do {                                                                                                        \
-    if constexpr (LAYERED)                                                                                    \
+    if constexpr (DT == TWA_I4 && kI4IntegerDots && !LAYERED && KB == 1 && VPL == 1)                            \
+      hipLaunchKernelGGL((project_i4_kernel<U_, NCH_>), dim3(grid), dim3(256), 0, st, P, g, partial, cpw,     \
+                         tiles_per_wg);                                                                       \
+    else if constexpr (LAYERED)                                                                               \
       hipLaunchKernelGGL((project_layers_kernel<DT, U_, NCH_, VPL, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, \
                          partial, cpw, plan, aux);                                                            \
     else if constexpr (NCH_ <= 4)                                                                             \
@@ -526,7 +752,10 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
       TWA_LAUNCH(5, 5);
     } else {
       switch ((cpw + 3) / 4) {
-        case 1: TWA_LAUNCH(4, 1); break;
+        case 1:
+          if constexpr (DT == TWA_I4 && kI4IntegerDots && !LAYERED && KB == 1 && VPL == 1) TWA_LAUNCH(2, 2);   // (its pipeline needs two chunks)
+          else TWA_LAUNCH(4, 1);
+          break;
         case 2: TWA_LAUNCH(4, 2); break;
         case 3: TWA_LAUNCH(4, 3); break;
         case 4: TWA_LAUNCH(4, 4); break;
@@ -628,7 +857,6 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   hipLaunchKernelGGL(project_layers_reduce_kernel<kMinMax<DT>>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial,
                      partial_g, P.n, plan, P.D, grid, reinterpret_cast<const float*>(P.scales),
                      kNibbles<DT> ? 8.0f : P.code_bias,   // (nibbles are decoded as code + 8 - 8)
-                    
                      S, bs);
   return hip_check(hipGetLastError());
 }
@@ -667,9 +895,6 @@ int launch_project_layers(const PView& P, int dtype, const float* g, const void*
   }
 }
 
-// k > 1 gradients.  Up to 32 basis vectors (and not int4, whose 32-element vectors leave no
-// registers for k gradient slices): one pass over P serves all k gradients (project_batched_kernel).
-// Otherwise the gradients are projected one launch at a time.
 // k > 1 gradients: one pass over P serves all k gradients (project_batched_kernel).  A launch takes up to 32
 // basis vectors (4 waves x 8 column slots, k running sums each); a wider matrix is served in groups of 32 vectors,
 // one launch each -- P is still read once in total, only the gradients are read once per group (n = 100, k = 8:
