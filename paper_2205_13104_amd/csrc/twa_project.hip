@@ -129,7 +129,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
   constexpr int SLOTS = U * NCH;
-  constexpr bool DOT8 = DT == TWA_I4 && kI4IntegerDots;     // the 4-bit block codes: integer dot products
+  constexpr bool DOT8 = kNibbles<DT> && kI4IntegerDots;     // 4-bit codes (block or min-max): integer dot products
   static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -265,6 +265,12 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
         }
         if constexpr (DOT8) {
           static_assert(!DOT8 || EPV == 32, "a lane's slice is one 128-bit load of codes");
+          if constexpr (kMinMax<DT>) {                        // the zero point b_l multiplies the layer's sum of g itself
+            float sum = 0.0f;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) sum += gs[c][v][e];
+            gsum += sum;
+          }
           gunit[c][v] = fixed_point_digits(gs[c][v], gdig[c][v]);
           gcorr[c][v] = 0.0f;
         } else if constexpr (kNibbles<DT> || kMinMax<DT>) {
@@ -330,8 +336,12 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
 #pragma unroll
             for (int c = 0; c < KB; ++c) {
               const float d = (float)dot_codes_fixed(raw[u][v], gdig[c][v]) * gunit[c][v];
-              const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)as_u32(sc[u][v])) * P.gscale;
-              acc[slot][c] = __builtin_fmaf(d, scale, acc[slot][c]);
+              if constexpr (S::kScaled) {
+                const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)as_u32(sc[u][v])) * P.gscale;
+                acc[slot][c] = __builtin_fmaf(d, scale, acc[slot][c]);
+              } else {
+                acc[slot][c] += d;                            // min-max codes: a_l multiplies the finished sum
+              }
             }
             continue;
           }
