@@ -105,3 +105,54 @@ def test_batched_and_single_int4_projections_agree_bit_for_bit():
     S = twa.project(pm, G)
     for c in range(k):
         assert torch.equal(S[c], twa.project(pm, G[c, :D].contiguous()))
+
+
+@pytest.mark.parametrize("kind", ["i4", "mm4"])
+def test_layerwise_projection_on_four_bit_codes_follows_the_same_model(kind):
+    """Layer-wise, a slice that straddles a layer boundary is rounded once per layer, the other layer's elements
+    counting as zeros; the model's six-sigma bar per coefficient, for the block codes and the paper's min-max codes."""
+    from paper_2205_13104_amd import synth
+    D, n = 120011, 20
+    sizes = [5, 1, 0, 30, 64, 2049, 1000, 4097, 17]
+    sizes = sizes + [(D - sum(sizes)) // 2, 0]
+    sizes.append(D - sum(sizes))
+    off = synth.layer_offsets(sizes)
+    offs = off.numpy()
+    L = len(sizes)
+    plan = twa.LayerPlan(off, D)
+    P32 = random_basis_like(D, n, seed=12)
+    if kind == "i4":
+        pm = twa.quantize(P32, D, twa.I4)
+        om = to_oracle(pm)
+        dense = om.dense()[:, :D]
+    else:
+        pm = twa.quantize_minmax(P32, D, plan, bits=4)
+        om = to_oracle(pm, layer_off=offs)
+        dense = om.dense()[:, :D]
+    for name, g in gradients(D, seed=21):
+        S = twa.project_layers(pm, torch.from_numpy(g).cuda(), plan).cpu().numpy().astype(np.float64)
+        g64 = g.astype(np.float64)
+        ref = orc.project_layers(om, g64, offs)
+        assert S.shape == ref.shape == (L, n)
+        worst = 0.0
+        for l in range(L):
+            a, b = int(offs[l]), int(offs[l + 1])
+            if b == a:
+                assert np.all(S[l] == 0.0)
+                continue
+            gl = np.zeros(D, dtype=np.float32)
+            gl[a:b] = g[a:b]
+            u = slice_units(gl)[a:b]
+            if kind == "i4":
+                wgt = dense[:, a:b]                                  # what multiplies a rounding error of g: the stored value
+            else:
+                al = float(pm.scales[l, 0])                          # min-max: the integer part is a_l * (code - 8); b_l and 8 a_l
+                wgt = dense[:, a:b] - (float(pm.scales[l, 1]) + 8.0 * al)   # multiply the float sum of g
+            terms = np.sqrt((dense[:, a:b] ** 2) @ (g64[a:b] ** 2))
+            likely = 6.0 * np.sqrt((wgt ** 2) @ (u ** 2) / 12.0) + 2e-6 * terms + 2e-6 * abs(float(np.sum(g64[a:b]))) * \
+                (0.0 if kind == "i4" else abs(float(pm.scales[l, 1])) + 8.0 * abs(float(pm.scales[l, 0])))
+            worst = max(worst, float(np.max(np.abs(S[l] - ref[l]) / np.maximum(likely, 1e-300))))
+            assert np.all(np.abs(S[l] - ref[l]) <= likely), (name, l, sizes[l])
+        say("layer-wise", kind, name, " rel_l2", rel_l2(S, ref), " largest error / six sigma", worst)
+        if name in ("gaussian", "tiny", "huge"):
+            assert rel_l2(S, ref) <= REL_L2_TOL
