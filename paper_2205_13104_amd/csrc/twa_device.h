@@ -141,7 +141,8 @@ template <int DT> constexpr bool kNibbles = DT == TWA_I4 || DT == TWA_U4MM;
 //   F32, BF16 : raw = value
 //   I8        : raw = q
 //   I4        : raw[e] = (q+8) for even e, 16*(q+8) for odd e   (elements e = 2*byte, 2*byte+1)
-// Callers fold the 1/16 and the -8 into per-tile / per-block terms instead of per element.
+// Callers fold the 1/16 and the -8 into per-tile / per-block terms instead of per element.  (The expansion decodes
+// nibbles this way; the projection takes them as integers, see twa_project.hip.)
 template <int DT> __device__ __forceinline__ void decode(const u32x4& v, float* raw);
 
 template <> __device__ __forceinline__ void decode<TWA_F32>(const u32x4& v, float* raw) {

@@ -8,8 +8,8 @@
 //     the n basis vectors between them, so a lane keeps <= 32 running sums in registers with
 //     compile-time indices;
 //   * every lane fetches 128 bits per load, a wave covers 1 KB contiguous of one basis vector;
-//     int8 / int4 / bf16 are decoded in registers, the block scale is applied once per
-//     (lane-vector, basis vector), never per element;
+//     int8 / bf16 are decoded in registers, 4-bit codes enter integer dot products as they are stored; the block
+//     scale is applied once per (lane-vector, basis vector), never per element;
 //   * all loads go through buffer descriptors: the ragged end of D and unused column slots
 //     read zeros without memory traffic and without branches in the steady state;
 //   * one cross-lane reduction per wave at the very end, per-workgroup partial sums in the
@@ -33,7 +33,6 @@ namespace twa {
 // Error model: g is rounded to multiples of `unit` <= 2^-21 max|g_slice| (error <= unit / 2); products and sums
 // of a slice are exact; the running sums over tiles are fp32 as for every other storage type.
 // A slice that holds an infinity or a NaN gets unit = NaN, which every sum it enters inherits.
-constexpr bool kI4IntegerDots = true;
 constexpr int kFixDigits = 6;
 
 // out[k] = nibble k of y[0..7] gathered into one dword (nibble r of out[k] = nibble k of y[r]), k < 6:
@@ -129,7 +128,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
   constexpr int SLOTS = U * NCH;
-  constexpr bool DOT8 = kNibbles<DT> && kI4IntegerDots;     // 4-bit codes (block or min-max): integer dot products
+  constexpr bool DOT8 = kNibbles<DT>;                      // 4-bit codes (block or min-max): integer dot products
   static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -224,7 +223,6 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
     // ---- this lane's slice of the gradient(s); the descriptor ends at element D (at the end of
     //      the layer), and the range check is per dword, so elements past that end arrive as 0 --
     float gs[KB][VPL][EPV];
-    float gcorr[KB][VPL];
     uint32_t gdig[DOT8 ? KB : 1][DOT8 ? VPL : 1][4][kFixDigits];     // DOT8: the slice as fixed-point digits,
     float gunit[DOT8 ? KB : 1][DOT8 ? VPL : 1];                      // and what one unit of it is worth
     float mean_hi[SQUARES ? VPL : 1][EPV], mean_lo[SQUARES ? VPL : 1][EPV];     // SQUARES: this lane's slice of the mean
@@ -272,19 +270,11 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
             gsum += sum;
           }
           gunit[c][v] = fixed_point_digits(gs[c][v], gdig[c][v]);
-          gcorr[c][v] = 0.0f;
-        } else if constexpr (kNibbles<DT> || kMinMax<DT>) {
+        } else if constexpr (kMinMax<DT>) {
           float sum = 0.0f;
 #pragma unroll
           for (int e = 0; e < EPV; ++e) sum += gs[c][v][e];
-          if constexpr (kMinMax<DT>) gsum += sum;
-          gcorr[c][v] = kNibbles<DT> ? -8.0f * sum : 0.0f;     // nibble codes are taken relative to 8
-          if constexpr (kNibbles<DT>) {
-#pragma unroll
-            for (int e = 1; e < EPV; e += 2) gs[c][v][e] *= 0.0625f;   // odd nibbles decode as 16*code
-          }
-        } else {
-          gcorr[c][v] = 0.0f;
+          gsum += sum;
         }
       }
     }
@@ -354,12 +344,12 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
 #pragma unroll
           for (int c = 0; c < KB; ++c) {
             if constexpr (S::kScaled) {
-              float d = gcorr[c][v];
+              float d = 0.0f;
 #pragma unroll
               for (int e = 0; e < EPV; ++e) d = __builtin_fmaf(x[e], gs[c][v][e], d);
               acc[slot][c] = __builtin_fmaf(d, sc[u][v], acc[slot][c]);
             } else {
-              float d = acc[slot][c] + (kNibbles<DT> ? gcorr[c][v] : 0.0f);
+              float d = acc[slot][c];
 #pragma unroll
               for (int e = 0; e < EPV; ++e) d = __builtin_fmaf(SQUARES ? x[e] * gs[c][v][e] : x[e], SQUARES ? x[e] : gs[c][v][e], d);
               acc[slot][c] = d;
@@ -728,7 +718,7 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
 #define TWA_LAUNCH(U_, NCH_)                                                                                  \
   do {                                                                                                        \
-    if constexpr (DT == TWA_I4 && kI4IntegerDots && !LAYERED && KB == 1 && VPL == 1)                            \
+    if constexpr (DT == TWA_I4 && !LAYERED && KB == 1 && VPL == 1)                                              \
       hipLaunchKernelGGL((project_i4_kernel<U_, NCH_>), dim3(grid), dim3(256), 0, st, P, g, partial, cpw,     \
                          tiles_per_wg);                                                                       \
     else if constexpr (LAYERED)                                                                               \
@@ -763,7 +753,7 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
     } else {
       switch ((cpw + 3) / 4) {
         case 1:
-          if constexpr (DT == TWA_I4 && kI4IntegerDots && !LAYERED && KB == 1 && VPL == 1) TWA_LAUNCH(2, 2);   // (its pipeline needs two chunks)
+          if constexpr (DT == TWA_I4 && !LAYERED && KB == 1 && VPL == 1) TWA_LAUNCH(2, 2);   // (project_i4_kernel's pipeline needs two chunks)
           else TWA_LAUNCH(4, 1);
           break;
         case 2: TWA_LAUNCH(4, 2); break;
@@ -866,7 +856,7 @@ static int launch_project_layers_dt(const PView& P, const float* g, const void* 
   if (rc != TWA_OK) return rc;
   hipLaunchKernelGGL(project_layers_reduce_kernel<kMinMax<DT>>, dim3(L), dim3(TWA_MAX_N * kRedWays), 0, st, partial,
                      partial_g, P.n, plan, P.D, grid, reinterpret_cast<const float*>(P.scales),
-                     kNibbles<DT> ? 8.0f : P.code_bias,   // (nibbles are decoded as code + 8 - 8)
+                     kNibbles<DT> ? 8.0f : P.code_bias,   // (nibbles enter the dot products as code - 8)
                      S, bs);
   return hip_check(hipGetLastError());
 }
