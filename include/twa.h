@@ -281,12 +281,14 @@ int twa_quantize(const float* P, int64_t D, int32_t n, int64_t ldp, twa_pmat* ou
  *   s  [out] k*n floats, s[c*n + j] = sum_i value(P)_ij * g_c[i].
  *   ws, ws_bytes  device workspace of at least twa_project_workspace_bytes(n, k).
  * fp32 arithmetic; the reduction order is fixed, so repeated calls give identical bits.
- * TWA_I4 computes the products in integers: every 32 consecutive elements of g (slices starting at
+ * TWA_I4 (and, in the layer-wise calls, the min-max formats of 4 bits and fewer) computes the products in
+ * integers: every 32 consecutive elements of g (slices starting at
  * multiples of 32) are first rounded to nearest even multiples of unit = 2^(e-22), 2^e being the
  * smallest power of two above the slice's largest |g_i| (unit >= 2^-126) -- an error of at most
  * unit/2 <= 2^-22 max|g_slice| per element -- and the products with the codes and their sums over
  * a slice are then exact; the sums over slices are fp32 as for the other types.  A slice that
- * holds an infinity or a NaN makes every coefficient NaN.
+ * holds an infinity or a NaN makes every coefficient NaN.  (Layer-wise, the elements of a slice that
+ * belong to another layer count as zeros.)
  */
 int twa_project(const twa_pmat* P, const float* g, int32_t k, int64_t ldg, float* s, void* ws,
                 size_t ws_bytes, void* stream);

@@ -59,8 +59,20 @@ __device__ __forceinline__ void gather_digits(const uint32_t (&y)[8], uint32_t (
   }
 }
 
-// The fixed-point digits of a lane's 32 gradient elements, in the nibble order of the stored codes (element
-// 8m + r in nibble r of dg[m][k]); returns `unit`.
+// Codes of 4 bits and fewer enter the dot products; the narrower ones are spread to one code per nibble first.
+template <int DT>
+constexpr bool kDotCodes = kNibbles<DT> || DT == TWA_U2MM || DT == TWA_U1MM || DT == TWA_U3MM;
+
+// Which of the lane's 32 elements meets nibble r of the m-th dword of spread codes (see spread_codes).
+template <int DT> __device__ __forceinline__ constexpr int slice_elem(int m, int r) {
+  if constexpr (DT == TWA_U1MM) return 4 * r + m;                       // dword m holds bit m of every nibble of the word
+  else if constexpr (DT == TWA_U2MM || DT == TWA_U3MM) return 16 * (m >> 1) + 2 * r + (m & 1);   // even / odd codes of word m/2
+  else return 8 * m + r;                                                 // 4-bit codes: as stored
+}
+
+// The fixed-point digits of a lane's 32 gradient elements, in the nibble order of the spread codes (element
+// slice_elem(m, r) in nibble r of dg[m][k]); returns `unit`.
+template <int DT>
 __device__ __forceinline__ float fixed_point_digits(const float (&g)[32], uint32_t (&dg)[4][kFixDigits]) {
   uint32_t amax = 0;                               // largest |g| as a bit pattern: NaN sorts above infinity
 #pragma unroll
@@ -78,7 +90,7 @@ __device__ __forceinline__ float fixed_point_digits(const float (&g)[32], uint32
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
       // 1.5 * 2^23 + x: the low mantissa bits hold x (two's complement), rounded to nearest even by the FMA
-      const uint32_t bits = as_u32(__builtin_fmaf(g[8 * m + r], up, 12582912.0f));
+      const uint32_t bits = as_u32(__builtin_fmaf(g[slice_elem<DT>(m, r)], up, 12582912.0f));
       // x + 0x888888 has the digits d_k + 8 in its nibbles; XOR 8 makes each the two's complement nibble of d_k
       y[r] = (bits + (0x00888888u - 0x4B400000u)) ^ 0x00888888u;
     }
@@ -87,11 +99,42 @@ __device__ __forceinline__ float fixed_point_digits(const float (&g)[32], uint32
   return unit;
 }
 
-// sum_i q_i x_i for the 32 codes of one 128-bit load against the digits of the lane's slice.
+// One code per nibble, as signed 4-bit numbers, from what a lane loaded for one basis vector:
+//   4 bits: the stored nibble is code + 8 (block codes) or the unsigned code c (min-max): XOR 8 gives code or c - 8;
+//   2 bits: a word holds 16 codes, code j at bits 2j: the even ones and the odd ones make a dword each;
+//   1 bit : the word holds 32 codes: bit s of every nibble makes dword s;
+//   3 bits: words 0 and 1 hold the low two bits like the 2-bit layout, word 2 the high bit of element 16h + 4k + m at
+//           bit 8k + m + 4h: for the even codes of word h (m = 0, 2) it moves to bit 2 of nibbles 2k, 2k + 1, for the odd
+//           ones (m = 1, 3) likewise.
+template <int DT> __device__ __forceinline__ void spread_codes(const u32x4& codes, int (&q)[4]) {
+  if constexpr (kNibbles<DT>) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) q[m] = (int)(codes[m] ^ 0x88888888u);
+  } else if constexpr (DT == TWA_U2MM) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      q[2 * h] = (int)(codes[h] & 0x33333333u);
+      q[2 * h + 1] = (int)((codes[h] >> 2) & 0x33333333u);
+    }
+  } else if constexpr (DT == TWA_U1MM) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) q[m] = (int)((codes[0] >> m) & 0x11111111u);
+  } else {
+    static_assert(DT == TWA_U3MM, "codes of 4 bits and fewer");
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t t = codes[2] >> (4 * h);
+      q[2 * h] = (int)((codes[h] & 0x33333333u) | ((t & 0x01010101u) << 2) | ((t & 0x04040404u) << 4));
+      q[2 * h + 1] = (int)(((codes[h] >> 2) & 0x33333333u) | ((t & 0x02020202u) << 1) | ((t & 0x08080808u) << 3));
+    }
+  }
+}
+
+// sum_i q_i x_i for the 32 codes of one load against the digits of the lane's slice.
+template <int DT>
 __device__ __forceinline__ int dot_codes_fixed(const u32x4& codes, const uint32_t (&dg)[4][kFixDigits]) {
   int q[4];
-#pragma unroll
-  for (int m = 0; m < 4; ++m) q[m] = (int)(codes[m] ^ 0x88888888u);   // stored nibble = code + 8
+  spread_codes<DT>(codes, q);
   // Horner over the digits, most significant first, in ONE accumulator (wrap-around in between is harmless:
   // the final value is below 2^31 in magnitude and the arithmetic is modulo 2^32)
   int v = 0;
@@ -128,7 +171,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
   constexpr int SLOTS = U * NCH;
-  constexpr bool DOT8 = kNibbles<DT>;                      // 4-bit codes (block or min-max): integer dot products
+  constexpr bool DOT8 = kDotCodes<DT>;                     // codes of 4 bits and fewer: integer dot products
   static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -269,7 +312,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
             for (int e = 0; e < EPV; ++e) sum += gs[c][v][e];
             gsum += sum;
           }
-          gunit[c][v] = fixed_point_digits(gs[c][v], gdig[c][v]);
+          gunit[c][v] = fixed_point_digits<DT>(gs[c][v], gdig[c][v]);
         } else if constexpr (kMinMax<DT>) {
           float sum = 0.0f;
 #pragma unroll
@@ -325,7 +368,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
           if constexpr (DOT8) {
 #pragma unroll
             for (int c = 0; c < KB; ++c) {
-              const float d = (float)dot_codes_fixed(raw[u][v], gdig[c][v]) * gunit[c][v];
+              const float d = (float)dot_codes_fixed<DT>(raw[u][v], gdig[c][v]) * gunit[c][v];
               if constexpr (S::kScaled) {
                 const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)as_u32(sc[u][v])) * P.gscale;
                 acc[slot][c] = __builtin_fmaf(d, scale, acc[slot][c]);
@@ -485,7 +528,7 @@ __global__ __launch_bounds__(256, 2) void project_i4_kernel(PView P, const float
   auto compute_chunk = [&](int ch, const u32x4 (&raw)[U], const uint32_t (&sc)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float d = (float)dot_codes_fixed(raw[u], gdig) * gunit;
+      const float d = (float)dot_codes_fixed<TWA_I4>(raw[u], gdig) * gunit;
       const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)sc[u]) * P.gscale;
       acc[ch * U + u] = __builtin_fmaf(d, scale, acc[ch * U + u]);
     }
@@ -504,7 +547,7 @@ __global__ __launch_bounds__(256, 2) void project_i4_kernel(PView P, const float
   load_chunk(t0, 0, 0u, rawZ, scZ);
   fence();
   for (int64_t t = t0; t < t1; ++t) {
-    gunit = fixed_point_digits(gs, gdig);
+    gunit = fixed_point_digits<TWA_I4>(gs, gdig);
     fence();
     const uint32_t dead = t + 1 < t1 ? 0u : 0x80000000u;
     load_g(t + 1, dead);                                            // gs is free: the digits are formed

@@ -1,4 +1,4 @@
-"""The projection on 4-bit block codes computes in integers: every lane rounds its 32-element slice of the gradient to
+"""The projection on codes of 4 bits and fewer computes in integers: every lane rounds its 32-element slice of the gradient to
 multiples of unit = 2^(e-22), where 2^e is the smallest power of two above the slice's largest |g_i|, and from there on
 the products and the sums of a slice are exact (include/twa.h, TWA_I4).  These tests hold the kernel to that model
 against the fp64 oracle, which projects the gradient as it is: a worst-case bound per coefficient built from the
@@ -107,10 +107,11 @@ def test_batched_and_single_int4_projections_agree_bit_for_bit():
         assert torch.equal(S[c], twa.project(pm, G[c, :D].contiguous()))
 
 
-@pytest.mark.parametrize("kind", ["i4", "mm4"])
-def test_layerwise_projection_on_four_bit_codes_follows_the_same_model(kind):
+@pytest.mark.parametrize("kind", ["i4", "mm4", "mm3", "mm2", "mm1"])
+def test_layerwise_projection_on_narrow_codes_follows_the_same_model(kind):
     """Layer-wise, a slice that straddles a layer boundary is rounded once per layer, the other layer's elements
-    counting as zeros; the model's six-sigma bar per coefficient, for the block codes and the paper's min-max codes."""
+    counting as zeros; the model's six-sigma bar per coefficient, for the block codes and the paper's min-max codes
+    of 4, 3, 2 bits and 1 bit (all of which enter the integer dot products, the narrow ones spread to nibbles)."""
     from paper_2205_13104_amd import synth
     D, n = 120011, 20
     sizes = [5, 1, 0, 30, 64, 2049, 1000, 4097, 17]
@@ -126,9 +127,10 @@ def test_layerwise_projection_on_four_bit_codes_follows_the_same_model(kind):
         om = to_oracle(pm)
         dense = om.dense()[:, :D]
     else:
-        pm = twa.quantize_minmax(P32, D, plan, bits=4)
+        pm = twa.quantize_minmax(P32, D, plan, bits=int(kind[2:]))
         om = to_oracle(pm, layer_off=offs)
         dense = om.dense()[:, :D]
+    bias = 8.0 if kind == "mm4" else 0.0                             # 4-bit codes enter the dot products as c - 8, narrower ones as c
     for name, g in gradients(D, seed=21):
         S = twa.project_layers(pm, torch.from_numpy(g).cuda(), plan).cpu().numpy().astype(np.float64)
         g64 = g.astype(np.float64)
@@ -146,11 +148,11 @@ def test_layerwise_projection_on_four_bit_codes_follows_the_same_model(kind):
             if kind == "i4":
                 wgt = dense[:, a:b]                                  # what multiplies a rounding error of g: the stored value
             else:
-                al = float(pm.scales[l, 0])                          # min-max: the integer part is a_l * (code - 8); b_l and 8 a_l
-                wgt = dense[:, a:b] - (float(pm.scales[l, 1]) + 8.0 * al)   # multiply the float sum of g
+                al = float(pm.scales[l, 0])                          # min-max: the integer part is a_l * (code - bias); b_l and
+                wgt = dense[:, a:b] - (float(pm.scales[l, 1]) + bias * al)  # bias * a_l multiply the float sum of g
             terms = np.sqrt((dense[:, a:b] ** 2) @ (g64[a:b] ** 2))
             likely = 6.0 * np.sqrt((wgt ** 2) @ (u ** 2) / 12.0) + 2e-6 * terms + 2e-6 * abs(float(np.sum(g64[a:b]))) * \
-                (0.0 if kind == "i4" else abs(float(pm.scales[l, 1])) + 8.0 * abs(float(pm.scales[l, 0])))
+                (0.0 if kind == "i4" else abs(float(pm.scales[l, 1])) + bias * abs(float(pm.scales[l, 0])))
             worst = max(worst, float(np.max(np.abs(S[l] - ref[l]) / np.maximum(likely, 1e-300))))
             assert np.all(np.abs(S[l] - ref[l]) <= likely), (name, l, sizes[l])
         say("layer-wise", kind, name, " rel_l2", rel_l2(S, ref), " largest error / six sigma", worst)
