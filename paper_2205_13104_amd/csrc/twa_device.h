@@ -345,12 +345,19 @@ __device__ __forceinline__ bool plan_header_ok(const int64_t* off, int L, int64_
   const int32_t* h = reinterpret_cast<const int32_t*>(off) - kPlanHeaderBytes / 4;
   return (uint32_t)h[0] == kPlanMagic && h[1] == L && *reinterpret_cast<const int64_t*>(h + 2) == D;
 }
+// The plan tables are written by an earlier launch, never by the kernels that walk them, and every lane reads the
+// same entry: they are fetched as constants, i.e. through the scalar cache.  As ordinary global loads they went
+// through the vector memory path, and waiting for one meant waiting for every load the wave had in flight (the
+// counter is in order) -- which drains a pipelined stream at every look at the plan.
+template <typename T> __device__ __forceinline__ T ld_plan(const T* p) {
+  return *(const __attribute__((address_space(4))) T*)(p);
+}
 // Largest l in [0, L-1] with first[l] <= t: the layer that owns tile t (empty layers own none).
 __device__ __forceinline__ int layer_of_tile(const LayerPlan& plan, int64_t t) {
   int a = 0, b = plan.L - 1;
   while (a < b) {
     const int mid = (a + b + 1) >> 1;
-    if (plan.first[mid] <= t) a = mid; else b = mid - 1;
+    if (ld_plan(plan.first + mid) <= t) a = mid; else b = mid - 1;
   }
   return a;
 }
@@ -364,10 +371,10 @@ struct LayerCursor {
   int64_t lo, hi;                    // its elements
   __device__ __forceinline__ void load(const LayerPlan& plan, int l) {
     cur = l;
-    first_cur = plan.first[l];
-    first_next = plan.first[l + 1];
-    lo = plan.off[l];
-    hi = plan.off[l + 1];
+    first_cur = ld_plan(plan.first + l);
+    first_next = ld_plan(plan.first + l + 1);
+    lo = ld_plan(plan.off + l);
+    hi = ld_plan(plan.off + l + 1);
   }
   // true if tile t lies in a later layer than the cursor (the caller may want to act before moving on)
   __device__ __forceinline__ bool behind(const LayerPlan& plan, int64_t t) const {

@@ -343,16 +343,17 @@ __global__ __launch_bounds__(256, 2) void expand_update_kernel(PView P, const fl
   const int cur0 = LAYERED && first < t_end ? layer_of_tile(plan, first) : 0;
   auto locate = [&](int64_t t, int& c) -> Where {
     if constexpr (LAYERED) {
-      while (c < plan.L - 1 && plan.first[c + 1] <= t) ++c;
-      const int64_t lo = plan.off[c];
-      int64_t hi = plan.off[c + 1];
+      // (tables that no kernel of this launch writes, the same entry for every lane: scalar fetches)
+      while (c < plan.L - 1 && ld_plan(plan.first + c + 1) <= t) ++c;
+      const int64_t lo = ld_plan(plan.off + c);
+      int64_t hi = ld_plan(plan.off + c + 1);
       hi = hi < D ? hi : D;
-      const int64_t e0 = (lo & ~(int64_t)(kLayerAlign - 1)) + (t - plan.first[c]) * X::TILE;
+      const int64_t e0 = (lo & ~(int64_t)(kLayerAlign - 1)) + (t - ld_plan(plan.first + c)) * X::TILE;
       float ma = 1.0f, mb = 0.0f;
       if constexpr (kMinMax<DT>) {
         const float* ab = reinterpret_cast<const float*>(P.scales) + 2 * (int64_t)c;
-        ma = ab[0];
-        mb = ab[1] + P.code_bias * ma;
+        ma = ld_plan(ab);
+        mb = ld_plan(ab + 1) + P.code_bias * ma;
       }
       return Where{e0, (uint32_t)lo, (uint32_t)hi, s + (int64_t)c * P.n, ma, mb};
     } else {

@@ -572,6 +572,178 @@ __global__ __launch_bounds__(256, 2) void project_i4_kernel(PView P, const float
   }
 }
 
+// The layer-wise projection on codes that enter the dot products (4-bit block codes; min-max codes of 4 bits and
+// fewer), pipelined across tiles like project_i4_kernel.  The tiles follow the layer plan as in project_body (a tile
+// belongs to one layer; the gradient is read through a descriptor that ends with the layer; the elements in front
+// of an unaligned layer start are zeroed; a lane wholly outside the layer reads nothing), and the place of the NEXT
+// tile is worked out one tile ahead, on a copy of the layer cursor, so that its slice of g and its first chunk of
+// codes can be fetched while this tile is consumed.  When the next tile belongs to another layer the running sums
+// are reduced and written to partial slot (workgroup + layer) after this tile, as in project_body.
+template <int DT, int U, int NCH>
+__global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, const float* __restrict__ g,
+                                                                    float* __restrict__ partial, int cpw,
+                                                                    LayerPlan plan, float* __restrict__ aux) {
+  using S = Store<DT>;
+  constexpr int EPV = S::kEPV;
+  constexpr int TILE = kWave * EPV;
+  constexpr int SLOTS = U * NCH;
+  static_assert(kDotCodes<DT> && EPV == 32 && TILE == kLayerAlign && TILE == kScaleSpan, "32 codes per lane, one span per tile");
+  static_assert(NCH >= 2, "chunk 0 of the next tile is fetched while another chunk is consumed");
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t D = P.D;
+  if (!plan_header_ok(plan.off, plan.L, D)) return;           // not this call's plan: the reduction kernel answers with NaN
+  const int64_t ntiles = (int64_t)plan.first[plan.L];
+  const int tiles_per_wg = (int)((ntiles + gridDim.x - 1) / gridDim.x);
+  const int64_t t0 = (int64_t)blockIdx.x * tiles_per_wg;
+  int64_t t1 = t0 + tiles_per_wg;
+  if (t1 > ntiles) t1 = ntiles;
+  if (t0 >= t1) return;                                        // a workgroup without tiles owns no partial slot
+  const int c0 = wave * cpw;
+  int ncol = P.n - c0;
+  ncol = ncol < 0 ? 0 : (ncol > cpw ? cpw : ncol);
+  const uint32_t col_bytes = stored_bytes<DT>(D);
+  const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
+  const int gshift = kScaleSpanShift - P.block_shift;
+  const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes : 0u;
+  const uint32_t loc = (uint32_t)lane * EPV;                   // this lane's first element inside a tile
+
+  // where a tile sits: first element of its grid cell, the part of the cell that belongs to the layer, the end of
+  // the layer in the gradient, and the place of this lane's codes in a stored vector
+  struct Place {
+    int64_t e0;
+    uint32_t head, tail, g_bytes, voff;
+  };
+  auto place = [&](const LayerCursor& c, int64_t t) {
+    Place p;
+    const int64_t hi = c.hi < D ? c.hi : D;
+    const int64_t e0 = c.tile_start(t, TILE);
+    // the same for every lane; said so, or the descriptors built from these numbers are taken for lane-dependent
+    // and every load through them is wrapped in a loop over the distinct values
+    const auto uni = [](uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); };
+    p.e0 = (int64_t)(((uint64_t)uni((uint32_t)((uint64_t)e0 >> 32)) << 32) | uni((uint32_t)e0));
+    p.g_bytes = uni((uint32_t)(hi * 4));
+    p.head = uni(c.lo > e0 ? (uint32_t)(c.lo - e0 < TILE ? c.lo - e0 : TILE) : 0u);
+    p.tail = uni(hi - e0 < TILE ? (uint32_t)(hi > e0 ? hi - e0 : 0) : (uint32_t)TILE);
+    p.voff = (loc + EPV <= p.head || loc >= p.tail) ? col_bytes : (uint32_t)((((uint64_t)p.e0 + loc) * S::kBitsPerElem) >> 3);
+    return p;
+  };
+
+  float acc[SLOTS];
+#pragma unroll
+  for (int sl = 0; sl < SLOTS; ++sl) acc[sl] = 0.0f;
+  float gsum = 0.0f;                                           // min-max formats: the layer's sum of the gradient itself
+  auto flush = [&](int slot_row) {
+    if constexpr (kMinMax<DT>) {
+      const float tot = wave_sum_to_last_lane(gsum);
+      if (wave == 0 && lane == kSumLane) aux[slot_row] = tot;
+      gsum = 0.0f;
+    }
+#pragma unroll
+    for (int sl = 0; sl < SLOTS; ++sl) {
+      const float tot = wave_sum_to_last_lane(acc[sl]);
+      if (lane == kSumLane && sl < ncol) partial[(int64_t)slot_row * P.n + c0 + sl] = tot;
+      acc[sl] = 0.0f;
+    }
+  };
+
+  float gs[EPV];
+  uint32_t gdig[4][kFixDigits];
+  float gunit = 0.0f;
+  // (`dead` = 0x80000000 puts every offset of a fetch outside its descriptor: zeros, no memory traffic, no branch)
+  auto load_g = [&](const Place& p, uint32_t dead) {
+    const rsrc_t rg = make_rsrc(g, p.g_bytes);
+    const uint32_t elem = (uint32_t)p.e0 + loc;
+#pragma unroll
+    for (int q = 0; q < EPV / 4; ++q) {
+      const u32x4 x = ld128(rg, ((elem + 4u * q) * 4u) | dead);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) gs[4 * q + r] = as_f32(x[r]);
+    }
+  };
+  auto load_chunk = [&](const Place& p, int ch, uint32_t dead, u32x4 (&raw)[U], uint32_t (&sc)[U]) {
+    rsrc_t rs = make_rsrc(g, 0u);
+    if constexpr (S::kScaled) rs = make_rsrc(P.scales + (p.e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, span_scale_bytes);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int slot = ch * U + u;
+      const bool valid = slot < ncol;
+      const int col = valid ? c0 + slot : 0;
+      const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
+      raw[u] = load_codes<DT>(rc, p.voff | dead);
+      if constexpr (S::kScaled) {
+        const uint32_t soff = valid ? ((((uint32_t)col) << gshift) + (loc >> P.block_shift)) * (uint32_t)S::kScaleBytes : 0x7fffff00u;
+        sc[u] = ld16(rs, soff | dead);
+      } else {
+        sc[u] = 0u;
+      }
+    }
+  };
+  auto compute_chunk = [&](int ch, const u32x4 (&raw)[U], const uint32_t (&sc)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float d = (float)dot_codes_fixed<DT>(raw[u], gdig) * gunit;
+      if constexpr (S::kScaled) {
+        const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)sc[u]) * P.gscale;
+        acc[ch * U + u] = __builtin_fmaf(d, scale, acc[ch * U + u]);
+      } else {
+        acc[ch * U + u] += d;                                   // min-max codes: a_l multiplies the finished sum
+      }
+    }
+  };
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+
+  LayerCursor lc{0, 0, 0, 0, 0};
+  lc.load(plan, layer_of_tile(plan, t0));
+  Place now = place(lc, t0);
+  u32x4 rawX[U], rawY[U], rawZ[U];
+  uint32_t scX[U], scY[U], scZ[U];
+  load_g(now, 0u);
+  load_chunk(now, 0, 0u, rawZ, scZ);
+  fence();
+  for (int64_t t = t0; t < t1; ++t) {
+    if (now.head != 0) {                                        // first tile of a layer with an unaligned start
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) gs[e] = loc + e >= now.head ? gs[e] : 0.0f;
+    }
+    if constexpr (kMinMax<DT>) {
+      float sum = 0.0f;
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) sum += gs[e];
+      gsum += sum;
+    }
+    gunit = fixed_point_digits<DT>(gs, gdig);
+    fence();
+    // the next tile: its layer, its place, and whether the sums have to be handed over before it
+    const bool more = t + 1 < t1;
+    const uint32_t dead = more ? 0u : 0x80000000u;
+    LayerCursor ln = lc;
+    bool next_layer = false;
+    if (more && ln.behind(plan, t + 1)) {
+      ln.seek(plan, t + 1);
+      next_layer = true;
+    }
+    const Place nxt = place(ln, more ? t + 1 : t);
+    load_g(nxt, dead);                                          // gs is free: the digits are formed
+    fence();
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      if (ch + 1 == NCH) load_chunk(nxt, 0, dead, rawZ, scZ);
+      else if ((ch + 1) % 2 == 1) load_chunk(now, ch + 1, 0u, rawX, scX);
+      else load_chunk(now, ch + 1, 0u, rawY, scY);
+      fence();
+      if (ch == 0) compute_chunk(ch, rawZ, scZ);
+      else if (ch % 2 == 1) compute_chunk(ch, rawX, scX);
+      else compute_chunk(ch, rawY, scY);
+      fence();
+    }
+    if (next_layer) flush((int)blockIdx.x + lc.cur);            // a workgroup never holds a layer without tiles
+    lc = ln;
+    now = nxt;
+  }
+  flush((int)blockIdx.x + lc.cur);
+}
+
 // S = P^T G for up to TWA_MAX_K gradients in ONE pass over P (up to 32 basis vectors per launch; not int4).
 // The gradients are 44 % of the bytes at k = 8, n = 20, so they must not be fetched once per wave:
 // the workgroup loads each tile of G once, coalesced, into a double-buffered LDS tile (the loads of
@@ -764,6 +936,9 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
     if constexpr (DT == TWA_I4 && !LAYERED && KB == 1 && VPL == 1)                                              \
       hipLaunchKernelGGL((project_i4_kernel<U_, NCH_>), dim3(grid), dim3(256), 0, st, P, g, partial, cpw,     \
                          tiles_per_wg);                                                                       \
+    else if constexpr (LAYERED && kDotCodes<DT> && !SQUARES && KB == 1 && VPL == 1 && (NCH_) >= 2)              \
+      hipLaunchKernelGGL((project_layers_dot_kernel<DT, U_, NCH_>), dim3(grid), dim3(256), 0, st, P, g, partial, \
+                         cpw, plan, aux);                                                                     \
     else if constexpr (LAYERED)                                                                               \
       hipLaunchKernelGGL((project_layers_kernel<DT, U_, NCH_, VPL, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, \
                          partial, cpw, plan, aux);                                                            \
@@ -796,7 +971,7 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
     } else {
       switch ((cpw + 3) / 4) {
         case 1:
-          if constexpr (DT == TWA_I4 && !LAYERED && KB == 1 && VPL == 1) TWA_LAUNCH(2, 2);   // (project_i4_kernel's pipeline needs two chunks)
+          if constexpr (kDotCodes<DT> && !SQUARES && KB == 1 && VPL == 1) TWA_LAUNCH(2, 2);   // (the pipelined kernels need two chunks)
           else TWA_LAUNCH(4, 1);
           break;
         case 2: TWA_LAUNCH(4, 2); break;
