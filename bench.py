@@ -44,7 +44,7 @@ STORAGE_NAME = {"f32": "fp32", "bf16": "bf16", "i8": "int8", "i4": "int4", "mm16
 # vector-ALU lane-instructions per stored element of the step kernels (projection-like, expansion-like), from
 # rocprofv3 --pmc SQ_INSTS_VALU (profiles/sq_counters_imagenet_resnet50_int4_int8.txt): the expansion on 4-bit codes
 # is co-limited by the vector ALUs; the projection on them computes in integer dot products and is not
-VALU_INSTR_PER_ELEMENT = {"i8": (2.14, 2.28), "mm8": (2.14, 2.28), "i4": (1.67, 2.64), "mm4": (1.72, 2.53)}
+VALU_INSTR_PER_ELEMENT = {"i8": (2.14, 2.28), "mm8": (2.14, 2.28), "i4": (1.67, 2.64), "mm4": (1.66, 2.53)}
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
