@@ -171,7 +171,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * VPL * EPV;
   constexpr int SLOTS = U * NCH;
-  constexpr bool DOT8 = kDotCodes<DT>;                     // codes of 4 bits and fewer: integer dot products
+  static_assert(!kDotCodes<DT>, "codes of 4 bits and fewer are projected by project_dot_kernel");
   static_assert(kScaleSpan % TILE == 0 || TILE % kScaleSpan == 0, "tiles and scale spans nest");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -266,8 +266,6 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
     // ---- this lane's slice of the gradient(s); the descriptor ends at element D (at the end of
     //      the layer), and the range check is per dword, so elements past that end arrive as 0 --
     float gs[KB][VPL][EPV];
-    uint32_t gdig[DOT8 ? KB : 1][DOT8 ? VPL : 1][4][kFixDigits];     // DOT8: the slice as fixed-point digits,
-    float gunit[DOT8 ? KB : 1][DOT8 ? VPL : 1];                      // and what one unit of it is worth
     float mean_hi[SQUARES ? VPL : 1][EPV], mean_lo[SQUARES ? VPL : 1][EPV];     // SQUARES: this lane's slice of the mean
 #pragma unroll
     for (int c = 0; c < KB; ++c) {
@@ -304,16 +302,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
             for (int e = 0; e < EPV; ++e) gs[c][v][e] = rel + e >= head ? gs[c][v][e] : 0.0f;
           }
         }
-        if constexpr (DOT8) {
-          static_assert(!DOT8 || EPV == 32, "a lane's slice is one 128-bit load of codes");
-          if constexpr (kMinMax<DT>) {                        // the zero point b_l multiplies the layer's sum of g itself
-            float sum = 0.0f;
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) sum += gs[c][v][e];
-            gsum += sum;
-          }
-          gunit[c][v] = fixed_point_digits<DT>(gs[c][v], gdig[c][v]);
-        } else if constexpr (kMinMax<DT>) {
+        if constexpr (kMinMax<DT>) {
           float sum = 0.0f;
 #pragma unroll
           for (int e = 0; e < EPV; ++e) sum += gs[c][v][e];
@@ -350,8 +339,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
                 valid ? ((((pos >> kScaleSpanShift) * (uint32_t)P.n + (uint32_t)col) << gshift) +
                          ((pos & (uint32_t)(kScaleSpan - 1)) >> P.block_shift)) * (uint32_t)S::kScaleBytes
                       : 0x7fffff00u;
-            if constexpr (DOT8) sc[u][v] = as_f32(ld16(rs, soff));      // the binary16 bits: widened when consumed
-            else sc[u][v] = load_scale<DT>(rs, soff, P.gscale);
+            sc[u][v] = load_scale<DT>(rs, soff, P.gscale);
           } else {
             sc[u][v] = 1.0f;
           }
@@ -365,19 +353,6 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
         const int slot = ch * U + u;
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
-          if constexpr (DOT8) {
-#pragma unroll
-            for (int c = 0; c < KB; ++c) {
-              const float d = (float)dot_codes_fixed<DT>(raw[u][v], gdig[c][v]) * gunit[c][v];
-              if constexpr (S::kScaled) {
-                const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)as_u32(sc[u][v])) * P.gscale;
-                acc[slot][c] = __builtin_fmaf(d, scale, acc[slot][c]);
-              } else {
-                acc[slot][c] += d;                            // min-max codes: a_l multiplies the finished sum
-              }
-            }
-            continue;
-          }
           float x[EPV];
           decode<DT>(raw[u][v], x);
           if constexpr (SQUARES) {
@@ -404,21 +379,13 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
     // double buffered: the loads of chunk ch+1 are issued before chunk ch is consumed
     u32x4 rawA[U][VPL], rawB[U][VPL];
     float scA[U][VPL], scB[U][VPL];
-    // (DOT8: what consumes a load is a single XOR, which the scheduler would otherwise put, with its wait, right
-    //  behind the load -- one load in flight per wave.  Nothing may cross the fences.)
-    auto fence = [] { if constexpr (DOT8) __builtin_amdgcn_sched_barrier(0); };
     load_chunk(0, rawA, scA);
-    fence();
 #pragma unroll
     for (int ch = 0; ch < NCH; ch += 2) {
       if (ch + 1 < NCH) load_chunk(ch + 1, rawB, scB);
-      fence();
       compute_chunk(ch, rawA, scA);
-      fence();
       if (ch + 2 < NCH) load_chunk(ch + 2, rawA, scA);
-      fence();
       if (ch + 1 < NCH) compute_chunk(ch + 1, rawB, scB);
-      fence();
     }
   }
 
@@ -458,153 +425,49 @@ __global__ __launch_bounds__(256, 2) void project_layers_kernel(PView P, const f
   project_body<DT, 1, U, NCH, VPL, true, SQUARES>(P, g, 0, 1, partial, cpw, 0, plan, aux);
 }
 
-// The whole-model projection on 4-bit block codes (k = 1): the body above with the integer dot products, and the
-// stream pipelined ACROSS tiles.  With 32 elements per 128-bit load a tile is only 1 KB per basis vector, so the
-// start of a tile -- fetch the slice of g, turn it into digits, fetch the first chunk of codes -- is a large part
-// of the tile's time, and a wave that has nothing in flight meanwhile costs bandwidth (a pure-read kernel with
-// this access pattern falls from 6.3 to 3.9 TB/s when its loads are not kept in flight).  Here the next tile's
-// slice of g is fetched as soon as this tile's digits are formed (its registers are free then), and the next
-// tile's first chunk of codes while this tile's last chunk is consumed.  Sums, reduction and partial-sum layout
-// as in project_body.
-template <int U, int NCH>
-__global__ __launch_bounds__(256, 2) void project_i4_kernel(PView P, const float* __restrict__ g,
-                                                         float* __restrict__ partial, int cpw, int tiles_per_wg) {
-  using S = Store<TWA_I4>;
-  constexpr int EPV = S::kEPV;                                     // 32 codes per lane and basis vector
-  constexpr int TILE = kWave * EPV;                                // = one scale span
-  constexpr int SLOTS = U * NCH;
-  static_assert(TILE == kScaleSpan, "a tile is one span of scales");
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t D = P.D;
-  const int64_t ntiles = (D + TILE - 1) / TILE;
-  const int64_t t0 = (int64_t)blockIdx.x * tiles_per_wg;
-  int64_t t1 = t0 + tiles_per_wg;
-  if (t1 > ntiles) t1 = ntiles;
-  const int c0 = wave * cpw;
-  int ncol = P.n - c0;
-  ncol = ncol < 0 ? 0 : (ncol > cpw ? cpw : ncol);
-  const uint32_t col_bytes = stored_bytes<TWA_I4>(D);
-  const int64_t ld_bytes = P.ld >> 1;
-  const int gshift = kScaleSpanShift - P.block_shift;              // log2(scales per span and vector)
-  const uint32_t span_scale_bytes = ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes;
-  const rsrc_t rg = make_rsrc(g, (uint32_t)(D * 4));               // elements past D arrive as 0
-  const uint32_t loc = (uint32_t)lane * EPV;                       // this lane's first element inside a tile
-
-  float acc[SLOTS];
-#pragma unroll
-  for (int sl = 0; sl < SLOTS; ++sl) acc[sl] = 0.0f;
-
-  float gs[EPV];                                                   // slice of g of the tile whose digits are formed next
-  uint32_t gdig[4][kFixDigits];
-  float gunit = 0.0f;
-  // (`dead` = 0x80000000 puts every offset of a fetch outside its descriptor: a prefetch past the workgroup's last
-  //  tile is issued like any other, returns zeros and moves no memory -- no branch in the pipeline)
-  auto load_g = [&](int64_t t, uint32_t dead) {
-    const uint32_t elem = (uint32_t)(t * TILE) + loc;
-#pragma unroll
-    for (int q = 0; q < EPV / 4; ++q) {
-      const u32x4 x = ld128(rg, ((elem + 4u * q) * 4u) | dead);    // shared by the 4 waves: keep it cacheable
-#pragma unroll
-      for (int r = 0; r < 4; ++r) gs[4 * q + r] = as_f32(x[r]);
-    }
-  };
-  // chunk ch of tile t: codes and binary16 scale bits of column slots [ch*U, (ch+1)*U)
-  auto load_chunk = [&](int64_t t, int ch, uint32_t dead, u32x4 (&raw)[U], uint32_t (&sc)[U]) {
-    const uint32_t voff = (uint32_t)(((uint64_t)t * TILE + loc) >> 1) | dead;
-    const rsrc_t rs = make_rsrc(P.scales + t * (int64_t)span_scale_bytes, span_scale_bytes);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int slot = ch * U + u;
-      const bool valid = slot < ncol;
-      const int col = valid ? c0 + slot : 0;
-      const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
-      raw[u] = load_codes<TWA_I4>(rc, voff);
-      // [vector][block in span]; an unused column slot reads far outside the range and gets 0
-      const uint32_t soff = valid ? ((((uint32_t)col) << gshift) + (loc >> P.block_shift)) * (uint32_t)S::kScaleBytes : 0x7fffff00u;
-      sc[u] = ld16(rs, soff | dead);
-    }
-  };
-  auto compute_chunk = [&](int ch, const u32x4 (&raw)[U], const uint32_t (&sc)[U]) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const float d = (float)dot_codes_fixed<TWA_I4>(raw[u], gdig) * gunit;
-      const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)sc[u]) * P.gscale;
-      acc[ch * U + u] = __builtin_fmaf(d, scale, acc[ch * U + u]);
-    }
-  };
-  // nothing may cross a fence: what consumes a load is a single XOR, which the scheduler would otherwise put,
-  // with its wait, right behind the load
-  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-  // Three code buffers: chunk 0 of a tile always sits in Z, chunks 1, 3, .. in X, chunks 2, 4, .. in Y, so that every
-  // tile runs the same code (two buffers would change roles from tile to tile when NCH is odd, and the second copy
-  // of the loop body costs the kernel its registers).  Z is free once chunk 0 is consumed: the next tile's chunk 0
-  // is fetched into it while this tile's last chunk is consumed.
-  static_assert(NCH >= 2, "chunk 0 of the next tile is fetched while another chunk is consumed");
-  u32x4 rawX[U], rawY[U], rawZ[U];
-  uint32_t scX[U], scY[U], scZ[U];
-  load_g(t0, 0u);                                                   // (every workgroup of the grid owns a tile)
-  load_chunk(t0, 0, 0u, rawZ, scZ);
-  fence();
-  for (int64_t t = t0; t < t1; ++t) {
-    gunit = fixed_point_digits<TWA_I4>(gs, gdig);
-    fence();
-    const uint32_t dead = t + 1 < t1 ? 0u : 0x80000000u;
-    load_g(t + 1, dead);                                            // gs is free: the digits are formed
-    fence();
-#pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) {
-      if (ch + 1 == NCH) load_chunk(t + 1, 0, dead, rawZ, scZ);
-      else if ((ch + 1) % 2 == 1) load_chunk(t, ch + 1, 0u, rawX, scX);
-      else load_chunk(t, ch + 1, 0u, rawY, scY);
-      fence();
-      if (ch == 0) compute_chunk(ch, rawZ, scZ);
-      else if (ch % 2 == 1) compute_chunk(ch, rawX, scX);
-      else compute_chunk(ch, rawY, scY);
-      fence();
-    }
-  }
-
-#pragma unroll
-  for (int sl = 0; sl < SLOTS; ++sl) {
-    const float tot = wave_sum_to_last_lane(acc[sl]);
-    if (lane == kSumLane && sl < ncol) partial[(int64_t)blockIdx.x * P.n + c0 + sl] = tot;
-  }
-}
-
-// The layer-wise projection on codes that enter the dot products (4-bit block codes; min-max codes of 4 bits and
-// fewer), pipelined across tiles like project_i4_kernel.  The tiles follow the layer plan as in project_body (a tile
-// belongs to one layer; the gradient is read through a descriptor that ends with the layer; the elements in front
-// of an unaligned layer start are zeroed; a lane wholly outside the layer reads nothing), and the place of the NEXT
-// tile is worked out one tile ahead, on a copy of the layer cursor, so that its slice of g and its first chunk of
-// codes can be fetched while this tile is consumed.  When the next tile belongs to another layer the running sums
-// are reduced and written to partial slot (workgroup + layer) after this tile, as in project_body.
-template <int DT, int U, int NCH>
-__global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, const float* __restrict__ g,
-                                                                    float* __restrict__ partial, int cpw,
-                                                                    LayerPlan plan, float* __restrict__ aux) {
+// The projection on codes that enter the dot products (k = 1; 4-bit block codes, whole model or layer-wise; min-max
+// codes of 4 bits and fewer, layer-wise), with the stream pipelined ACROSS tiles.  With 32 elements per lane and
+// load a tile is at most 1 KB per basis vector, so the start of a tile -- fetch the slice of g, turn it into
+// digits, fetch the first chunk of codes -- is a large part of the tile's time, and a wave that has nothing in
+// flight meanwhile costs bandwidth (a pure-read kernel with this access pattern falls from 6.3 to 3.9 TB/s when
+// its loads are not kept in flight).  Here the next tile's slice of g is fetched as soon as this tile's digits are
+// formed (its registers are free then), and the next tile's first chunk of codes while this tile's last chunk is
+// consumed.  Sums, reduction and partial-sum layout as in project_body.
+// LAYERED: the tiles follow the layer plan as in project_body (a tile belongs to one layer; the gradient is read
+// through a descriptor that ends with the layer; the elements in front of an unaligned layer start are zeroed; a
+// lane wholly outside the layer reads nothing), and the place of the NEXT tile is worked out one tile ahead, on a
+// copy of the layer cursor.  When the next tile belongs to another layer the running sums are reduced and written
+// to partial slot (workgroup + layer) after this tile.
+template <int DT, int U, int NCH, bool LAYERED>
+__global__ __launch_bounds__(256, 2) void project_dot_kernel(PView P, const float* __restrict__ g,
+                                                             float* __restrict__ partial, int cpw, int tiles_per_wg,
+                                                             LayerPlan plan, float* __restrict__ aux) {
   using S = Store<DT>;
   constexpr int EPV = S::kEPV;
   constexpr int TILE = kWave * EPV;
   constexpr int SLOTS = U * NCH;
   static_assert(kDotCodes<DT> && EPV == 32 && TILE == kLayerAlign && TILE == kScaleSpan, "32 codes per lane, one span per tile");
   static_assert(NCH >= 2, "chunk 0 of the next tile is fetched while another chunk is consumed");
+  static_assert(LAYERED || !kMinMax<DT>, "the min-max formats exist layer-wise only");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t D = P.D;
-  if (!plan_header_ok(plan.off, plan.L, D)) return;           // not this call's plan: the reduction kernel answers with NaN
-  const int64_t ntiles = (int64_t)plan.first[plan.L];
-  const int tiles_per_wg = (int)((ntiles + gridDim.x - 1) / gridDim.x);
+  int64_t ntiles = (D + TILE - 1) / TILE;
+  if constexpr (LAYERED) {
+    if (!plan_header_ok(plan.off, plan.L, D)) return;         // not this call's plan: the reduction kernel answers with NaN
+    ntiles = (int64_t)plan.first[plan.L];                     // known on the device only: the split is made here
+    tiles_per_wg = (int)((ntiles + gridDim.x - 1) / gridDim.x);
+  }
   const int64_t t0 = (int64_t)blockIdx.x * tiles_per_wg;
   int64_t t1 = t0 + tiles_per_wg;
   if (t1 > ntiles) t1 = ntiles;
-  if (t0 >= t1) return;                                        // a workgroup without tiles owns no partial slot
+  if (t0 >= t1) return;              // layer-wise: a workgroup without tiles owns no partial slot (whole model: none exists)
   const int c0 = wave * cpw;
   int ncol = P.n - c0;
   ncol = ncol < 0 ? 0 : (ncol > cpw ? cpw : ncol);
   const uint32_t col_bytes = stored_bytes<DT>(D);
   const int64_t ld_bytes = (P.ld * S::kBitsPerElem) >> 3;
-  const int gshift = kScaleSpanShift - P.block_shift;
+  const int gshift = kScaleSpanShift - P.block_shift;          // log2(scales per span and vector)
   const uint32_t span_scale_bytes = S::kScaled ? ((uint32_t)P.n << gshift) * (uint32_t)S::kScaleBytes : 0u;
   const uint32_t loc = (uint32_t)lane * EPV;                   // this lane's first element inside a tile
 
@@ -616,16 +479,24 @@ __global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, con
   };
   auto place = [&](const LayerCursor& c, int64_t t) {
     Place p;
-    const int64_t hi = c.hi < D ? c.hi : D;
-    const int64_t e0 = c.tile_start(t, TILE);
-    // the same for every lane; said so, or the descriptors built from these numbers are taken for lane-dependent
-    // and every load through them is wrapped in a loop over the distinct values
-    const auto uni = [](uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); };
-    p.e0 = (int64_t)(((uint64_t)uni((uint32_t)((uint64_t)e0 >> 32)) << 32) | uni((uint32_t)e0));
-    p.g_bytes = uni((uint32_t)(hi * 4));
-    p.head = uni(c.lo > e0 ? (uint32_t)(c.lo - e0 < TILE ? c.lo - e0 : TILE) : 0u);
-    p.tail = uni(hi - e0 < TILE ? (uint32_t)(hi > e0 ? hi - e0 : 0) : (uint32_t)TILE);
-    p.voff = (loc + EPV <= p.head || loc >= p.tail) ? col_bytes : (uint32_t)((((uint64_t)p.e0 + loc) * S::kBitsPerElem) >> 3);
+    if constexpr (LAYERED) {
+      const int64_t hi = c.hi < D ? c.hi : D;
+      const int64_t e0 = c.tile_start(t, TILE);
+      // the same for every lane; said so, or the descriptors built from these numbers are taken for lane-dependent
+      // and every load through them is wrapped in a loop over the distinct values
+      const auto uni = [](uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); };
+      p.e0 = (int64_t)(((uint64_t)uni((uint32_t)((uint64_t)e0 >> 32)) << 32) | uni((uint32_t)e0));
+      p.g_bytes = uni((uint32_t)(hi * 4));
+      p.head = uni(c.lo > e0 ? (uint32_t)(c.lo - e0 < TILE ? c.lo - e0 : TILE) : 0u);
+      p.tail = uni(hi - e0 < TILE ? (uint32_t)(hi > e0 ? hi - e0 : 0) : (uint32_t)TILE);
+      p.voff = (loc + EPV <= p.head || loc >= p.tail) ? col_bytes : (uint32_t)((((uint64_t)p.e0 + loc) * S::kBitsPerElem) >> 3);
+    } else {
+      p.e0 = t * TILE;
+      p.g_bytes = (uint32_t)(D * 4);                           // elements past D arrive as 0
+      p.head = 0u;
+      p.tail = (uint32_t)TILE;
+      p.voff = (uint32_t)((((uint64_t)p.e0 + loc) * S::kBitsPerElem) >> 3);
+    }
     return p;
   };
 
@@ -633,6 +504,7 @@ __global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, con
 #pragma unroll
   for (int sl = 0; sl < SLOTS; ++sl) acc[sl] = 0.0f;
   float gsum = 0.0f;                                           // min-max formats: the layer's sum of the gradient itself
+  // one reduction over the wave's lanes, then the partial sums of row `slot_row`
   auto flush = [&](int slot_row) {
     if constexpr (kMinMax<DT>) {
       const float tot = wave_sum_to_last_lane(gsum);
@@ -647,20 +519,22 @@ __global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, con
     }
   };
 
-  float gs[EPV];
+  float gs[EPV];                                               // slice of g of the tile whose digits are formed next
   uint32_t gdig[4][kFixDigits];
   float gunit = 0.0f;
-  // (`dead` = 0x80000000 puts every offset of a fetch outside its descriptor: zeros, no memory traffic, no branch)
+  // (`dead` = 0x80000000 puts every offset of a fetch outside its descriptor: a prefetch past the workgroup's last
+  //  tile is issued like any other, returns zeros and moves no memory -- no branch in the pipeline)
   auto load_g = [&](const Place& p, uint32_t dead) {
     const rsrc_t rg = make_rsrc(g, p.g_bytes);
     const uint32_t elem = (uint32_t)p.e0 + loc;
 #pragma unroll
     for (int q = 0; q < EPV / 4; ++q) {
-      const u32x4 x = ld128(rg, ((elem + 4u * q) * 4u) | dead);
+      const u32x4 x = ld128(rg, ((elem + 4u * q) * 4u) | dead);      // shared by the 4 waves: keep it cacheable
 #pragma unroll
       for (int r = 0; r < 4; ++r) gs[4 * q + r] = as_f32(x[r]);
     }
   };
+  // chunk ch of a tile: codes (and binary16 scale bits) of column slots [ch*U, (ch+1)*U)
   auto load_chunk = [&](const Place& p, int ch, uint32_t dead, u32x4 (&raw)[U], uint32_t (&sc)[U]) {
     rsrc_t rs = make_rsrc(g, 0u);
     if constexpr (S::kScaled) rs = make_rsrc(P.scales + (p.e0 >> kScaleSpanShift) * (int64_t)span_scale_bytes, span_scale_bytes);
@@ -672,6 +546,7 @@ __global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, con
       const rsrc_t rc = make_rsrc(P.data + (int64_t)col * ld_bytes, valid ? col_bytes : 0u);
       raw[u] = load_codes<DT>(rc, p.voff | dead);
       if constexpr (S::kScaled) {
+        // [vector][block in span]; an unused column slot reads far outside the range and gets 0
         const uint32_t soff = valid ? ((((uint32_t)col) << gshift) + (loc >> P.block_shift)) * (uint32_t)S::kScaleBytes : 0x7fffff00u;
         sc[u] = ld16(rs, soff | dead);
       } else {
@@ -691,20 +566,28 @@ __global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, con
       }
     }
   };
+  // nothing may cross a fence: what consumes a load is a single XOR or mask, which the scheduler would otherwise
+  // put, with its wait, right behind the load
   auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
 
   LayerCursor lc{0, 0, 0, 0, 0};
-  lc.load(plan, layer_of_tile(plan, t0));
+  if constexpr (LAYERED) lc.load(plan, layer_of_tile(plan, t0));
   Place now = place(lc, t0);
+  // Three code buffers: chunk 0 of a tile always sits in Z, chunks 1, 3, .. in X, chunks 2, 4, .. in Y, so that every
+  // tile runs the same code (two buffers would change roles from tile to tile when NCH is odd, and the second copy
+  // of the loop body costs the kernel its registers).  Z is free once chunk 0 is consumed: the next tile's chunk 0
+  // is fetched into it while this tile's last chunk is consumed.
   u32x4 rawX[U], rawY[U], rawZ[U];
   uint32_t scX[U], scY[U], scZ[U];
   load_g(now, 0u);
   load_chunk(now, 0, 0u, rawZ, scZ);
   fence();
   for (int64_t t = t0; t < t1; ++t) {
-    if (now.head != 0) {                                        // first tile of a layer with an unaligned start
+    if constexpr (LAYERED) {
+      if (now.head != 0) {                                      // first tile of a layer with an unaligned start
 #pragma unroll
-      for (int e = 0; e < EPV; ++e) gs[e] = loc + e >= now.head ? gs[e] : 0.0f;
+        for (int e = 0; e < EPV; ++e) gs[e] = loc + e >= now.head ? gs[e] : 0.0f;
+      }
     }
     if constexpr (kMinMax<DT>) {
       float sum = 0.0f;
@@ -719,9 +602,11 @@ __global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, con
     const uint32_t dead = more ? 0u : 0x80000000u;
     LayerCursor ln = lc;
     bool next_layer = false;
-    if (more && ln.behind(plan, t + 1)) {
-      ln.seek(plan, t + 1);
-      next_layer = true;
+    if constexpr (LAYERED) {
+      if (more && ln.behind(plan, t + 1)) {
+        ln.seek(plan, t + 1);
+        next_layer = true;
+      }
     }
     const Place nxt = place(ln, more ? t + 1 : t);
     load_g(nxt, dead);                                          // gs is free: the digits are formed
@@ -737,11 +622,13 @@ __global__ __launch_bounds__(256, 2) void project_layers_dot_kernel(PView P, con
       else compute_chunk(ch, rawY, scY);
       fence();
     }
-    if (next_layer) flush((int)blockIdx.x + lc.cur);            // a workgroup never holds a layer without tiles
+    if constexpr (LAYERED) {
+      if (next_layer) flush((int)blockIdx.x + lc.cur);          // a workgroup never holds a layer without tiles
+    }
     lc = ln;
     now = nxt;
   }
-  flush((int)blockIdx.x + lc.cur);
+  flush(LAYERED ? (int)blockIdx.x + lc.cur : (int)blockIdx.x);
 }
 
 // S = P^T G for up to TWA_MAX_K gradients in ONE pass over P (up to 32 basis vectors per launch; not int4).
@@ -933,12 +820,9 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
 #define TWA_LAUNCH(U_, NCH_)                                                                                  \
   do {                                                                                                        \
-    if constexpr (DT == TWA_I4 && !LAYERED && KB == 1 && VPL == 1)                                              \
-      hipLaunchKernelGGL((project_i4_kernel<U_, NCH_>), dim3(grid), dim3(256), 0, st, P, g, partial, cpw,     \
-                         tiles_per_wg);                                                                       \
-    else if constexpr (LAYERED && kDotCodes<DT> && !SQUARES && KB == 1 && VPL == 1 && (NCH_) >= 2)              \
-      hipLaunchKernelGGL((project_layers_dot_kernel<DT, U_, NCH_>), dim3(grid), dim3(256), 0, st, P, g, partial, \
-                         cpw, plan, aux);                                                                     \
+    if constexpr (kDotCodes<DT> && !SQUARES && KB == 1 && VPL == 1 && (NCH_) >= 2)                              \
+      hipLaunchKernelGGL((project_dot_kernel<DT, U_, NCH_, LAYERED>), dim3(grid), dim3(256), 0, st, P, g, partial, \
+                         cpw, tiles_per_wg, plan, aux);                                                       \
     else if constexpr (LAYERED)                                                                               \
       hipLaunchKernelGGL((project_layers_kernel<DT, U_, NCH_, VPL, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, \
                          partial, cpw, plan, aux);                                                            \
