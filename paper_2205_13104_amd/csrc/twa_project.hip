@@ -398,9 +398,7 @@ __device__ __forceinline__ void project_body(PView P, const float* __restrict__ 
 
 // The kernels around the body differ in their register budget only, which decides how the compiler
 // schedules the loads (measured at D = 25.6 M over n = 10 .. 128 and all storage types):
-//   * whole model, many basis vectors per wave (5 or more chunks, n > 64): the compiler's default.  Told to
-//     fit two waves per SIMD it schedules the int4 variants for far fewer registers than it may use
-//     and they lose 40 %;
+//   * whole model, many basis vectors per wave (5 or more chunks, n > 64): the compiler's default;
 //   * whole model, few basis vectors per wave: exactly two waves per SIMD.  By default several of these
 //     variants use the accumulation registers as well and run at ONE wave per SIMD (int8, n = 10: 0.129 ms
 //     instead of 0.078 ms);
