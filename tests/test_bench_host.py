@@ -43,6 +43,13 @@ def test_committed_traffic_figures_match_the_algorithmic_bytes():
         # projection: P and g read, n floats written; expansion: P and w read, w written
         assert abs(proj / (p + 4 * D + 4 * n) - 1) < 5e-3, (tag, proj)
         assert abs(expd / (p + 8 * D) - 1) < 5e-3, (tag, expd)
+    # layer-wise (161 parameter tensors): the same streams; the 4-bit min-max codes carry no block scales
+    for tag, p in (("layerwise_imagenet_resnet50_int8", _p_bytes(D, n, 8, 128, 4)), ("layerwise_imagenet_resnet50_minmax4", _p_bytes(D, n, 4, 64, 0))):
+        proj = b.read_traffic(tag, "twa_beta_step")
+        expd = b.read_traffic(tag, "twa_weights_from_beta")
+        assert proj is not None and expd is not None, tag
+        assert abs(proj / (p + 4 * D) - 1) < 5e-3, (tag, proj)          # (+1.3 % of tiles on layer boundaries read nothing twice)
+        assert abs(expd / (p + 8 * D) - 1) < 5e-3, (tag, expd)
     # the batched projection of the fine-tuning shape: bf16 P read once, k = 8 gradients read
     Dv, nv, k = 86_567_656, 20, 8
     t = b.read_traffic("batched_vit_b16_finetune_bf16", "twa_project")
