@@ -436,8 +436,10 @@ __global__ __launch_bounds__(256, 2) void project_layers_kernel(PView P, const f
 // lane wholly outside the layer reads nothing), and the place of the NEXT tile is worked out one tile ahead, on a
 // copy of the layer cursor.  When the next tile belongs to another layer the running sums are reduced and written
 // to partial slot (workgroup + layer) after this tile.
-template <int DT, int U, int NCH, bool LAYERED>
-__global__ __launch_bounds__(256, 2) void project_dot_kernel(PView P, const float* __restrict__ g,
+// KB = 2 (whole model only): two gradients, g and g + ldg, share one pass over the codes; their sums go to partial
+// rows 2 * workgroup and 2 * workgroup + 1 (the layout the reduction of a batch expects).
+template <int DT, int U, int NCH, bool LAYERED, int KB = 1>
+__global__ __launch_bounds__(256, 2) void project_dot_kernel(PView P, const float* __restrict__ g, int64_t ldg,
                                                              float* __restrict__ partial, int cpw, int tiles_per_wg,
                                                              LayerPlan plan, float* __restrict__ aux) {
   using S = Store<DT>;
@@ -447,6 +449,7 @@ __global__ __launch_bounds__(256, 2) void project_dot_kernel(PView P, const floa
   static_assert(kDotCodes<DT> && EPV == 32 && TILE == kLayerAlign && TILE == kScaleSpan, "32 codes per lane, one span per tile");
   static_assert(NCH >= 2, "chunk 0 of the next tile is fetched while another chunk is consumed");
   static_assert(LAYERED || !kMinMax<DT>, "the min-max formats exist layer-wise only");
+  static_assert(KB == 1 || (KB == 2 && !LAYERED), "gradients in pairs: whole model only");
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t D = P.D;
@@ -498,9 +501,11 @@ __global__ __launch_bounds__(256, 2) void project_dot_kernel(PView P, const floa
     return p;
   };
 
-  float acc[SLOTS];
+  float acc[SLOTS][KB];
 #pragma unroll
-  for (int sl = 0; sl < SLOTS; ++sl) acc[sl] = 0.0f;
+  for (int sl = 0; sl < SLOTS; ++sl)
+#pragma unroll
+    for (int c = 0; c < KB; ++c) acc[sl][c] = 0.0f;
   float gsum = 0.0f;                                           // min-max formats: the layer's sum of the gradient itself
   // one reduction over the wave's lanes, then the partial sums of row `slot_row`
   auto flush = [&](int slot_row) {
@@ -511,25 +516,31 @@ __global__ __launch_bounds__(256, 2) void project_dot_kernel(PView P, const floa
     }
 #pragma unroll
     for (int sl = 0; sl < SLOTS; ++sl) {
-      const float tot = wave_sum_to_last_lane(acc[sl]);
-      if (lane == kSumLane && sl < ncol) partial[(int64_t)slot_row * P.n + c0 + sl] = tot;
-      acc[sl] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < KB; ++c) {
+        const float tot = wave_sum_to_last_lane(acc[sl][c]);
+        if (lane == kSumLane && sl < ncol) partial[((int64_t)slot_row * KB + c) * P.n + c0 + sl] = tot;
+        acc[sl][c] = 0.0f;
+      }
     }
   };
 
-  float gs[EPV];                                               // slice of g of the tile whose digits are formed next
-  uint32_t gdig[4][kFixDigits];
-  float gunit = 0.0f;
+  float gs[KB][EPV];                                           // slice of g of the tile whose digits are formed next
+  uint32_t gdig[KB][4][kFixDigits];
+  float gunit[KB];
   // (`dead` = 0x80000000 puts every offset of a fetch outside its descriptor: a prefetch past the workgroup's last
   //  tile is issued like any other, returns zeros and moves no memory -- no branch in the pipeline)
   auto load_g = [&](const Place& p, uint32_t dead) {
-    const rsrc_t rg = make_rsrc(g, p.g_bytes);
     const uint32_t elem = (uint32_t)p.e0 + loc;
 #pragma unroll
-    for (int q = 0; q < EPV / 4; ++q) {
-      const u32x4 x = ld128(rg, ((elem + 4u * q) * 4u) | dead);      // shared by the 4 waves: keep it cacheable
+    for (int c = 0; c < KB; ++c) {
+      const rsrc_t rg = make_rsrc(g + (int64_t)c * ldg, p.g_bytes);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) gs[4 * q + r] = as_f32(x[r]);
+      for (int q = 0; q < EPV / 4; ++q) {
+        const u32x4 x = ld128(rg, ((elem + 4u * q) * 4u) | dead);    // shared by the 4 waves: keep it cacheable
+#pragma unroll
+        for (int r = 0; r < 4; ++r) gs[c][4 * q + r] = as_f32(x[r]);
+      }
     }
   };
   // chunk ch of a tile: codes (and binary16 scale bits) of column slots [ch*U, (ch+1)*U)
@@ -555,12 +566,15 @@ __global__ __launch_bounds__(256, 2) void project_dot_kernel(PView P, const floa
   auto compute_chunk = [&](int ch, const u32x4 (&raw)[U], const uint32_t (&sc)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float d = (float)dot_codes_fixed<DT>(raw[u], gdig) * gunit;
-      if constexpr (S::kScaled) {
-        const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)sc[u]) * P.gscale;
-        acc[ch * U + u] = __builtin_fmaf(d, scale, acc[ch * U + u]);
-      } else {
-        acc[ch * U + u] += d;                                   // min-max codes: a_l multiplies the finished sum
+#pragma unroll
+      for (int c = 0; c < KB; ++c) {
+        const float d = (float)dot_codes_fixed<DT>(raw[u], gdig[c]) * gunit[c];
+        if constexpr (S::kScaled) {
+          const float scale = (float)__builtin_bit_cast(_Float16, (uint16_t)sc[u]) * P.gscale;
+          acc[ch * U + u][c] = __builtin_fmaf(d, scale, acc[ch * U + u][c]);
+        } else {
+          acc[ch * U + u][c] += d;                              // min-max codes: a_l multiplies the finished sum
+        }
       }
     }
   };
@@ -584,16 +598,17 @@ __global__ __launch_bounds__(256, 2) void project_dot_kernel(PView P, const floa
     if constexpr (LAYERED) {
       if (now.head != 0) {                                      // first tile of a layer with an unaligned start
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) gs[e] = loc + e >= now.head ? gs[e] : 0.0f;
+        for (int e = 0; e < EPV; ++e) gs[0][e] = loc + e >= now.head ? gs[0][e] : 0.0f;
       }
     }
     if constexpr (kMinMax<DT>) {
       float sum = 0.0f;
 #pragma unroll
-      for (int e = 0; e < EPV; ++e) sum += gs[e];
+      for (int e = 0; e < EPV; ++e) sum += gs[0][e];
       gsum += sum;
     }
-    gunit = fixed_point_digits<DT>(gs, gdig);
+#pragma unroll
+    for (int c = 0; c < KB; ++c) gunit[c] = fixed_point_digits<DT>(gs[c], gdig[c]);
     fence();
     // the next tile: its layer, its place, and whether the sums have to be handed over before it
     const bool more = t + 1 < t1;
@@ -818,9 +833,9 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
   // chunks of 4 column slots; 25 columns per wave (n = 97..100) divide exactly into 5 chunks of 5
 #define TWA_LAUNCH(U_, NCH_)                                                                                  \
   do {                                                                                                        \
-    if constexpr (kDotCodes<DT> && !SQUARES && KB == 1 && VPL == 1 && (NCH_) >= 2)                              \
-      hipLaunchKernelGGL((project_dot_kernel<DT, U_, NCH_, LAYERED>), dim3(grid), dim3(256), 0, st, P, g, partial, \
-                         cpw, tiles_per_wg, plan, aux);                                                       \
+    if constexpr (kDotCodes<DT> && !SQUARES && (KB == 1 || (KB == 2 && !LAYERED)) && VPL == 1 && (NCH_) >= 2)   \
+      hipLaunchKernelGGL((project_dot_kernel<DT, U_, NCH_, LAYERED, KB>), dim3(grid), dim3(256), 0, st, P, g,   \
+                         ldg, partial, cpw, tiles_per_wg, plan, aux);                                         \
     else if constexpr (LAYERED)                                                                               \
       hipLaunchKernelGGL((project_layers_kernel<DT, U_, NCH_, VPL, SQUARES>), dim3(grid), dim3(256), 0, st, P, g, \
                          partial, cpw, plan, aux);                                                            \
@@ -849,11 +864,12 @@ static int launch_project_dt(const PView& P, const float* g, int64_t ldg, int kv
     }
   } else {
     if (cpw == 25) {
-      TWA_LAUNCH(5, 5);
+      if constexpr (kDotCodes<DT> && KB == 2) TWA_LAUNCH(4, 7);      // (chunks of 5 do not fit the registers with two gradients)
+      else TWA_LAUNCH(5, 5);
     } else {
       switch ((cpw + 3) / 4) {
         case 1:
-          if constexpr (kDotCodes<DT> && !SQUARES && KB == 1 && VPL == 1) TWA_LAUNCH(2, 2);   // (the pipelined kernels need two chunks)
+          if constexpr (kDotCodes<DT> && !SQUARES && VPL == 1) TWA_LAUNCH(2, 2);   // (the pipelined kernel needs two chunks)
           else TWA_LAUNCH(4, 1);
           break;
         case 2: TWA_LAUNCH(4, 2); break;
@@ -998,8 +1014,8 @@ int launch_project_layers(const PView& P, int dtype, const float* g, const void*
 // k > 1 gradients: one pass over P serves all k gradients (project_batched_kernel).  A launch takes up to 32
 // basis vectors (4 waves x 8 column slots, k running sums each); a wider matrix is served in groups of 32 vectors,
 // one launch each -- P is still read once in total, only the gradients are read once per group (n = 100, k = 8:
-// 2.6 GB + 4 x 0.8 GB instead of the 8 x 2.7 GB of one launch per gradient).  The 4-bit codes keep the
-// one-launch-per-gradient path: their 32-element lane vectors leave no registers for k gradient slices.
+// 2.6 GB + 4 x 0.8 GB instead of the 8 x 2.7 GB of one launch per gradient).  The 4-bit codes are projected two
+// gradients per pass (project_dot_kernel with KB = 2).
 template <int DT>
 static int launch_project_batched_dt(const PView& P, const float* g, int64_t ldg, int k, float* s, float* partial,
                                      int max_grid, hipStream_t st) {
@@ -1026,9 +1042,25 @@ static int launch_project_batched_dt(const PView& P, const float* g, int64_t ldg
     hipLaunchKernelGGL(project_reduce_kernel, dim3(P.n * k), dim3(kWave), 0, st, partial, grid, P.n * k, s);
     return hip_check(hipGetLastError());
   }
-  for (int c = 0; c < k; ++c) {
-    int rc = launch_project(P, DT, g + (int64_t)c * ldg, s + (int64_t)c * P.n, partial, max_grid, st);
-    if (rc != TWA_OK) return rc;
+  // the 4-bit codes: two gradients share a pass over P (their fixed-point digits take 50 registers together, which is
+  // what the kernel has); an odd last one goes alone
+  if constexpr (DT == TWA_I4) {
+    const bool pairs = (P.n + 3) / 4 <= 28;       // (more than 28 basis vectors per wave: the pair kernel would spill)
+    for (int c = 0; !pairs && c < k; ++c) {
+      int rc = launch_project(P, DT, g + (int64_t)c * ldg, s + (int64_t)c * P.n, partial, max_grid, st);
+      if (rc != TWA_OK) return rc;
+    }
+    if (!pairs) return TWA_OK;
+    for (int c = 0; c + 1 < k; c += 2) {
+      int grid = 0;
+      int rc = launch_project_dt<TWA_I4, 2, 1>(P, g + (int64_t)c * ldg, ldg, 2, partial, max_grid, &grid, st);
+      if (rc != TWA_OK) return rc;
+      hipLaunchKernelGGL(project_reduce_kernel, dim3(P.n * 2), dim3(kWave), 0, st, partial, grid, P.n * 2,
+                         s + (int64_t)c * P.n);
+      rc = hip_check(hipGetLastError());
+      if (rc != TWA_OK) return rc;
+    }
+    if (k & 1) return launch_project(P, DT, g + (int64_t)(k - 1) * ldg, s + (int64_t)(k - 1) * P.n, partial, max_grid, st);
   }
   return TWA_OK;
 }

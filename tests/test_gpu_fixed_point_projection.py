@@ -98,13 +98,16 @@ def test_a_non_finite_gradient_element_poisons_every_coefficient(bad):
     assert torch.isfinite(twa.project(pm, g)).all()
 
 
-def test_batched_and_single_int4_projections_agree_bit_for_bit():
-    D, n, k = 90001, 37, 3
+@pytest.mark.parametrize("n,k", [(37, 3), (100, 8), (120, 2), (5, 7)])
+def test_batched_and_single_int4_projections_agree_bit_for_bit(n, k):
+    """A batch is projected two gradients per pass over the codes (an odd last one alone; one per pass beyond 112 basis
+    vectors): the same sums in the same order as one call per gradient."""
+    D = 90001
     pm = twa.quantize(random_basis_like(D, n, seed=6), D, twa.I4)
     G = torch.randn((k, D + 3), device="cuda") * 1e-2
     S = twa.project(pm, G)
     for c in range(k):
-        assert torch.equal(S[c], twa.project(pm, G[c, :D].contiguous()))
+        assert torch.equal(S[c], twa.project(pm, G[c, :D].contiguous())), c
 
 
 @pytest.mark.parametrize("kind", ["i4", "mm4", "mm3", "mm2", "mm1"])

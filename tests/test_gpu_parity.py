@@ -119,7 +119,8 @@ def test_project_ignores_padding_garbage():
 
 @pytest.mark.parametrize("dtype,n,k", [(twa.BF16, 20, 8), (twa.F32, 10, 3), (twa.I8, 32, 8), (twa.I4, 12, 2),
                                        (twa.BF16, 40, 4), (twa.I8, 100, 8), (twa.F32, 128, 3), (twa.BF16, 33, 8),
-                                       (twa.I8, 65, 2), (twa.F32, 97, 8), (twa.I4, 100, 3)])
+                                       (twa.I8, 65, 2), (twa.F32, 97, 8), (twa.I4, 100, 3), (twa.I4, 100, 8), (twa.I4, 128, 4),
+                                       (twa.I4, 61, 5), (twa.I4, 3, 2)])
 def test_project_batched_matches_oracle(dtype, n, k):
     D = 150001
     say("project_batched", NAMES[dtype], D, n, k)
